@@ -1,0 +1,186 @@
+/*
+ * okt.h - C ABI of the Ok-Topk one-GPU hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the per-iteration
+ * gradient sparsification of Ok-Topk SGD and the local sparse reduction a
+ * worker performs on the pieces it receives for its own region of the index
+ * space (Li & Hoefler, "Near-Optimal Sparse Allreduce for Distributed Deep
+ * Learning", PPoPP'22; Algorithm 1 "O(k) sparse allreduce", Algorithm 2
+ * "Ok-Topk SGD").
+ *
+ * Conventions common to every call
+ *   - Pointers named d_* are DEVICE pointers owned by the caller.  The library
+ *     allocates and frees nothing, ever; scratch memory comes in through the
+ *     d_ws / ws_bytes pair (size it with okt_workspace_bytes; 256-byte aligned;
+ *     its contents on entry do not matter and are garbage on exit).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every call only enqueues work on that stream and returns; no call
+ *     synchronises with the host.  Scalar results (threshold, counts) are
+ *     written to device memory so that the next call consumes them without a
+ *     host round trip.  Two calls that share one workspace must be ordered on
+ *     one stream.
+ *   - fp32 is IEEE binary32; an index is a uint32; vectors are contiguous.
+ *     Dense fp32 vectors must be 16-byte aligned, uint64 outputs 8-byte aligned.
+ *   - "Magnitude" order is the order of key(x) = bits(x) & 0x7fffffff, i.e. the
+ *     order of |x| for finite x (+-0 lowest; Inf above finite; NaN above Inf).
+ *   - Return value: OKT_OK, or a negative okt_status.  Argument errors are found
+ *     on the host before anything is launched; then no output is touched.
+ *     OKT_ERR_HIP means a launch failed (hipGetLastError has the reason).
+ */
+#ifndef OKT_H
+#define OKT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum okt_status {
+    OKT_OK = 0,
+    OKT_ERR_INVALID_ARG = -1, /* null/misaligned pointer, size out of range    */
+    OKT_ERR_WORKSPACE = -2,   /* d_ws missing, misaligned or too small         */
+    OKT_ERR_HIP = -3          /* the HIP runtime refused a launch              */
+} okt_status;
+
+/* Text for a status code; never NULL; static storage. */
+const char* okt_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int okt_version(void);
+
+/*
+ * Bytes of workspace that suffice for every call below on vectors of at most
+ * n_max elements, reductions over regions at most n_max wide and at most P_max
+ * contributions.  Pure host arithmetic.
+ */
+size_t okt_workspace_bytes(uint64_t n_max, uint32_t P_max);
+
+/*
+ * Accumulate residuals (Algorithm 2, line 4):  acc[i] = eps[i] + lr * G[i].
+ *   d_grad            in   fp32[n]  the stochastic gradient G
+ *   d_residual_inout  in   fp32[n]  the residual eps of the previous iteration
+ *                     out  fp32[n]  the accumulator acc, in place
+ *   lr                the learning rate alpha
+ * Arithmetic: fp32 multiply rounded, then fp32 add rounded (never fused);
+ * subnormals kept.  n = 0 is a no-op.  n must be below 2^32.
+ */
+int okt_residual_accumulate(const float* d_grad, float* d_residual_inout, float lr,
+                            uint64_t n, void* stream);
+
+/*
+ * Exact local top-k threshold (Algorithm 1, lines 2-4, th_re_evaluate; Sec.
+ * 3.1.3: the k-th largest value, which the paper obtains by sorting; here an
+ * exact radix select on the magnitude keys).
+ *   d_acc            in   fp32[n]
+ *   k                1 <= k <= n < 2^32
+ *   d_threshold_out  out  fp32[1]   th >= 0 whose key is the k-th largest key,
+ *                                   counted with multiplicity
+ *   d_count_ge_out   out  uint64[1] #{i : key(acc[i]) >= key(th)}  (>= k; > k
+ *                                   only when values tie with the k-th)
+ * Integer work only: the result is exact and run-to-run identical.
+ * Workspace: okt_workspace_bytes(n, 0); a smaller one (>= 32 KiB) still gives
+ * the same result, with more passes over d_acc.
+ */
+int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t k,
+                             float* d_threshold_out, uint64_t* d_count_ge_out,
+                             void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Threshold top-k selection, packaging into one consecutive COO buffer and
+ * residual update (Sec. 3.1.3 "selection according to a threshold only requires
+ * n comparisons"; Sec. 3.1.2 packaging; Algorithm 2, line 6, with `indexes`
+ * taken as all locally selected entries).
+ *   S = {i : key(acc[i]) >= key(*d_threshold)} in ascending i.
+ *   d_acc_inout  in   fp32[n] acc;  out  the residual: +0.0f at the emitted
+ *                entries, untouched elsewhere
+ *   d_threshold  in   fp32[1] on the device (its sign is ignored)
+ *   d_idx_out    out  uint32[capacity]  ascending indices of the emitted entries
+ *   d_val_out    out  fp32[capacity]    their values, bit copies of acc
+ *   capacity     entries the two output buffers can hold.  If |S| > capacity
+ *                only the first `capacity` members of S (in index order) are
+ *                emitted and zeroed; the others stay in the residual.
+ *   d_nnz_out    out  uint64[2]  {emitted = min(|S|, capacity), |S|}
+ * A single pass over acc.  n = 0 gives {0, 0}.  n must be below 2^32.
+ */
+int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshold,
+                         uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                         uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Balanced split of the index space [0, n) into R regions by the local top-k
+ * entries (Algorithm 1, lines 5-7, space_repartition; Sec. 3.1.1 "each worker
+ * calculates the local boundaries of the P regions by balancing the local top-k
+ * values"), and the split of the sorted COO buffer by those boundaries.
+ *   d_idx         in   uint32[*d_nnz] ascending (the output of
+ *                      okt_threshold_select)
+ *   d_nnz         in   uint64[1] on the device (d_nnz_out of the select works)
+ *   R             number of regions, >= 1
+ *   d_bounds_out  out  uint32[R+1]  b[0] = 0, b[R] = n,
+ *                      b[r] = idx[floor(r * nnz / R)]; if nnz = 0 the equal
+ *                      split b[r] = floor(r * n / R)
+ *   d_offsets_out out  uint64[R+1]  off[r] = first COO position whose index is
+ *                      >= b[r]; off[R] = nnz.  Region r owns COO entries
+ *                      [off[r], off[r+1]); the counts differ by at most one.
+ * Averaging the boundary vectors over workers is a collective and not part of
+ * this library.  1 <= n < 2^32.
+ */
+int okt_region_partition(const uint32_t* d_idx, const uint64_t* d_nnz, uint64_t n,
+                         uint32_t R, uint32_t* d_bounds_out, uint64_t* d_offsets_out,
+                         void* stream);
+
+/*
+ * Local reduction over one region (Algorithm 1, line 8, the "reduce" of
+ * split_and_reduce; Sec. 3.1.1: worker i sums the sparse pieces it receives for
+ * region i).  Plain sum, no 1/P.
+ *   d_idx_cat, d_val_cat  in  the P contributions back to back; contribution p is
+ *                         the slice [d_chunk_off[p], d_chunk_off[p+1]); inside a
+ *                         contribution indices are strictly ascending (anything
+ *                         else is undefined behaviour); entries outside [lo, hi)
+ *                         are skipped, so whole-space COO buffers may be passed
+ *   d_chunk_off           in  uint64[P+1] on the device, non-decreasing
+ *   P                     1 <= P <= 65535
+ *   lo, hi                the region, lo <= hi
+ *   d_idx_out, d_val_out  out uint32/fp32[capacity]: every index present in any
+ *                         contribution inside the region (also when the sum is
+ *                         zero), ascending, with the sum of its values.  Sums are
+ *                         accumulated in fp64 and rounded once to fp32; the order
+ *                         of the fp64 additions is not fixed.
+ *   capacity              entries the output can hold; the union is truncated to
+ *                         its first `capacity` members
+ *   d_nnz_out             out uint64[2] {emitted, size of the union}
+ *   d_dense_out_or_null   out fp32[hi-lo] the region densified (absent = +0.0f),
+ *                         or NULL
+ */
+int okt_sparse_reduce(const uint32_t* d_idx_cat, const float* d_val_cat,
+                      const uint64_t* d_chunk_off, uint32_t P, uint32_t lo, uint32_t hi,
+                      uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                      uint64_t* d_nnz_out, float* d_dense_out_or_null,
+                      void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * The same reduction for B independent regions in one launch (all regions a
+ * worker owns in one bucket, or the regions of several simulated workers).
+ * Region j has P contributions described by d_chunk_off[j*(P+1) .. j*(P+1)+P]
+ * (absolute positions in d_idx_cat / d_val_cat), bounds d_lo_hi[2j], d_lo_hi[2j+1]
+ * (uint32 on the device) and writes its output at position j * capacity of
+ * d_idx_out / d_val_out, its counts at d_nnz_out[2j..2j+1], and, if
+ * d_dense_out_or_null is given, its densified region at element j * max_width.
+ * Every region must be at most max_width wide (wider is an invalid argument the
+ * kernel reports by setting both counts of that region to UINT64_MAX).
+ * Workspace: okt_sparse_reduce_batch_workspace_bytes(B, max_width).
+ */
+size_t okt_sparse_reduce_batch_workspace_bytes(uint32_t B, uint32_t max_width);
+
+int okt_sparse_reduce_batch(const uint32_t* d_idx_cat, const float* d_val_cat,
+                            const uint64_t* d_chunk_off, const uint32_t* d_lo_hi,
+                            uint32_t B, uint32_t P, uint32_t max_width,
+                            uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                            uint64_t* d_nnz_out, float* d_dense_out_or_null,
+                            void* d_ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OKT_H */

@@ -1,0 +1,20 @@
+"""Ok-Topk one-GPU hot path for AMD MI355X: thin Python binding over libokt.so.
+
+Importing this package does not load the library; the first call does.  There
+is no CPU fallback: without the built HIP library every call raises.
+"""
+from .binding import (  # noqa: F401
+    OktError,
+    library_path,
+    load_library,
+    okt_region_partition,
+    okt_residual_accumulate,
+    okt_sparse_reduce,
+    okt_sparse_reduce_batch,
+    okt_sparse_reduce_batch_workspace_bytes,
+    okt_status_string,
+    okt_threshold_select,
+    okt_topk_threshold_exact,
+    okt_version,
+    okt_workspace_bytes,
+)

@@ -1,0 +1,203 @@
+"""ctypes binding of the C ABI declared in include/okt.h.
+
+Argument marshalling only: every function takes torch CUDA tensors (device
+memory) and plain Python scalars, checks dtype / device / contiguity, passes raw
+pointers and the current HIP stream, and raises OktError on a non-zero status.
+No arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+c_u32, c_u64, c_sz, c_vp, c_f32, c_int = (ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t,
+                                          ctypes.c_void_p, ctypes.c_float, ctypes.c_int)
+
+# name -> (restype, argtypes); mirrors include/okt.h
+SIGNATURES = {
+    "okt_status_string": (ctypes.c_char_p, [c_int]),
+    "okt_version": (c_int, []),
+    "okt_workspace_bytes": (c_sz, [c_u64, c_u32]),
+    "okt_sparse_reduce_batch_workspace_bytes": (c_sz, [c_u32, c_u32]),
+    "okt_residual_accumulate": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp]),
+    "okt_topk_threshold_exact": (c_int, [c_vp, c_u64, c_u64, c_vp, c_vp, c_vp, c_sz, c_vp]),
+    "okt_threshold_select": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_sz, c_vp]),
+    "okt_region_partition": (c_int, [c_vp, c_vp, c_u64, c_u32, c_vp, c_vp, c_vp]),
+    "okt_sparse_reduce": (c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp, c_u64, c_vp,
+                                  c_vp, c_vp, c_sz, c_vp]),
+    "okt_sparse_reduce_batch": (c_int, [c_vp, c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp,
+                                        c_u64, c_vp, c_vp, c_vp, c_sz, c_vp]),
+}
+
+
+class OktError(RuntimeError):
+    def __init__(self, call: str, status: int, text: str):
+        super().__init__(f"{call} failed: {text} (status {status})")
+        self.status = status
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libokt.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libokt.so (built in-tree by paper_2201_07598_amd.build)."""
+    global _LIB
+    if _LIB is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise OktError("load_library", -100,
+                           f"{path} is missing: run `python -m paper_2201_07598_amd.build`")
+        lib = ctypes.CDLL(path)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _LIB = lib
+    return _LIB
+
+
+def okt_status_string(status: int) -> str:
+    return load_library().okt_status_string(int(status)).decode()
+
+
+def okt_version() -> int:
+    return load_library().okt_version()
+
+
+def okt_workspace_bytes(n_max: int, P_max: int = 0) -> int:
+    return load_library().okt_workspace_bytes(int(n_max), int(P_max))
+
+
+def okt_sparse_reduce_batch_workspace_bytes(B: int, max_width: int) -> int:
+    return load_library().okt_sparse_reduce_batch_workspace_bytes(int(B), int(max_width))
+
+
+# --------------------------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _ptr(t, dtype, name, allow_none=False):
+    if t is None:
+        if allow_none:
+            return None
+        raise TypeError(f"{name} is required")
+    torch = _torch()
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor (device memory)")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise TypeError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = _torch().cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(call, status):
+    if status != 0:
+        raise OktError(call, status, okt_status_string(status))
+
+
+def _u64(torch):
+    # device-side uint64 scalars are carried in int64 tensors (same bytes)
+    return torch.int64
+
+
+def _u32(torch):
+    return torch.int32
+
+
+def okt_residual_accumulate(grad, residual_inout, lr: float, stream=None) -> None:
+    torch = _torch()
+    n = residual_inout.numel()
+    if grad.numel() != n:
+        raise ValueError("grad and residual must have the same length")
+    _check("okt_residual_accumulate", load_library().okt_residual_accumulate(
+        _ptr(grad, torch.float32, "grad"), _ptr(residual_inout, torch.float32, "residual_inout"),
+        float(lr), n, _stream(stream)))
+
+
+def okt_topk_threshold_exact(acc, k: int, threshold_out, count_ge_out, ws, stream=None) -> None:
+    torch = _torch()
+    if threshold_out.numel() < 1 or count_ge_out.numel() < 1:
+        raise ValueError("threshold_out and count_ge_out need one element")
+    _check("okt_topk_threshold_exact", load_library().okt_topk_threshold_exact(
+        _ptr(acc, torch.float32, "acc"), acc.numel(), int(k),
+        _ptr(threshold_out, torch.float32, "threshold_out"),
+        _ptr(count_ge_out, _u64(torch), "count_ge_out"),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(stream)))
+
+
+def okt_threshold_select(acc_inout, threshold, idx_out, val_out, nnz_out, ws, capacity=None,
+                         stream=None) -> None:
+    torch = _torch()
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > idx_out.numel() or cap > val_out.numel():
+        raise ValueError("capacity exceeds the output buffers")
+    if nnz_out.numel() < 2 or threshold.numel() < 1:
+        raise ValueError("nnz_out needs two elements, threshold one")
+    _check("okt_threshold_select", load_library().okt_threshold_select(
+        _ptr(acc_inout, torch.float32, "acc_inout"), acc_inout.numel(),
+        _ptr(threshold, torch.float32, "threshold"),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
+        _ptr(nnz_out, _u64(torch), "nnz_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
+        _stream(stream)))
+
+
+def okt_region_partition(idx, nnz, n: int, R: int, bounds_out, offsets_out, stream=None) -> None:
+    torch = _torch()
+    if bounds_out.numel() < R + 1 or offsets_out.numel() < R + 1:
+        raise ValueError("bounds_out and offsets_out need R+1 elements")
+    _check("okt_region_partition", load_library().okt_region_partition(
+        _ptr(idx, _u32(torch), "idx"), _ptr(nnz, _u64(torch), "nnz"), int(n), int(R),
+        _ptr(bounds_out, _u32(torch), "bounds_out"),
+        _ptr(offsets_out, _u64(torch), "offsets_out"), _stream(stream)))
+
+
+def okt_sparse_reduce(idx_cat, val_cat, chunk_off, lo: int, hi: int, idx_out, val_out, nnz_out,
+                      ws, dense_out=None, capacity=None, stream=None) -> None:
+    torch = _torch()
+    P = chunk_off.numel() - 1
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > idx_out.numel() or cap > val_out.numel():
+        raise ValueError("capacity exceeds the output buffers")
+    if dense_out is not None and dense_out.numel() < hi - lo:
+        raise ValueError("dense_out needs hi-lo elements")
+    if nnz_out.numel() < 2 or val_cat.numel() != idx_cat.numel():
+        raise ValueError("nnz_out needs two elements; idx_cat and val_cat the same length")
+    _check("okt_sparse_reduce", load_library().okt_sparse_reduce(
+        _ptr(idx_cat, _u32(torch), "idx_cat"), _ptr(val_cat, torch.float32, "val_cat"),
+        _ptr(chunk_off, _u64(torch), "chunk_off"), P, int(lo), int(hi),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
+        _ptr(nnz_out, _u64(torch), "nnz_out"),
+        _ptr(dense_out, torch.float32, "dense_out", allow_none=True),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(stream)))
+
+
+def okt_sparse_reduce_batch(idx_cat, val_cat, chunk_off, lo_hi, B: int, P: int, max_width: int,
+                            idx_out, val_out, capacity: int, nnz_out, ws, dense_out=None,
+                            stream=None) -> None:
+    torch = _torch()
+    if chunk_off.numel() < B * (P + 1) or lo_hi.numel() < 2 * B or nnz_out.numel() < 2 * B:
+        raise ValueError("chunk_off needs B*(P+1), lo_hi and nnz_out 2*B elements")
+    if idx_out.numel() < B * capacity or val_out.numel() < B * capacity:
+        raise ValueError("output buffers need B*capacity elements")
+    if dense_out is not None and dense_out.numel() < B * max_width:
+        raise ValueError("dense_out needs B*max_width elements")
+    _check("okt_sparse_reduce_batch", load_library().okt_sparse_reduce_batch(
+        _ptr(idx_cat, _u32(torch), "idx_cat"), _ptr(val_cat, torch.float32, "val_cat"),
+        _ptr(chunk_off, _u64(torch), "chunk_off"), _ptr(lo_hi, _u32(torch), "lo_hi"),
+        int(B), int(P), int(max_width),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"),
+        int(capacity), _ptr(nnz_out, _u64(torch), "nnz_out"),
+        _ptr(dense_out, torch.float32, "dense_out", allow_none=True),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(stream)))

@@ -1,0 +1,52 @@
+// Host-side pieces of the C ABI that belong to no single kernel.
+#include "okt_device.h"
+#include "okt_sizes.h"
+
+namespace okt {
+
+__global__ void zero_words_kernel(uint64_t* p, uint64_t words) {
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (; i < words; i += stride) p[i] = 0;
+}
+
+hipError_t launch_zero_words(void* p, uint64_t words, hipStream_t stream) {
+    if (words == 0) return hipSuccess;
+    uint64_t blocks = (words + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       (uint64_t*)p, words);
+    return hipGetLastError();
+}
+
+}  // namespace okt
+
+extern "C" {
+
+const char* okt_status_string(int status) {
+    switch (status) {
+        case OKT_OK: return "ok";
+        case OKT_ERR_INVALID_ARG: return "invalid argument";
+        case OKT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case OKT_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int okt_version(void) { return 100; }
+
+size_t okt_workspace_bytes(uint64_t n_max, uint32_t P_max) {
+    (void)P_max;
+    size_t need = okt::threshold_ws_bytes(n_max);
+    size_t s = okt::select_ws_bytes(n_max);
+    if (s > need) need = s;
+    s = okt::reduce_ws_bytes(1, n_max);
+    if (s > need) need = s;
+    return (need + 255) & ~(size_t)255;
+}
+
+size_t okt_sparse_reduce_batch_workspace_bytes(uint32_t B, uint32_t max_width) {
+    return (okt::reduce_ws_bytes(B, max_width) + 255) & ~(size_t)255;
+}
+
+}  // extern "C"
