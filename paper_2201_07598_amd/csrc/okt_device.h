@@ -40,16 +40,35 @@ __device__ __forceinline__ T wave_inclusive_scan(T v) {
 }
 
 // ---------------------------------------------------------------------------
-// Chained scan across workgroups (decoupled look-back).  One 64-bit descriptor
-// per tile carries a 2-bit status and a 32-bit count in ONE word, so a relaxed
-// device-scope load/store pair is enough: no separate flag, no fence.  Tiles
-// are numbered by a ticket taken at workgroup start, so every predecessor of a
-// tile belongs to a workgroup that is already running; the spin below therefore
-// always ends.
+// Chained scan across workgroups (decoupled look-back), two levels deep.
+//
+// Every tile needs the number of selected entries in all tiles before it.  One
+// 64-bit descriptor carries a 2-bit status and a 32-bit count in ONE word, so a
+// relaxed device-scope load/store pair is enough: no separate flag, no fence.
+// A plain look-back chain advances 64 tiles per round trip through device
+// memory (the 8 XCDs do not share an L2), which caps a streaming kernel far
+// below HBM speed.  So tiles are grouped by 64: a tile sums the aggregates of
+// the earlier tiles of its own group (one round trip) and, at the same time,
+// looks back over GROUP descriptors, 64 groups = 4096 tiles per round trip.
+// The last tile of a group publishes the group's aggregate and later its
+// inclusive prefix.
+//
+// Tiles are numbered by a ticket taken at workgroup start, so everything a tile
+// waits for is published by a workgroup that is already running and that waits
+// only for still earlier tickets: every wait ends.  As a backstop each wait is
+// bounded; a wait that runs out raises the error word of the workspace header.
 // ---------------------------------------------------------------------------
-constexpr uint64_t DESC_AGGREGATE = 1ull << 62;   // value = count of this tile
-constexpr uint64_t DESC_INCLUSIVE = 2ull << 62;   // value = count of tiles 0..this
+constexpr uint64_t DESC_AGGREGATE = 1ull << 62;   // value = count of this tile / group
+constexpr uint64_t DESC_INCLUSIVE = 2ull << 62;   // value = count of groups 0..this
 constexpr uint64_t DESC_VALUE = 0xffffffffull;
+constexpr int SCAN_GROUP = 64;                    // tiles per group
+constexpr uint32_t SPIN_LIMIT = 1u << 24;         // polls before a wait gives up
+
+struct ScanHeader {           // first 64 bytes of the workspace
+    uint32_t ticket;
+    uint32_t error;           // nonzero: a bounded wait ran out
+    uint32_t pad[14];
+};
 
 __device__ __forceinline__ uint64_t desc_load(const uint64_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -57,32 +76,50 @@ __device__ __forceinline__ uint64_t desc_load(const uint64_t* p) {
 __device__ __forceinline__ void desc_store(uint64_t* p, uint64_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-
-// Called by ONE full wave of the workgroup that owns `tile`.  Publishes the
-// tile's count and returns the sum of the counts of tiles 0..tile-1 (to every
-// lane).  desc[] must be zero before the first tile starts.
-__device__ __forceinline__ uint32_t lookback_exclusive(uint64_t* desc, uint32_t tile,
-                                                       uint32_t aggregate) {
-    const int lane = lane_id();
-    if (tile == 0) {
-        if (lane == 0) desc_store(desc, DESC_INCLUSIVE | aggregate);
-        return 0;
-    }
-    if (lane == 0) desc_store(desc + tile, DESC_AGGREGATE | aggregate);
-    uint32_t exclusive = 0;
-    int64_t base = (int64_t)tile - 1;
-    for (;;) {
-        const int64_t t = base - lane;
-        uint64_t d = DESC_INCLUSIVE;             // tiles before 0: nothing
-        if (t >= 0) {
-            d = desc_load(desc + t);
-            while ((d >> 62) == 0) {
-                __builtin_amdgcn_s_sleep(1);
-                d = desc_load(desc + t);
-            }
+// Poll until the descriptor is valid (status != 0).
+__device__ __forceinline__ uint64_t desc_wait(const uint64_t* p, ScanHeader* hdr) {
+    uint64_t d = desc_load(p);
+    uint32_t polls = 0;
+    while ((d >> 62) == 0) {
+        if (++polls > SPIN_LIMIT) {
+            __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return DESC_INCLUSIVE;      // give up: count 0, stops the walk
         }
+        __builtin_amdgcn_s_sleep(1);
+        d = desc_load(p);
+    }
+    return d;
+}
+
+// Called by ONE full wave.  Publishes the aggregate of `tile` and returns the sum
+// of the aggregates of the earlier tiles of its group (to every lane).  If the
+// tile closes its group, also publishes the group's aggregate.
+__device__ __forceinline__ uint32_t scan_within_group(ScanHeader* hdr, uint64_t* tile_desc,
+                                                      uint64_t* group_desc, uint32_t tile,
+                                                      uint32_t aggregate) {
+    const int lane = lane_id();
+    const uint32_t g = tile / SCAN_GROUP, j = tile % SCAN_GROUP;
+    if (lane == 0) desc_store(tile_desc + tile, DESC_AGGREGATE | aggregate);
+    uint32_t v = 0;
+    if ((uint32_t)lane < j) v = (uint32_t)(desc_wait(tile_desc + g * SCAN_GROUP + lane, hdr) & DESC_VALUE);
+    const uint32_t before = wave_sum(v);
+    if (j == SCAN_GROUP - 1 && lane == 0)
+        desc_store(group_desc + g, (g == 0 ? DESC_INCLUSIVE : DESC_AGGREGATE) | (uint64_t)(before + aggregate));
+    return before;
+}
+
+// Called by ONE full wave.  Returns the count of all groups before group g.
+__device__ __forceinline__ uint32_t scan_across_groups(ScanHeader* hdr, const uint64_t* group_desc,
+                                                       uint32_t g) {
+    const int lane = lane_id();
+    uint32_t exclusive = 0;
+    int64_t base = (int64_t)g - 1;
+    while (base >= 0) {
+        const int64_t t = base - lane;
+        uint64_t d = DESC_INCLUSIVE;              // before group 0: nothing
+        if (t >= 0) d = desc_wait(group_desc + t, hdr);
         const uint64_t inclusive_lanes = __ballot((d >> 62) == 2);
-        uint32_t v = (uint32_t)(d & DESC_VALUE);
+        const uint32_t v = (uint32_t)(d & DESC_VALUE);
         if (inclusive_lanes != 0) {
             const int first = __ffsll((unsigned long long)inclusive_lanes) - 1;
             exclusive += wave_sum(lane <= first ? v : 0u);
@@ -91,13 +128,24 @@ __device__ __forceinline__ uint32_t lookback_exclusive(uint64_t* desc, uint32_t 
         exclusive += wave_sum(v);
         base -= WAVE;
     }
-    if (lane == 0) desc_store(desc + tile, DESC_INCLUSIVE | (uint64_t)(exclusive + aggregate));
     return exclusive;
 }
 
-// Workspace header used by the chained scans: a ticket counter, then the
-// descriptors.  Kept on its own 64 bytes.
-constexpr size_t SCAN_HEADER_BYTES = 64;
+// Thread 0 of the tile that closes group g (g > 0) calls this once the group's
+// exclusive prefix is known.
+__device__ __forceinline__ void scan_close_group(uint64_t* group_desc, uint32_t g,
+                                                 uint32_t inclusive) {
+    desc_store(group_desc + g, DESC_INCLUSIVE | (uint64_t)inclusive);
+}
+
+// Workspace of a chained scan: the header, one descriptor per tile, then one per
+// group.
+constexpr size_t SCAN_HEADER_BYTES = sizeof(ScanHeader);
+static_assert(SCAN_HEADER_BYTES == 64, "header is one 64-byte line");
+inline uint64_t scan_groups(uint64_t tiles) { return (tiles + SCAN_GROUP - 1) / SCAN_GROUP; }
+inline size_t scan_ws_bytes(uint64_t tiles) {
+    return SCAN_HEADER_BYTES + 8 * (size_t)(tiles + scan_groups(tiles));
+}
 
 // Zero `words` 64-bit words (a fill kernel rather than a memset node, so that a
 // caller may capture the calls into a HIP graph).

@@ -39,13 +39,14 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_kernel(
     __shared__ uint64_t s_start[RED_CHUNKS];
     __shared__ uint32_t s_prefix[RED_CHUNKS + 1];
     __shared__ uint32_t s_wave[RED_BLOCK / WAVE];
-    __shared__ uint32_t s_tile, s_exclusive;
+    __shared__ uint32_t s_tile, s_before[2];
 
     const int tid = threadIdx.x;
     const uint32_t region = blockIdx.y;
-    uint32_t* ticket = (uint32_t*)(ws + (size_t)region * ws_region_bytes);
-    uint64_t* desc = (uint64_t*)(ws + (size_t)region * ws_region_bytes + SCAN_HEADER_BYTES);
-    if (tid == 0) s_tile = atomicAdd(ticket, 1u);
+    ScanHeader* hdr = (ScanHeader*)(ws + (size_t)region * ws_region_bytes);
+    uint64_t* tile_desc = (uint64_t*)(ws + (size_t)region * ws_region_bytes + SCAN_HEADER_BYTES);
+    uint64_t* group_desc = tile_desc + gridDim.x;
+    if (tid == 0) s_tile = atomicAdd(&hdr->ticket, 1u);
 
     const uint32_t lo = lo_hi ? lo_hi[2 * region] : lo0;
     const uint32_t hi = lo_hi ? lo_hi[2 * region + 1] : hi0;
@@ -141,12 +142,18 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_kernel(
         if (w < wave) rank += s_wave[w];
         aggregate += s_wave[w];
     }
+    const uint32_t group = tile / SCAN_GROUP;
     if (wave == 0) {
-        const uint32_t ex = lookback_exclusive(desc, tile, aggregate);
-        if (lane == 0) s_exclusive = ex;
+        const uint32_t before = scan_within_group(hdr, tile_desc, group_desc, tile, aggregate);
+        if (lane == 0) s_before[0] = before;
+    } else if (wave == 1) {
+        const uint32_t before = scan_across_groups(hdr, group_desc, group);
+        if (lane == 0) s_before[1] = before;
     }
     __syncthreads();
-    const uint32_t exclusive = s_exclusive;
+    const uint32_t exclusive = s_before[0] + s_before[1];
+    if (tid == 0 && group != 0 && tile % SCAN_GROUP == SCAN_GROUP - 1)
+        scan_close_group(group_desc, group, exclusive + aggregate);
     {
         uint32_t w = word;
         uint64_t pos = (uint64_t)exclusive + rank;
@@ -167,8 +174,10 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_kernel(
     }
     if (tile == ntiles - 1 && tid == 0) {
         const uint64_t total = (uint64_t)exclusive + aggregate;
-        nnz[0] = total < capacity ? total : capacity;
-        nnz[1] = total;
+        const bool failed =
+            __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+        nnz[0] = failed ? ~0ull : (total < capacity ? total : capacity);
+        nnz[1] = failed ? ~0ull : total;
     }
 }
 

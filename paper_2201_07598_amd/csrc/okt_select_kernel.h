@@ -1,0 +1,226 @@
+// The threshold-select kernel, as a template over its shape.
+#ifndef OKT_SELECT_KERNEL_H
+#define OKT_SELECT_KERNEL_H
+
+#include "okt_device.h"
+
+namespace okt {
+
+// Lanes below this one that have their bit set in a 64-bit wave mask.
+__device__ __forceinline__ uint32_t mask_rank(uint64_t m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// How an element is tested against the threshold.  For every threshold that is
+// not a NaN, key(x) >= key(th) is the same as !(|x| < |th|) in IEEE arithmetic
+// with subnormals kept: one compare with an |.| source modifier per element, a
+// NaN x counts as selected just as its key lies above every non-NaN key.  A NaN
+// threshold (possible only if the k-th largest magnitude itself is a NaN) takes
+// the integer key comparison.
+struct TestFloat {
+    float th_abs;
+    __device__ __forceinline__ bool operator()(float x) const { return !(__builtin_fabsf(x) < th_abs); }
+};
+struct TestKey {
+    uint32_t th_key;
+    __device__ __forceinline__ bool operator()(float x) const { return magnitude_key(x) >= th_key; }
+};
+
+struct StashEntry { uint32_t idx; float val; };     // 8 bytes: one LDS store per entry
+
+// One round of a wave: 64 lanes x float4 = 256 consecutive elements starting at
+// `first` (lane l holds first + 4l .. first + 4l + 3); sx..sw say which of the
+// lane's components are selected.  Calls sink(rank, index, value) for every
+// selected element, rank counting from `count` in ascending index order, and
+// returns the new count (wave-uniform).  Nearly every round that selects
+// anything selects at most one component per lane; that case costs one rank
+// (a single mbcnt pair) and one sink call.
+template <typename Sink>
+__device__ __forceinline__ uint32_t select_round(uint32_t first, const float4& v, bool sx, bool sy,
+                                                 bool sz, bool sw, uint32_t count, Sink&& sink) {
+    const uint64_t bx = __ballot(sx), by = __ballot(sy), bz = __ballot(sz), bw = __ballot(sw);
+    const uint64_t bxy = bx | by, bxyz = bxy | bz, any = bxyz | bw;
+    if (any == 0) return count;
+    const uint32_t i0 = first + 4u * (uint32_t)lane_id();
+    const uint64_t multi = (bx & by) | (bxy & bz) | (bxyz & bw);   // lanes selecting 2+ components
+    if (multi == 0) {
+        if (sx | sy | sz | sw) {
+            // exactly one of sx..sw is set.  The components go through an empty
+            // asm so that the blend stays three selects; seen as one vector, the
+            // compiler turns it into an indexed access through scratch memory.
+            float vx = v.x, vy = v.y, vz = v.z, vw = v.w;
+            asm volatile("" : "+v"(vx), "+v"(vy), "+v"(vz), "+v"(vw));
+            uint32_t comp = 0;
+            float x = vx;
+            if (sy) { comp = 1; x = vy; }
+            if (sz) { comp = 2; x = vz; }
+            if (sw) { comp = 3; x = vw; }
+            sink(count + mask_rank(any), i0 + comp, x);
+        }
+        return count + (uint32_t)__popcll(any);
+    }
+    uint32_t rank = count + mask_rank(bx) + mask_rank(by) + mask_rank(bz) + mask_rank(bw);
+    if (sx) sink(rank++, i0, v.x);
+    if (sy) sink(rank++, i0 + 1, v.y);
+    if (sz) sink(rank++, i0 + 2, v.z);
+    if (sw) sink(rank++, i0 + 3, v.w);
+    return count + (uint32_t)(__popcll(bx) + __popcll(by) + __popcll(bz) + __popcll(bw));
+}
+
+// Walks the wave's piece [start, end) of acc in rounds of 256 elements, U rounds
+// in flight, and feeds every selected element to `sink` in ascending index
+// order.  Returns the number of selected elements.
+template <int U, typename Test, typename Sink>
+__device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start, uint64_t end,
+                                                Test test, Sink&& sink) {
+    const int lane = lane_id();
+    uint32_t count = 0;
+    uint64_t r = start;
+    for (; r + 256 * U <= end; r += 256 * U) {            // start is 16-byte aligned
+        const float4* src = reinterpret_cast<const float4*>(acc + r) + lane;
+        float4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = src[u * WAVE];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            count = select_round((uint32_t)r + 256u * u, v[u], test(v[u].x), test(v[u].y),
+                                 test(v[u].z), test(v[u].w), count, sink);
+    }
+    for (; r < end; r += 256) {                           // ragged rounds of the last piece
+        const uint64_t i = r + 4u * (uint32_t)lane;
+        float e[4];
+        bool s[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bool inside = i + c < end;
+            e[c] = inside ? acc[i + c] : 0.0f;
+            s[c] = inside && test(e[c]);
+        }
+        count = select_round((uint32_t)r, make_float4(e[0], e[1], e[2], e[3]), s[0], s[1], s[2],
+                             s[3], count, sink);
+    }
+    return count;
+}
+
+// Workgroup `seg` (a ticket) owns WAVES consecutive pieces of `piece` elements,
+// one per wave.  A wave streams its piece once, with no barrier and no wait in
+// the loop, and parks the few selected (index, value) pairs in its LDS stash.
+// Then the workgroup publishes its count, learns the count of everything before
+// it from the chained scan, and writes its pairs to their final place, zeroing
+// the residual entries it emitted.  A wave whose piece holds more selected
+// entries than the stash walks its piece a second time and writes directly
+// (dense thresholds only; the residual is still untouched at that point).
+template <int BLOCK, int U, int STASH, bool TICKET, typename Test>
+__device__ __forceinline__ void select_body(
+    float* __restrict__ acc, uint32_t n, Test test, uint32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
+    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece,
+    uint32_t seg, StashEntry (*s_stash)[STASH], uint32_t* s_count, uint32_t* s_before) {
+    constexpr int WAVES = BLOCK / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    const uint64_t start = ((uint64_t)seg * WAVES + wave) * piece;
+    const uint64_t end = start + piece < n ? start + piece : n;       // start >= n: empty
+
+    // A selected element is parked in the stash and zeroed on the spot, while its
+    // cache line is still close by: zeroing it later costs a read-modify-write of
+    // a line long gone from the caches.  Whatever must not stay zero after all
+    // (output full, stash overflow) is written back from the stash below.
+    StashEntry* mine = s_stash[wave];
+    const uint32_t count =
+        select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
+            if (rank < (uint32_t)STASH) {
+                mine[rank] = StashEntry{i, x};
+                acc[i] = 0.0f;
+            }
+        });
+    if (lane == 0) s_count[wave] = count;
+    __syncthreads();
+    uint32_t aggregate = 0, wave_first = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+        if (w == wave) wave_first = aggregate;
+        aggregate += s_count[w];
+    }
+
+    // ---- position of the segment in the output: two waves, two levels, at once ----
+    const uint32_t group = seg / SCAN_GROUP;
+    if (wave == 0) {
+        const uint32_t before = scan_within_group(hdr, seg_desc, group_desc, seg, aggregate);
+        if (lane == 0) s_before[0] = before;
+    } else if (wave == 1) {
+        const uint32_t before = scan_across_groups(hdr, group_desc, group);
+        if (lane == 0) s_before[1] = before;
+    }
+    __syncthreads();
+    const uint32_t exclusive = s_before[0] + s_before[1];
+    if (tid == 0 && group != 0 && seg % SCAN_GROUP == SCAN_GROUP - 1)
+        scan_close_group(group_desc, group, exclusive + aggregate);
+
+    // ---- emit in ascending index order, and zero what was emitted ----
+    const uint64_t first = (uint64_t)exclusive + wave_first;
+    if (count <= (uint32_t)STASH) {
+        for (uint32_t j = lane; j < count; j += WAVE) {
+            const uint64_t pos = first + j;
+            const StashEntry e = mine[j];
+            if (pos < capacity) {
+                idx_out[pos] = e.idx;
+                val_out[pos] = e.val;
+            } else {
+                acc[e.idx] = e.val;         // output full: the entry stays in the residual
+            }
+        }
+    } else {
+        // stash overflow: put back what was zeroed, then walk the piece again
+        for (uint32_t j = lane; j < (uint32_t)STASH; j += WAVE) acc[mine[j].idx] = mine[j].val;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // stores land before the re-read
+        select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
+            const uint64_t pos = first + rank;
+            if (pos < capacity) {
+                idx_out[pos] = i;
+                val_out[pos] = x;
+                acc[i] = 0.0f;
+            }
+        });
+    }
+    if (seg == nseg - 1 && tid == 0) {
+        const uint64_t total = (uint64_t)exclusive + aggregate;
+        const bool failed =
+            __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+        nnz_out[0] = failed ? ~0ull : (total < capacity ? total : capacity);
+        nnz_out[1] = failed ? ~0ull : total;
+    }
+}
+
+template <int BLOCK, int U, int STASH, bool TICKET>
+__global__ __launch_bounds__(BLOCK) void select_kernel(
+    float* __restrict__ acc, uint32_t n, const float* __restrict__ d_threshold,
+    uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
+    uint64_t* __restrict__ nnz_out, ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc,
+    uint32_t nseg, uint32_t piece) {
+    static_assert(BLOCK % WAVE == 0 && BLOCK >= 2 * WAVE, "needs two waves for the scan");
+    constexpr int WAVES = BLOCK / WAVE;
+    __shared__ StashEntry s_stash[WAVES][STASH];
+    __shared__ uint32_t s_count[WAVES];
+    __shared__ uint32_t s_seg;
+    __shared__ uint32_t s_before[2];           // within the group, across groups
+
+    if (TICKET) {
+        if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+        __syncthreads();
+    }
+    const uint32_t seg = TICKET ? s_seg : blockIdx.x;
+    const float th = *d_threshold;
+    if (th == th) {
+        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestFloat{__builtin_fabsf(th)}, idx_out,
+                                             val_out, capacity, nnz_out, hdr, seg_desc,
+                                             group_desc, nseg, piece, seg, s_stash, s_count,
+                                             s_before);
+    } else {
+        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestKey{magnitude_key(th)}, idx_out, val_out,
+                                             capacity, nnz_out, hdr, seg_desc, group_desc, nseg,
+                                             piece, seg, s_stash, s_count, s_before);
+    }
+}
+
+}  // namespace okt
+#endif
