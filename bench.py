@@ -302,7 +302,7 @@ def time_reduce_batch(args, torch, np, okt, wl, w, lo, hi):
     out_idx = torch.zeros(B * E1, dtype=torch.int32, device=dev)
     out_val = torch.zeros(B * E1, dtype=torch.float32, device=dev)
     nnz = torch.zeros(2 * B, dtype=torch.int64, device=dev)
-    ws = torch.empty(okt.okt_sparse_reduce_batch_workspace_bytes(B, width), dtype=torch.uint8,
+    ws = torch.empty(okt.okt_sparse_reduce_batch_workspace_bytes(B, P, width), dtype=torch.uint8,
                      device=dev)
     log(f"[bench] reduce batch: B={B} regions, {B * E1} entries uploaded ({time.time() - t0:.1f}s)")
     times = []

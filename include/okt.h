@@ -169,9 +169,9 @@ int okt_sparse_reduce(const uint32_t* d_idx_cat, const float* d_val_cat,
  * d_dense_out_or_null is given, its densified region at element j * max_width.
  * Every region must be at most max_width wide (wider is an invalid argument the
  * kernel reports by setting both counts of that region to UINT64_MAX).
- * Workspace: okt_sparse_reduce_batch_workspace_bytes(B, max_width).
+ * Workspace: okt_sparse_reduce_batch_workspace_bytes(B, P, max_width).
  */
-size_t okt_sparse_reduce_batch_workspace_bytes(uint32_t B, uint32_t max_width);
+size_t okt_sparse_reduce_batch_workspace_bytes(uint32_t B, uint32_t P, uint32_t max_width);
 
 int okt_sparse_reduce_batch(const uint32_t* d_idx_cat, const float* d_val_cat,
                             const uint64_t* d_chunk_off, const uint32_t* d_lo_hi,

@@ -21,7 +21,7 @@ SIGNATURES = {
     "okt_status_string": (ctypes.c_char_p, [c_int]),
     "okt_version": (c_int, []),
     "okt_workspace_bytes": (c_sz, [c_u64, c_u32]),
-    "okt_sparse_reduce_batch_workspace_bytes": (c_sz, [c_u32, c_u32]),
+    "okt_sparse_reduce_batch_workspace_bytes": (c_sz, [c_u32, c_u32, c_u32]),
     "okt_residual_accumulate": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp]),
     "okt_topk_threshold_exact": (c_int, [c_vp, c_u64, c_u64, c_vp, c_vp, c_vp, c_sz, c_vp]),
     "okt_threshold_select": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_sz, c_vp]),
@@ -71,8 +71,8 @@ def okt_workspace_bytes(n_max: int, P_max: int = 0) -> int:
     return load_library().okt_workspace_bytes(int(n_max), int(P_max))
 
 
-def okt_sparse_reduce_batch_workspace_bytes(B: int, max_width: int) -> int:
-    return load_library().okt_sparse_reduce_batch_workspace_bytes(int(B), int(max_width))
+def okt_sparse_reduce_batch_workspace_bytes(B: int, P: int, max_width: int) -> int:
+    return load_library().okt_sparse_reduce_batch_workspace_bytes(int(B), int(P), int(max_width))
 
 
 # --------------------------------------------------------------------------

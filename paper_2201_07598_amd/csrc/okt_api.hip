@@ -36,17 +36,17 @@ const char* okt_status_string(int status) {
 int okt_version(void) { return 100; }
 
 size_t okt_workspace_bytes(uint64_t n_max, uint32_t P_max) {
-    (void)P_max;
+    if (P_max == 0) P_max = 1;
     size_t need = okt::threshold_ws_bytes(n_max);
     size_t s = okt::select_ws_bytes(n_max);
     if (s > need) need = s;
-    s = okt::reduce_ws_bytes(1, n_max);
+    s = okt::reduce_ws_bytes(1, n_max, P_max);
     if (s > need) need = s;
     return (need + 255) & ~(size_t)255;
 }
 
-size_t okt_sparse_reduce_batch_workspace_bytes(uint32_t B, uint32_t max_width) {
-    return (okt::reduce_ws_bytes(B, max_width) + 255) & ~(size_t)255;
+size_t okt_sparse_reduce_batch_workspace_bytes(uint32_t B, uint32_t P, uint32_t max_width) {
+    return (okt::reduce_ws_bytes(B, max_width, P ? P : 1) + 255) & ~(size_t)255;
 }
 
 }  // extern "C"

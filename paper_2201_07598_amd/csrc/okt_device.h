@@ -99,6 +99,7 @@ __device__ __forceinline__ uint32_t scan_within_group(ScanHeader* hdr, uint64_t*
                                                       uint32_t aggregate) {
     const int lane = lane_id();
     const uint32_t g = tile / SCAN_GROUP, j = tile % SCAN_GROUP;
+    // storing the same word twice is harmless: a caller may have published early
     if (lane == 0) desc_store(tile_desc + tile, DESC_AGGREGATE | aggregate);
     uint32_t v = 0;
     if ((uint32_t)lane < j) v = (uint32_t)(desc_wait(tile_desc + g * SCAN_GROUP + lane, hdr) & DESC_VALUE);
@@ -106,6 +107,12 @@ __device__ __forceinline__ uint32_t scan_within_group(ScanHeader* hdr, uint64_t*
     if (j == SCAN_GROUP - 1 && lane == 0)
         desc_store(group_desc + g, (g == 0 ? DESC_INCLUSIVE : DESC_AGGREGATE) | (uint64_t)(before + aggregate));
     return before;
+}
+
+// A tile may publish its aggregate as soon as it knows it, ahead of the scan.
+__device__ __forceinline__ void scan_publish_early(uint64_t* tile_desc, uint32_t tile,
+                                                   uint32_t aggregate) {
+    desc_store(tile_desc + tile, DESC_AGGREGATE | aggregate);
 }
 
 // Called by ONE full wave.  Returns the count of all groups before group g.

@@ -2,20 +2,33 @@
 // sparse contributions a worker receives for its region (Algorithm 1, line 8;
 // Sec. 3.1.1).  Plain sum over the union of the supports.
 //
-// A workgroup owns RED_TILE consecutive index slots of the region.  It finds
-// its slice of every contribution by binary search (contributions are sorted),
-// then streams the slices, flattened into one list so that all 256 threads stay
-// busy whatever the slice lengths, into a dense fp64 tile in LDS (LDS atomic add;
-// a bitmap records which slots were hit).  The tile is then compacted in index
-// order; its position in the output comes from a chained scan over tile counts.
-// Traffic: every input entry is read once (8 B), every output entry written
-// once (8 B), plus 4 B per slot if the dense region is requested.
+// Two kernels per call.
+//  1. reduce_slices_kernel: the region is cut into tiles of `slots` consecutive
+//     index slots; one thread per (tile boundary, contribution) finds, by binary
+//     search in the sorted contribution, where the boundary falls.  All searches
+//     of a call run side by side, so their latency is paid once.
+//  2. reduce_tile_kernel: a workgroup owns one tile.  Its slice of every
+//     contribution is known from the table, so all its entries are addressed up
+//     front: the slices are flattened into one list and every thread takes each
+//     256th entry, whatever the slice lengths.  Entries are summed with LDS fp64
+//     atomic adds.  Where the region is densely hit the accumulator of a slot is
+//     the slot itself.  Where it is sparsely hit the tile is wider than the
+//     accumulator array: a first sweep marks the hit slots in a bitmap, the
+//     popcount prefix of the bitmap ranks them, and the second sweep sums into
+//     accumulator [rank].  The tile is then written out in index order; its place
+//     in the output comes from the two-level chained scan over tile counts.
+// Traffic: every input entry is read once from HBM (the second sweep hits in
+// cache), every output entry is written once, plus 4 B per slot if the dense
+// region is requested.
 #include "okt_device.h"
 #include "okt_sizes.h"
 
+#include <type_traits>
+
 namespace okt {
 
-constexpr int RED_WORDS = RED_TILE / 32;
+constexpr int RED_WAVES = RED_BLOCK / WAVE;
+constexpr uint32_t RED_WORDS_MAX = RED_S_MAX / 32;
 
 __device__ __forceinline__ uint64_t lower_bound_idx(const uint32_t* __restrict__ a, uint64_t lo,
                                                     uint64_t hi, uint32_t x) {
@@ -26,154 +39,308 @@ __device__ __forceinline__ uint64_t lower_bound_idx(const uint32_t* __restrict__
     return lo;
 }
 
+struct RegionView {
+    uint32_t lo, hi, width, ntiles;
+    bool bad;
+};
+__device__ __forceinline__ RegionView region_view(const uint32_t* lo_hi, uint32_t lo0, uint32_t hi0,
+                                                  uint32_t region, uint32_t max_width,
+                                                  uint32_t slots) {
+    RegionView r;
+    r.lo = lo_hi ? lo_hi[2 * region] : lo0;
+    r.hi = lo_hi ? lo_hi[2 * region + 1] : hi0;
+    r.bad = r.hi < r.lo || r.hi - r.lo > max_width;
+    r.width = r.bad ? 0u : r.hi - r.lo;
+    r.ntiles = (uint32_t)(((uint64_t)r.width + slots - 1) / slots);
+    return r;
+}
+
+// table[region][t][p] = number of entries of contribution p with index below
+// lo + t * slots (clipped to hi), for t = 0 .. ntiles.
+__global__ __launch_bounds__(256) void reduce_slices_kernel(
+    const uint32_t* __restrict__ idx_cat, const uint64_t* __restrict__ chunk_off,
+    const uint32_t* __restrict__ lo_hi, uint32_t lo0, uint32_t hi0, uint32_t P,
+    uint32_t max_width, uint32_t slots, char* ws, uint32_t ws_region_bytes,
+    uint32_t table_offset) {
+    const uint32_t region = blockIdx.y;
+    const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
+    uint32_t* table = (uint32_t*)(ws + (size_t)region * ws_region_bytes + table_offset);
+    const uint64_t* off = chunk_off + (size_t)region * (P + 1);
+    const uint64_t cells = (uint64_t)(r.ntiles + 1) * P;
+    for (uint64_t c = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; c < cells;
+         c += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t t = (uint32_t)(c / P), p = (uint32_t)(c % P);
+        uint64_t bound = (uint64_t)r.lo + (uint64_t)t * slots;
+        if (bound > r.hi) bound = r.hi;
+        const uint64_t cb = off[p], ce = off[p + 1];
+        table[c] = (uint32_t)(lower_bound_idx(idx_cat, cb, ce, (uint32_t)bound) - cb);
+    }
+}
+
+// Zero the scan state (header and descriptors) at the head of every region's
+// workspace; the slice table behind it is fully rewritten by every call.
+__global__ __launch_bounds__(256) void reduce_clear_kernel(char* ws, uint32_t ws_region_bytes,
+                                                          uint32_t words) {
+    uint64_t* p = (uint64_t*)(ws + (size_t)blockIdx.y * ws_region_bytes);
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x)
+        p[i] = 0;
+}
+
+// Exclusive prefix over the popcounts of `words` bitmap words into s_wprefix;
+// returns the total (to every thread).  Called by the whole workgroup.
+__device__ __forceinline__ uint32_t bitmap_prefix(const uint32_t* s_bits, uint16_t* s_wprefix,
+                                                  uint32_t words, uint32_t* s_wave) {
+    constexpr uint32_t PER = RED_WORDS_MAX / RED_BLOCK;        // words per thread (4)
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    uint32_t c[PER], sum = 0;
+#pragma unroll
+    for (uint32_t j = 0; j < PER; ++j) {
+        const uint32_t w = tid * PER + j;
+        c[j] = w < words ? (uint32_t)__popc(s_bits[w]) : 0u;
+        sum += c[j];
+    }
+    const uint32_t incl = wave_inclusive_scan<uint32_t>(sum);
+    if (lane == WAVE - 1) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t before = incl - sum, total = 0;
+#pragma unroll
+    for (int w = 0; w < RED_WAVES; ++w) {
+        if (w < wave) before += s_wave[w];
+        total += s_wave[w];
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < PER; ++j) {
+        const uint32_t w = tid * PER + j;
+        if (w < words) s_wprefix[w] = (uint16_t)before;       // < RED_S_MAX <= 65536
+        before += c[j];
+    }
+    __syncthreads();
+    return total;
+}
+
 // grid = (tiles of the widest region, B).  Region j: chunk offsets at
 // chunk_off + j*(P+1); bounds from lo_hi[2j..] if lo_hi != NULL else (lo0, hi0).
-__global__ __launch_bounds__(RED_BLOCK) void reduce_kernel(
+__global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     const uint32_t* __restrict__ idx_cat, const float* __restrict__ val_cat,
     const uint64_t* __restrict__ chunk_off, const uint32_t* __restrict__ lo_hi, uint32_t lo0,
-    uint32_t hi0, uint32_t P, uint32_t max_width, uint32_t* __restrict__ idx_out,
+    uint32_t hi0, uint32_t P, uint32_t max_width, uint32_t slots, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
-    float* __restrict__ dense_out, char* ws, uint32_t ws_region_bytes) {
-    __shared__ double s_sum[RED_TILE];
-    __shared__ uint32_t s_bits[RED_WORDS];
-    __shared__ uint64_t s_start[RED_CHUNKS];
-    __shared__ uint32_t s_prefix[RED_CHUNKS + 1];
-    __shared__ uint32_t s_wave[RED_BLOCK / WAVE];
+    float* __restrict__ dense_out, char* ws, uint32_t ws_region_bytes, uint32_t table_offset) {
+    __shared__ double s_sum[RED_C];
+    __shared__ uint32_t s_bits[RED_WORDS_MAX];
+    __shared__ uint16_t s_wprefix[RED_WORDS_MAX];
+    __shared__ uint64_t s_start[RED_CHUNKS];      // slice starts of the current sweep
+    __shared__ uint32_t s_len[RED_CHUNKS];        // slice lengths
+    __shared__ uint32_t s_loaded_p0;              // which sweep they belong to
+    __shared__ uint32_t s_wave[RED_WAVES];
     __shared__ uint32_t s_tile, s_before[2];
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
     const uint32_t region = blockIdx.y;
-    ScanHeader* hdr = (ScanHeader*)(ws + (size_t)region * ws_region_bytes);
-    uint64_t* tile_desc = (uint64_t*)(ws + (size_t)region * ws_region_bytes + SCAN_HEADER_BYTES);
+    char* region_ws = ws + (size_t)region * ws_region_bytes;
+    ScanHeader* hdr = (ScanHeader*)region_ws;
+    uint64_t* tile_desc = (uint64_t*)(region_ws + SCAN_HEADER_BYTES);
     uint64_t* group_desc = tile_desc + gridDim.x;
-    if (tid == 0) s_tile = atomicAdd(&hdr->ticket, 1u);
+    const uint32_t* table = (const uint32_t*)(region_ws + table_offset);
+    if (tid == 0) {
+        s_tile = atomicAdd(&hdr->ticket, 1u);
+        s_loaded_p0 = ~0u;
+    }
 
-    const uint32_t lo = lo_hi ? lo_hi[2 * region] : lo0;
-    const uint32_t hi = lo_hi ? lo_hi[2 * region + 1] : hi0;
+    const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
     uint64_t* nnz = nnz_out + 2 * (size_t)region;
-    const bool bad = hi < lo || hi - lo > max_width;
-    const uint32_t width = bad ? 0u : hi - lo;
-    const uint32_t ntiles = (width + RED_TILE - 1) / RED_TILE;
-
-    for (int s = tid; s < RED_TILE; s += RED_BLOCK) s_sum[s] = 0.0;
-    if (tid < RED_WORDS) s_bits[tid] = 0;
+    const bool ranked = slots > RED_C;           // accumulators indexed by rank, not by slot
+    const uint32_t words_all = slots / 32;       // slots is a multiple of RED_C
+    for (uint32_t w = tid; w < words_all; w += RED_BLOCK) s_bits[w] = 0;
     __syncthreads();
     const uint32_t tile = s_tile;
-    if (ntiles == 0) {
+    if (r.ntiles == 0) {
         if (tile == 0 && tid == 0) {
-            nnz[0] = bad ? ~0ull : 0ull;
-            nnz[1] = bad ? ~0ull : 0ull;
+            nnz[0] = r.bad ? ~0ull : 0ull;
+            nnz[1] = r.bad ? ~0ull : 0ull;
         }
         return;
     }
-    if (tile >= ntiles) return;
-    const uint32_t a = lo + tile * (uint32_t)RED_TILE;              // first index of the tile
-    const uint32_t slots = (hi - a) < (uint32_t)RED_TILE ? (hi - a) : (uint32_t)RED_TILE;
+    if (tile >= r.ntiles) return;
+    const uint32_t a = r.lo + tile * slots;                       // first index of the tile
+    const uint32_t tslots = (r.hi - a) < slots ? (r.hi - a) : slots;
+    const uint32_t words = (tslots + 31) / 32;
     const uint64_t* off = chunk_off + (size_t)region * (P + 1);
+    const uint32_t* row0 = table + (size_t)tile * P;              // slice starts
+    const uint32_t* row1 = row0 + P;                              // slice ends
     idx_out += (size_t)region * capacity;
     val_out += (size_t)region * capacity;
 
-    // ---- accumulate the contributions, RED_CHUNKS of them per sweep ----
-    for (uint32_t p0 = 0; p0 < P; p0 += RED_CHUNKS) {
-        const uint32_t np = (P - p0) < (uint32_t)RED_CHUNKS ? (P - p0) : (uint32_t)RED_CHUNKS;
-        // slice of contribution p0+q that falls into [a, a+slots)
-        for (uint32_t q = tid; q < np; q += RED_BLOCK) {
-            const uint64_t cb = off[p0 + q], ce = off[p0 + q + 1];
-            const uint64_t sb = lower_bound_idx(idx_cat, cb, ce, a);
-            // a + slots may be 2^32 only if hi is; hi <= 2^32-1, so it fits
-            const uint64_t se = lower_bound_idx(idx_cat, sb, ce, a + slots);
-            s_start[q] = sb;
-            s_prefix[q + 1] = (uint32_t)(se - sb);      // <= RED_TILE
-        }
-        if (tid == 0) s_prefix[0] = 0;
-        __syncthreads();
-        // inclusive scan of the np counts (np <= 1024: four per thread)
-        {
-            uint32_t c[RED_CHUNKS / RED_BLOCK];
-            uint32_t sum = 0;
+    // Hands every entry of the tile to body(index, value).  Contributions are
+    // taken RED_CHUNKS at a time; slice q of a sweep belongs to wave q mod WAVES,
+    // whose lanes read it 64 consecutive entries at a time (coalesced).  A wave
+    // first names up to RED_UNROLL such blocks, across its slices, then issues all
+    // their loads, then consumes them: enough loads in flight to cover the memory
+    // latency, no per-entry search, and only wave-uniform bookkeeping.
+    auto for_each_entry = [&](auto with_values, auto&& body) {
+        constexpr bool VALUES = decltype(with_values)::value;
+        for (uint32_t p0 = 0; p0 < P; p0 += RED_CHUNKS) {
+            const uint32_t np = (P - p0) < (uint32_t)RED_CHUNKS ? (P - p0) : (uint32_t)RED_CHUNKS;
+            if (p0 != s_loaded_p0) {            // slice table of this sweep not in LDS yet
+                __syncthreads();
+                for (uint32_t q = tid; q < np; q += RED_BLOCK) {
+                    const uint32_t b = row0[p0 + q], e = row1[p0 + q];
+                    s_start[q] = off[p0 + q] + b;
+                    s_len[q] = e - b;
+                }
+                __syncthreads();
+                if (tid == 0) s_loaded_p0 = p0;
+            }
+            uint32_t q = (uint32_t)__builtin_amdgcn_readfirstlane(wave), o = 0;   // next block: slice q, entries o .. o+63
+            while (q < np) {
+                uint64_t pos[RED_UNROLL];
+                bool live[RED_UNROLL];
 #pragma unroll
-            for (int j = 0; j < RED_CHUNKS / RED_BLOCK; ++j) {
-                const uint32_t q = tid * (RED_CHUNKS / RED_BLOCK) + j;
-                c[j] = q < np ? s_prefix[q + 1] : 0u;
-                sum += c[j];
-            }
-            const uint32_t incl = wave_inclusive_scan<uint32_t>(sum);
-            const int lane = tid & (WAVE - 1), wave = tid >> 6;
-            if (lane == WAVE - 1) s_wave[wave] = incl;
-            __syncthreads();
-            uint32_t before = incl - sum;
-            for (int w = 0; w < wave; ++w) before += s_wave[w];
+                for (int k = 0; k < RED_UNROLL; ++k) {
+                    // skip empty slices
+                    while (q < np && s_len[q] == 0) q += RED_WAVES;
+                    const bool have = q < np;
+                    const uint32_t len =
+                        have ? (uint32_t)__builtin_amdgcn_readfirstlane(s_len[q]) : 0u;
+                    live[k] = have && o + lane < len;
+                    pos[k] = have ? s_start[q] + o + lane : 0;
+                    if (have) {
+                        o += WAVE;
+                        if (o >= len) { q += RED_WAVES; o = 0; }
+                    }
+                }
+                uint32_t index[RED_UNROLL];
+                float value[RED_UNROLL];
 #pragma unroll
-            for (int j = 0; j < RED_CHUNKS / RED_BLOCK; ++j) {
-                const uint32_t q = tid * (RED_CHUNKS / RED_BLOCK) + j;
-                before += c[j];
-                if (q < np) s_prefix[q + 1] = before;
+                for (int k = 0; k < RED_UNROLL; ++k) {
+                    if (live[k]) {
+                        index[k] = idx_cat[pos[k]];
+                        if (VALUES) value[k] = val_cat[pos[k]];
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < RED_UNROLL; ++k)
+                    if (live[k]) body(index[k], VALUES ? value[k] : 0.0f);
             }
         }
+    };
+    using Yes = std::true_type;      // sweep needs the values too
+    using No = std::false_type;      // sweep needs the indices only
+
+    // Both waves of the chained scan; every thread gets the count of all tiles
+    // before this one.
+    auto place_tile = [&](uint32_t count) -> uint32_t {
+        const uint32_t group = tile / SCAN_GROUP;
+        if (wave == 0) {
+            const uint32_t before = scan_within_group(hdr, tile_desc, group_desc, tile, count);
+            if (lane == 0) s_before[0] = before;
+        } else if (wave == 1) {
+            const uint32_t before = scan_across_groups(hdr, group_desc, group);
+            if (lane == 0) s_before[1] = before;
+        }
         __syncthreads();
-        const uint32_t total = s_prefix[np];
-        for (uint32_t j = tid; j < total; j += RED_BLOCK) {
-            // contribution q with s_prefix[q] <= j < s_prefix[q+1]
-            uint32_t ql = 0, qh = np;
-            while (qh - ql > 1) {
-                const uint32_t mid = (ql + qh) >> 1;
-                if (s_prefix[mid] <= j) ql = mid; else qh = mid;
-            }
-            const uint64_t pos = s_start[ql] + (j - s_prefix[ql]);
-            const uint32_t slot = idx_cat[pos] - a;
-            const double v = (double)val_cat[pos];
-            if (slot >= slots) continue;     // only reachable with unsorted input
-            __hip_atomic_fetch_add(&s_sum[slot], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const uint32_t before = s_before[0] + s_before[1];
+        if (tid == 0 && group != 0 && tile % SCAN_GROUP == SCAN_GROUP - 1)
+            scan_close_group(group_desc, group, before + count);
+        return before;
+    };
+    float* dense = dense_out ? dense_out + (size_t)region * max_width + (size_t)tile * slots
+                             : nullptr;
+    uint32_t distinct, exclusive;
+
+    if (!ranked) {
+        // ---- densely hit region: accumulator = slot, one sweep ----
+        for (uint32_t s = tid; s < RED_C; s += RED_BLOCK) s_sum[s] = 0.0;
+        __syncthreads();
+        for_each_entry(Yes{}, [&](uint32_t index, float x) {
+            const uint32_t slot = index - a;
+            if (slot >= tslots) return;          // only reachable with unsorted input
+            __hip_atomic_fetch_add(&s_sum[slot], (double)x, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
             __hip_atomic_fetch_or(&s_bits[slot >> 5], 1u << (slot & 31), __ATOMIC_RELAXED,
                                   __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
+        });
         __syncthreads();
-    }
-
-    // ---- count, chain, compact ----
-    const int lane = tid & (WAVE - 1), wave = tid >> 6;
-    const uint32_t word = tid < RED_WORDS ? s_bits[tid] : 0u;
-    const uint32_t cnt = __popc(word);
-    const uint32_t incl = wave_inclusive_scan<uint32_t>(cnt);
-    if (lane == WAVE - 1) s_wave[wave] = incl;
-    __syncthreads();
-    uint32_t rank = incl - cnt, aggregate = 0;
-    for (int w = 0; w < RED_BLOCK / WAVE; ++w) {
-        if (w < wave) rank += s_wave[w];
-        aggregate += s_wave[w];
-    }
-    const uint32_t group = tile / SCAN_GROUP;
-    if (wave == 0) {
-        const uint32_t before = scan_within_group(hdr, tile_desc, group_desc, tile, aggregate);
-        if (lane == 0) s_before[0] = before;
-    } else if (wave == 1) {
-        const uint32_t before = scan_across_groups(hdr, group_desc, group);
-        if (lane == 0) s_before[1] = before;
-    }
-    __syncthreads();
-    const uint32_t exclusive = s_before[0] + s_before[1];
-    if (tid == 0 && group != 0 && tile % SCAN_GROUP == SCAN_GROUP - 1)
-        scan_close_group(group_desc, group, exclusive + aggregate);
-    {
-        uint32_t w = word;
-        uint64_t pos = (uint64_t)exclusive + rank;
-        while (w) {
-            const int bit = __ffs(w) - 1;
-            w &= w - 1;
-            const uint32_t slot = (uint32_t)tid * 32u + bit;
-            if (pos < capacity) {
-                idx_out[pos] = a + slot;
-                val_out[pos] = (float)s_sum[slot];
+        distinct = bitmap_prefix(s_bits, s_wprefix, words, s_wave);
+        exclusive = place_tile(distinct);
+        for (uint32_t w = tid; w < words; w += RED_BLOCK) {
+            uint32_t bits = s_bits[w];
+            uint64_t pos = (uint64_t)exclusive + s_wprefix[w];
+            while (bits) {
+                const int bit = __ffs(bits) - 1;
+                bits &= bits - 1;
+                const uint32_t slot = w * 32u + bit;
+                if (pos < capacity) {
+                    idx_out[pos] = a + slot;
+                    val_out[pos] = (float)s_sum[slot];
+                }
+                ++pos;
             }
-            ++pos;
         }
+        if (dense)
+            for (uint32_t s = tid; s < tslots; s += RED_BLOCK) dense[s] = (float)s_sum[s];
+    } else {
+        // ---- sparsely hit region: mark, rank, then sum into accumulator [rank] ----
+        for_each_entry(No{}, [&](uint32_t index, float) {
+            const uint32_t slot = index - a;
+            if (slot < tslots)
+                __hip_atomic_fetch_or(&s_bits[slot >> 5], 1u << (slot & 31), __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_WORKGROUP);
+        });
+        __syncthreads();
+        distinct = bitmap_prefix(s_bits, s_wprefix, words, s_wave);
+        // the count is known before the sums: publish it now, wait for the others later
+        if (tid == 0) scan_publish_early(tile_desc, tile, distinct);
+        exclusive = 0;
+        const uint32_t rounds = (distinct + RED_C - 1) / RED_C;     // 1, unless the estimate was off
+        if (dense) {
+            for (uint32_t s = tid; s < tslots; s += RED_BLOCK) dense[s] = 0.0f;
+            __syncthreads();                     // zeros land before the values below
+        }
+        for (uint32_t round = 0; round < rounds; ++round) {
+            const uint32_t r0 = round * RED_C;                       // first rank of this round
+            if (round) __syncthreads();                              // previous round fully read
+            for (uint32_t s = tid; s < RED_C; s += RED_BLOCK) s_sum[s] = 0.0;
+            __syncthreads();
+            auto add = [&](uint32_t index, float x) {
+                const uint32_t slot = index - a;
+                if (slot >= tslots) return;
+                const uint32_t below = s_bits[slot >> 5] & ((1u << (slot & 31)) - 1u);
+                const uint32_t rank = (uint32_t)s_wprefix[slot >> 5] + (uint32_t)__popc(below) - r0;
+                if (rank < RED_C)
+                    __hip_atomic_fetch_add(&s_sum[rank], (double)x, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+            };
+            for_each_entry(Yes{}, add);
+            __syncthreads();
+            if (round == 0) exclusive = place_tile(distinct);
+            // values: accumulators are already in output order
+            const uint32_t in_round = distinct - r0 < RED_C ? distinct - r0 : RED_C;
+            for (uint32_t k = tid; k < in_round; k += RED_BLOCK) {
+                const uint64_t pos = (uint64_t)exclusive + r0 + k;
+                if (pos < capacity) val_out[pos] = (float)s_sum[k];
+            }
+            // indices (and the dense copy): walk the bitmap
+            for (uint32_t w = tid; w < words; w += RED_BLOCK) {
+                uint32_t bits = s_bits[w];
+                uint32_t rank = s_wprefix[w];
+                while (bits) {
+                    const int bit = __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    const uint32_t slot = w * 32u + bit;
+                    if (rank - r0 < RED_C) {
+                        const uint64_t pos = (uint64_t)exclusive + rank;
+                        if (pos < capacity) idx_out[pos] = a + slot;
+                        if (dense) dense[slot] = (float)s_sum[rank - r0];
+                    }
+                    ++rank;
+                }
+            }
+        }
+        if (rounds == 0) exclusive = place_tile(0u);   // an empty tile is still a link of the chain
     }
-    if (dense_out) {
-        float* dst = dense_out + (size_t)region * max_width + (size_t)tile * RED_TILE;
-        for (uint32_t s = tid; s < slots; s += RED_BLOCK) dst[s] = (float)s_sum[s];
-    }
-    if (tile == ntiles - 1 && tid == 0) {
-        const uint64_t total = (uint64_t)exclusive + aggregate;
+    if (tile == r.ntiles - 1 && tid == 0) {
+        const uint64_t total = (uint64_t)exclusive + distinct;
         const bool failed =
             __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
         nnz[0] = failed ? ~0ull : (total < capacity ? total : capacity);
@@ -194,15 +361,33 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
         !aligned(d_nnz_out, 8) || !aligned(d_idx_out, 4) || !aligned(d_val_out, 4) ||
         !aligned(d_dense, 4) || !aligned(d_lo_hi, 4))
         return OKT_ERR_INVALID_ARG;
-    const size_t region_bytes = reduce_ws_bytes_region(max_width);
+    // the caller's bound on the size of the union doubles as the density estimate
+    const uint32_t slots = reduce_tile_slots(max_width, capacity);
+    const size_t region_bytes = reduce_ws_bytes_region(max_width, P, slots);
+    if (region_bytes > 0xffffffffull) return OKT_ERR_INVALID_ARG;
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < region_bytes * B) return OKT_ERR_WORKSPACE;
-    uint64_t tiles = reduce_tiles(max_width);
+    uint64_t tiles = reduce_tiles(max_width, slots);
     if (tiles == 0) tiles = 1;
-    if (launch_zero_words(d_ws, region_bytes * B / 8, s) != hipSuccess) return OKT_ERR_HIP;
-    hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s, d_idx_cat,
-                       d_val_cat, d_chunk_off, d_lo_hi, lo, hi, P, max_width, d_idx_out,
-                       d_val_out, capacity, d_nnz_out, d_dense, (char*)d_ws,
-                       (uint32_t)region_bytes);
+    const uint32_t table_offset = (uint32_t)(64 + 8 * (tiles + (tiles + 63) / 64));
+    // the scan state of every region (header and descriptors) starts at zero; the
+    // table behind it is fully rewritten
+    {
+        const uint32_t words = table_offset / 8;
+        uint32_t cblocks = (words + 255) / 256;
+        if (cblocks > 64) cblocks = 64;
+        hipLaunchKernelGGL(reduce_clear_kernel, dim3(cblocks, B), dim3(256), 0, s, (char*)d_ws,
+                           (uint32_t)region_bytes, words);
+    }
+    const uint64_t cells = (tiles + 1) * P;
+    uint64_t sblocks = (cells + 255) / 256;
+    if (sblocks > 4096) sblocks = 4096;
+    hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)sblocks, B), dim3(256), 0, s,
+                       d_idx_cat, d_chunk_off, d_lo_hi, lo, hi, P, max_width, slots, (char*)d_ws,
+                       (uint32_t)region_bytes, table_offset);
+    hipLaunchKernelGGL(reduce_tile_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,
+                       d_idx_cat, d_val_cat, d_chunk_off, d_lo_hi, lo, hi, P, max_width, slots,
+                       d_idx_out, d_val_out, capacity, d_nnz_out, d_dense, (char*)d_ws,
+                       (uint32_t)region_bytes, table_offset);
     return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
 }
 

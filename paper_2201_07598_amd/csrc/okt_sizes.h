@@ -61,18 +61,49 @@ inline size_t threshold_ws_bytes(uint64_t n) {
 }
 
 // ---- sparse reduce ----
-constexpr int RED_BLOCK = 256;
-constexpr int RED_TILE = 4096;                 // index slots per workgroup
-constexpr int RED_CHUNKS = 1024;               // contributions handled per sweep
-inline uint64_t reduce_tiles(uint64_t width) { return (width + RED_TILE - 1) / RED_TILE; }
-// per region: a 64-byte header, one descriptor per tile and one per 64 tiles
-inline size_t reduce_ws_bytes_region(uint64_t max_width) {
-    uint64_t t = reduce_tiles(max_width);
-    if (t == 0) t = 1;
-    return 64 + 8 * (size_t)(t + (t + 63) / 64);
+// A workgroup of RED_BLOCK threads owns a tile of `slots` consecutive index
+// slots of the region and sums into RED_C fp64 accumulators in LDS.  In a region
+// that is densely hit a tile is RED_C slots wide and slot = accumulator.  In a
+// sparsely hit region a tile is up to RED_S_MAX slots wide: a first sweep marks
+// the hit slots in a bitmap, the popcount prefix of the bitmap ranks them, and
+// the accumulators are indexed by rank, so the LDS holds hit slots only.
+#ifndef OKT_RED_C
+#define OKT_RED_C 4096
+#endif
+#ifndef OKT_RED_BLOCK
+#define OKT_RED_BLOCK 512
+#endif
+#ifndef OKT_RED_UNROLL
+#define OKT_RED_UNROLL 8
+#endif
+constexpr int RED_BLOCK = OKT_RED_BLOCK;
+constexpr int RED_UNROLL = OKT_RED_UNROLL;      // entries a thread keeps in flight
+constexpr uint32_t RED_C = OKT_RED_C;           // accumulators per tile and round
+constexpr uint32_t RED_S_MAX = 32768;           // widest tile (bits in the bitmap)
+constexpr int RED_CHUNKS = 256;                 // contributions handled per sweep
+
+// Tile width for a region `width` wide whose union is expected to hold at most
+// `expected` entries: the widest power-of-two multiple of RED_C that keeps the
+// expected number of hit slots per tile below 70 % of the accumulators.
+inline uint32_t reduce_tile_slots(uint64_t width, uint64_t expected) {
+    uint32_t slots = RED_C;
+    if (width == 0) return slots;
+    while (slots < RED_S_MAX && slots < width &&
+           (double)(2 * slots) * (double)expected <= 0.7 * RED_C * (double)width)
+        slots *= 2;
+    return slots;
 }
-inline size_t reduce_ws_bytes(uint64_t B, uint64_t max_width) {
-    return (size_t)B * reduce_ws_bytes_region(max_width);
+inline uint64_t reduce_tiles(uint64_t width, uint32_t slots) { return (width + slots - 1) / slots; }
+// per region: a 64-byte header, one descriptor per tile and one per 64 tiles,
+// then the table of slice starts, (tiles + 1) x P uint32, padded to 64 bytes
+inline size_t reduce_ws_bytes_region(uint64_t max_width, uint32_t P, uint32_t slots) {
+    uint64_t t = reduce_tiles(max_width, slots);
+    if (t == 0) t = 1;
+    size_t bytes = 64 + 8 * (size_t)(t + (t + 63) / 64) + 4 * (size_t)(t + 1) * P;
+    return (bytes + 63) & ~(size_t)63;
+}
+inline size_t reduce_ws_bytes(uint64_t B, uint64_t max_width, uint32_t P) {
+    return (size_t)B * reduce_ws_bytes_region(max_width, P, RED_C);     // narrowest tile: largest
 }
 
 }  // namespace okt

@@ -267,6 +267,35 @@ def test_reduce_special_cases():
     check_reduce(idx, val, one, 0, n, capacity=0)
 
 
+def test_reduce_tile_modes():
+    """Wide tiles with accumulators indexed by rank (sparse regions), narrow
+    tiles with accumulator = slot (dense regions), and the several-rounds path
+    taken when a wide tile turns out to hold more hit slots than accumulators."""
+    rng = np.random.default_rng(77)
+    # every slot of a 40,000 wide region hit by each of three contributions
+    idx = np.arange(1000, 41_000, dtype=np.uint32)
+    vals = [lap(70 + p, idx.size) for p in range(3)]
+    off = np.arange(4, dtype=np.uint64) * idx.size
+    cat_i, cat_v = np.tile(idx, 3), np.concatenate(vals)
+    got, _ = check_reduce(cat_i, cat_v, off, 1000, 41_000)               # dense estimate
+    assert got["total"] == 40_000
+    got, _ = check_reduce(cat_i, cat_v, off, 1000, 41_000, capacity=50)  # sparse estimate, dense data
+    assert got["total"] == 40_000 and got["emitted"] == 50
+    got, _ = check_reduce(cat_i, cat_v, off, 500, 70_001, capacity=50)
+    # a sparse region: 3,000 entries over 900,001 slots
+    sp = np.sort(rng.choice(900_001, 1000, replace=False)).astype(np.uint32) + np.uint32(123)
+    parts = [sp, np.sort(rng.choice(900_001, 1000, replace=False)).astype(np.uint32) + np.uint32(123), sp]
+    sv = [lap(80 + p, 1000) for p in range(3)]
+    got, ref = check_reduce(np.concatenate(parts), np.concatenate(sv),
+                            np.arange(4, dtype=np.uint64) * 1000, 123, 900_124)
+    assert 1000 < got["total"] <= 2000
+    # clustered entries inside a region estimated sparse: one tile overflows its accumulators
+    cl = np.concatenate([np.arange(200_000, 209_000), rng.choice(800_000, 500, replace=False) + 300_000])
+    cl = np.sort(np.unique(cl)).astype(np.uint32)
+    got, _ = check_reduce(cl, lap(90, cl.size), np.array([0, cl.size], np.uint64), 0, 1_200_000)
+    assert got["total"] == cl.size
+
+
 def test_reduce_disjoint_contributions_fill_in():
     # non-overlapping indexes: the union is the sum of the sizes and every value
     # is a bit copy (the fill-in arithmetic of the paper's Introduction)
@@ -307,7 +336,7 @@ def test_reduce_batch_matches_single_regions():
     out_val = torch.zeros(B * cap, dtype=torch.float32, device=DEV)
     nnz = torch.zeros(2 * B, dtype=torch.int64, device=DEV)
     dense = torch.full((B * width,), 3.0, dtype=torch.float32, device=DEV)
-    ws = workspace(okt.okt_sparse_reduce_batch_workspace_bytes(B, width))
+    ws = workspace(okt.okt_sparse_reduce_batch_workspace_bytes(B, P, width))
     okt.okt_sparse_reduce_batch(to_dev(idx_cat), to_dev(val_cat), to_dev(np.concatenate(offs)),
                                 to_dev(np.array(lohi, dtype=np.uint32)), B, P, width,
                                 out_idx, out_val, cap, nnz, ws, dense_out=dense)
