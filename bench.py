@@ -176,7 +176,7 @@ def main():
     calls_per_step = {"accumulate": ITERS_PER_STEP, "threshold": 1, "select": ITERS_PER_STEP,
                       "partition": 1, "reduce": ITERS_PER_STEP}
     if warm:
-        dominant = max(warm, key=lambda c: warm[c][0] * calls_per_step[c])
+        dominant = max(warm, key=lambda c: warm[c][1] * calls_per_step[c])   # by median
     else:
         dominant = "accumulate"
     for c in CALLS:
