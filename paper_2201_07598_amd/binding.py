@@ -118,6 +118,8 @@ def _u32(torch):
 
 def okt_residual_accumulate(grad, residual_inout, lr: float, stream=None) -> None:
     torch = _torch()
+    _ptr(residual_inout, torch.float32, "residual_inout")
+    _ptr(grad, torch.float32, "grad")
     n = residual_inout.numel()
     if grad.numel() != n:
         raise ValueError("grad and residual must have the same length")

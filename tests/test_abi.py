@@ -1,0 +1,74 @@
+"""The C ABI: the built library loads without a GPU, exports every function that
+include/okt.h declares, the Python binding mirrors the header, and argument
+errors are caught on the host before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2201_07598_amd as okt
+from paper_2201_07598_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "okt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(okt_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    lib = okt.load_library()
+    names = declared_functions()
+    assert {"okt_residual_accumulate", "okt_topk_threshold_exact", "okt_threshold_select",
+            "okt_region_partition", "okt_sparse_reduce"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_mirrors_the_header():
+    assert sorted(binding.SIGNATURES) == declared_functions()
+    for name in binding.SIGNATURES:
+        assert callable(getattr(okt, name)), name
+
+
+def test_status_strings_and_version():
+    assert okt.okt_version() >= 100
+    assert okt.okt_status_string(0) == "ok"
+    for code in (-1, -2, -3, -99):
+        assert okt.okt_status_string(code)
+
+
+def test_workspace_sizes_are_monotone_and_aligned():
+    sizes = [okt.okt_workspace_bytes(n, 16) for n in (1, 1 << 20, 25_557_032, 336_000_000)]
+    assert sizes == sorted(sizes) and all(s % 256 == 0 and s > 0 for s in sizes)
+    assert okt.okt_workspace_bytes(1 << 20, 256) >= okt.okt_workspace_bytes(1 << 20, 4)
+    assert okt.okt_sparse_reduce_batch_workspace_bytes(8, 16, 100_000) >= \
+        8 * (okt.okt_sparse_reduce_batch_workspace_bytes(1, 16, 100_000) - 256)
+
+
+def test_argument_errors_are_found_on_the_host():
+    lib = okt.load_library()
+    INVALID, WORKSPACE = -1, -2
+    null = ctypes.c_void_p(None)
+    fake = ctypes.c_void_p(0x1000)          # aligned, never dereferenced on these paths
+    odd = ctypes.c_void_p(0x1004)           # not 16-byte aligned
+    assert lib.okt_residual_accumulate(null, null, 1.0, 0, null) == 0          # n = 0: no-op
+    assert lib.okt_residual_accumulate(null, fake, 1.0, 8, null) == INVALID
+    assert lib.okt_residual_accumulate(fake, odd, 1.0, 8, null) == INVALID
+    assert lib.okt_residual_accumulate(fake, fake, 1.0, 1 << 32, null) == INVALID
+    assert lib.okt_topk_threshold_exact(fake, 10, 0, fake, fake, fake, 1 << 20, null) == INVALID   # k = 0
+    assert lib.okt_topk_threshold_exact(fake, 10, 11, fake, fake, fake, 1 << 20, null) == INVALID  # k > n
+    assert lib.okt_topk_threshold_exact(fake, 10, 5, fake, fake, fake, 64, null) == WORKSPACE
+    assert lib.okt_topk_threshold_exact(fake, 10, 5, fake, fake, null, 1 << 20, null) == WORKSPACE
+    assert lib.okt_threshold_select(fake, 10, null, fake, fake, 4, fake, fake, 1 << 20, null) == INVALID
+    assert lib.okt_threshold_select(fake, 1 << 20, fake, fake, fake, 4, fake, fake, 8, null) == WORKSPACE
+    assert lib.okt_region_partition(fake, fake, 0, 4, fake, fake, null) == INVALID          # n = 0
+    assert lib.okt_region_partition(fake, fake, 100, 0, fake, fake, null) == INVALID        # R = 0
+    assert lib.okt_sparse_reduce(fake, fake, fake, 0, 0, 10, fake, fake, 4, fake, null, fake, 1 << 20, null) == INVALID
+    assert lib.okt_sparse_reduce(fake, fake, fake, 4, 20, 10, fake, fake, 4, fake, null, fake, 1 << 20, null) == INVALID
+    assert lib.okt_sparse_reduce(fake, fake, fake, 4, 0, 1 << 20, fake, fake, 4, fake, null, fake, 64, null) == WORKSPACE
+    with pytest.raises(TypeError):
+        okt.okt_residual_accumulate(None, None, 1.0)
