@@ -1,0 +1,107 @@
+"""GPU parity at the full sizes of the five configurations, through the same
+entry points and launch shapes bench.py times.  The oracle still checks every
+element (numpy handles these lengths in seconds); only the number of iterations
+is cut where the full schedule would take minutes of host time."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2201_07598_amd as okt
+import workloads as wl
+from oracle import okt_oracle as orc
+from tests.okt_harness import (DEV, GpuPath, bits_equal, gpu_reduce, reduce_tolerance, to_dev,
+                               u32, u64)
+
+pytestmark = pytest.mark.gpu
+
+
+def loop(w, iterations):
+    gpu = GpuPath(w.n, 4 * w.k)
+    res = np.zeros(w.n, dtype=np.float32)
+    th = None
+    ridx = None
+    for it in range(iterations):
+        g = wl.gradient(w, it)
+        gpu.accumulate(to_dev(g), w.lr)
+        acc = orc.residual_accumulate(g, res, w.lr)
+        del g
+        if w.refresh(it):
+            gpu.threshold(w.k)
+            th, cnt = orc.topk_threshold_exact(acc, w.k, method="partition")
+            assert gpu.th.cpu().numpy().view(np.uint32)[0] == np.float32(th).view(np.uint32), it
+            assert int(u64(gpu.count_ge)[0]) == cnt, it
+        gpu.select()
+        ridx, rval, res, total = orc.threshold_select(acc, th, capacity=4 * w.k)
+        del acc
+        idx, val, emitted, gtotal = gpu.selected()
+        assert (emitted, gtotal) == (ridx.size, total), it
+        assert np.array_equal(idx, ridx) and bits_equal(val, rval), it
+        assert bits_equal(gpu.residual.cpu().numpy(), res), it
+        if w.refresh(it):
+            assert total == cnt
+        print(f"{w.name} it={it} nnz={total} |nnz-k|/k={abs(total - w.k) / w.k:.4f}", flush=True)
+    return gpu, ridx
+
+
+def check_partition(gpu, ridx, n, R):
+    b = torch.zeros(R + 1, dtype=torch.int32, device=DEV)
+    off = torch.zeros(R + 1, dtype=torch.int64, device=DEV)
+    okt.okt_region_partition(gpu.idx, gpu.nnz, n, R, b, off)
+    rb, roff = orc.region_partition(ridx, n, R)
+    assert np.array_equal(u32(b), rb) and np.array_equal(u64(off), roff)
+    return rb
+
+
+def check_reduce(idx, val, off, lo, hi):
+    got = gpu_reduce(idx, val, off, lo, hi)
+    ref = orc.sparse_reduce(idx, val, off, lo, hi)
+    assert got["total"] == got["emitted"] == ref["idx"].size
+    assert np.array_equal(got["idx"], ref["idx"])
+    err = np.abs(got["val"].astype(np.float64) - ref["val"].astype(np.float64))
+    assert np.all(err <= reduce_tolerance(ref))
+    tol = np.zeros(hi - lo)
+    tol[ref["idx"].astype(np.int64) - lo] = reduce_tolerance(ref)
+    assert np.all(np.abs(got["dense"].astype(np.float64) - ref["dense"]) <= tol)
+    return ref
+
+
+@pytest.mark.timeout(300)
+def test_cfg2_full_size():
+    w = wl.WORKLOADS["cfg2"]
+    gpu, ridx = loop(w, 3)                      # exact threshold at 0, reused at 1 and 2
+    check_partition(gpu, ridx, w.n, w.P)
+    lo, hi = 0, w.n // w.P                      # the region bench.py reduces
+    ref = check_reduce(*wl.contributions(w, lo, hi), lo, hi)
+    assert ref["idx"].size > 0.9 * w.P * w.m
+
+
+@pytest.mark.timeout(300)
+def test_cfg3_full_size():
+    w = wl.WORKLOADS["cfg3"]
+    gpu, ridx = loop(w, 2)
+    rb = check_partition(gpu, ridx, w.n, w.P)
+    lo, hi = w.n // w.P, 2 * (w.n // w.P)
+    ref = check_reduce(*wl.contributions(w, lo, hi), lo, hi)
+    # 30 % of each worker's entries are one shared pool: they collide P ways
+    assert ref["hits"].max() == w.P and int(ref["idx"].size) < w.P * w.m
+
+
+@pytest.mark.timeout(600)
+def test_cfg4_full_size():
+    w = wl.WORKLOADS["cfg4"]
+    gpu, ridx = loop(w, 2)                      # exact radix select in both iterations
+    rb = check_partition(gpu, ridx, w.n, 64).astype(np.int64)
+    widths = np.diff(rb)
+    r = int(np.argmax(widths))                  # the widest region
+    lo, hi = int(rb[r]), int(rb[r + 1])
+    check_reduce(*wl.contributions(w, lo, hi), lo, hi)
+
+
+@pytest.mark.timeout(300)
+def test_cfg5_full_size():
+    w = wl.WORKLOADS["cfg5"]
+    width = -(-w.n // w.P)                      # one GPU's region of a 256-GPU job
+    lo = 128 * width
+    idx, val, off = wl.contributions(w, lo, lo + width)
+    ref = check_reduce(idx, val, off, lo, lo + width)
+    assert ref["hits"].max() > 64               # hot indices collide across most workers
