@@ -79,7 +79,10 @@ inline size_t threshold_ws_bytes(uint64_t n) {
 constexpr int RED_BLOCK = OKT_RED_BLOCK;
 constexpr int RED_UNROLL = OKT_RED_UNROLL;      // entries a thread keeps in flight
 constexpr uint32_t RED_C = OKT_RED_C;           // accumulators per tile and round
-constexpr uint32_t RED_S_MAX = 32768;           // widest tile (bits in the bitmap)
+#ifndef OKT_RED_S_MAX
+#define OKT_RED_S_MAX 32768
+#endif
+constexpr uint32_t RED_S_MAX = OKT_RED_S_MAX;   // widest tile (bits in the bitmap)
 constexpr int RED_CHUNKS = 256;                 // contributions handled per sweep
 
 // Tile width for a region `width` wide whose union is expected to hold at most
