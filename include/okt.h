@@ -80,7 +80,7 @@ int okt_residual_accumulate(const float* d_grad, float* d_residual_inout, float 
  *   d_count_ge_out   out  uint64[1] #{i : key(acc[i]) >= key(th)}  (>= k; > k
  *                                   only when values tie with the k-th)
  * Integer work only: the result is exact and run-to-run identical.
- * Workspace: okt_workspace_bytes(n, 0); a smaller one (>= 32 KiB) still gives
+ * Workspace: okt_workspace_bytes(n, 0); a smaller one (>= 64 KiB) still gives
  * the same result, with more passes over d_acc.
  */
 int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t k,

@@ -36,13 +36,19 @@ constexpr uint32_t SEL_PIECE_MAX = 16384;
 constexpr uint32_t SEL_TARGET_WGS = OKT_SEL_TARGET_WGS;
 
 struct SelectShape { uint32_t nseg, piece; };
-inline SelectShape select_shape(uint64_t n) {
-    uint64_t per_wave = (n + (uint64_t)SEL_TARGET_WGS * SEL_WAVES - 1) / ((uint64_t)SEL_TARGET_WGS * SEL_WAVES);
-    uint64_t piece = (per_wave + SEL_ROUND - 1) / SEL_ROUND * SEL_ROUND;
-    if (piece < SEL_ROUND) piece = SEL_ROUND;
-    if (piece > SEL_PIECE_MAX) piece = SEL_PIECE_MAX;
-    const uint64_t per_wg = piece * SEL_WAVES;
+// Pieces of a multiple of `round` elements, one per wave, `waves` per workgroup,
+// about `target_wgs` workgroups, no piece above `piece_max`.
+inline SelectShape select_shape_for(uint64_t n, int waves, uint32_t round,
+                                    uint32_t target_wgs = 512, uint32_t piece_max = 1u << 20) {
+    uint64_t per_wave = (n + (uint64_t)target_wgs * waves - 1) / ((uint64_t)target_wgs * waves);
+    uint64_t piece = (per_wave + round - 1) / round * round;
+    if (piece < round) piece = round;
+    if (piece > piece_max) piece = piece_max;
+    const uint64_t per_wg = piece * waves;
     return SelectShape{(uint32_t)((n + per_wg - 1) / per_wg), (uint32_t)piece};
+}
+inline SelectShape select_shape(uint64_t n) {
+    return select_shape_for(n, SEL_WAVES, SEL_ROUND, SEL_TARGET_WGS, SEL_PIECE_MAX);
 }
 inline size_t select_ws_bytes(uint64_t n) {       // header, segment and group descriptors
     const uint64_t t = select_shape(n).nseg;
@@ -53,10 +59,12 @@ inline size_t select_ws_bytes(uint64_t n) {       // header, segment and group d
 constexpr int RS_BITS1 = 11, RS_BITS2 = 11, RS_BITS3 = 9;   // 11 + 11 + 9 = 31
 constexpr int RS_MAX_BINS = 1 << 11;
 constexpr size_t RS_STATE_BYTES = 256;
-constexpr size_t RS_HIST_BYTES = 3 * RS_MAX_BINS * sizeof(uint32_t);
+constexpr size_t RS_HIST_BYTES = 4 * RS_MAX_BINS * sizeof(uint32_t);   // sample + three digits
+constexpr uint64_t RS_SAMPLE_MIN_N = 4u << 20;   // shorter vectors are simply read three times
+constexpr uint64_t RS_SAMPLE_BLOCKS = 1024;      // sample: about this many blocks of 1024 elements
 inline size_t threshold_ws_min_bytes() { return RS_STATE_BYTES + RS_HIST_BYTES; }
 inline size_t threshold_ws_bytes(uint64_t n) {
-    // state + three histograms + room for the keys that survive the first digit
+    // state + histograms + room for the candidate keys (a few percent of the vector)
     return threshold_ws_min_bytes() + 4 * (size_t)(n / 8 + 1024);
 }
 

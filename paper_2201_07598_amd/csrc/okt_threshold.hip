@@ -1,74 +1,93 @@
 // okt_topk_threshold_exact: the exact k-th largest |acc| (Algorithm 1, lines
-// 2-4, th_re_evaluate; Sec. 3.1.3).  The paper sorts; this is an exact MSD
-// radix select over the 31-bit magnitude key, digits of 11 + 11 + 9 bits, most
-// significant first (the first digit is the exponent and three mantissa bits).
+// 2-4, th_re_evaluate; Sec. 3.1.3).  The paper sorts; this is an exact
+// selection on the 31-bit magnitude key that reads the vector about once.
 //
-// Per digit: one streaming pass builds a histogram of that digit over the keys
-// that match the digits found so far (LDS histogram per workgroup, flushed with
-// one global atomic per non-empty bin), then one small workgroup walks the
-// histogram from the top to find the bin that holds rank k.  All counts are
-// integers, so the result is exact and independent of scheduling.  State lives
-// in the workspace on the device; the host never waits.
+//   1. A histogram of the first digit (exponent and three mantissa bits) over a
+//      strided sample of about a million elements gives a key that lies, with a
+//      wide margin, below the k-th largest one.
+//   2. One streaming pass over the whole vector copies every key at or above
+//      that bound, a little more than k of them, to the workspace (the select
+//      kernel's loop: one compare per element, per-wave LDS stash, one global
+//      atomic per flush).
+//   3. If at least k keys were collected (always, unless the sample misled),
+//      rank k is among them, and an exact MSD radix select, digits of
+//      11 + 11 + 9 bits, runs over the candidates only.  Otherwise, or when the
+//      vector is short or the workspace small, the same radix select runs over
+//      the whole vector (three more passes).
+// Either way the answer is the exact order statistic: all arithmetic is integer
+// counting, the sample only decides how much is read.  State lives in the
+// workspace on the device; the host never waits.
 #include "okt_device.h"
+#include "okt_select_kernel.h"
 #include "okt_sizes.h"
 
 namespace okt {
 
 struct RadixState {
     uint32_t prefix;       // digits found so far (the high bits of the answer)
-    uint32_t pad;
+    uint32_t use_cand;     // 1: the radix passes run over the candidate keys
     uint64_t k_rem;        // rank still to find inside the current prefix
     uint64_t above;        // keys strictly above the current prefix
+    uint64_t m;            // number of 32-bit words the radix passes run over
+    uint32_t cand_lo;      // every key >= cand_lo is a candidate
+    uint32_t pad;
+    unsigned long long cand_count;    // number of candidates found by the counting pass
 };
+static_assert(sizeof(RadixState) <= RS_STATE_BYTES, "state fits its slot");
 
 constexpr int HIST_BLOCK = 256;
 constexpr int HIST_ITERS = 4;                              // float4 per thread per step
 constexpr int HIST_STEP4 = HIST_BLOCK * HIST_ITERS;        // float4 per workgroup per step
 
-// One digit pass over the keys.  SHIFT/BITS select the digit; keys take part if
-// their bits above the digit equal state->prefix (always, for the first digit).
+// ---------------------------------------------------------------------------
+// radix passes (over the candidates, or over the whole vector)
+// ---------------------------------------------------------------------------
+// One digit pass.  SHIFT/BITS select the digit; a key takes part if its bits
+// above the digit equal state->prefix (always, for the first digit).  The source
+// is the candidate array or the vector itself, as the state says; both are
+// arrays of 32-bit words whose low 31 bits are the key.
 template <int SHIFT, int BITS, bool FIRST>
 __global__ __launch_bounds__(HIST_BLOCK) void radix_hist_kernel(
-    const float* __restrict__ acc, uint32_t n, const RadixState* __restrict__ state,
-    uint32_t* __restrict__ hist) {
+    const float* __restrict__ acc, const uint32_t* __restrict__ cand,
+    const RadixState* __restrict__ state, uint32_t* __restrict__ hist) {
     constexpr int BINS = 1 << BITS;
     __shared__ uint32_t s_hist[BINS];
+    const uint32_t* src = state->use_cand ? cand : reinterpret_cast<const uint32_t*>(acc);
+    const uint32_t m = (uint32_t)state->m;
+    const uint32_t m4 = m >> 2;
+    uint32_t base4 = blockIdx.x * (uint32_t)HIST_STEP4;
+    if (base4 >= m4 && !(blockIdx.x == 0)) return;          // nothing for this workgroup
     for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) s_hist[b] = 0;
     const uint32_t prefix = FIRST ? 0u : state->prefix;
     __syncthreads();
 
-    auto take = [&](float x) {
-        const uint32_t key = magnitude_key(x);
+    auto take = [&](uint32_t word) {
+        const uint32_t key = word & ABS_MASK;
         if (FIRST || (key >> (SHIFT + BITS)) == prefix)
             atomicAdd(&s_hist[(key >> SHIFT) & (BINS - 1)], 1u);
     };
-
-    const uint32_t n4 = n >> 2;
-    const float4* src = reinterpret_cast<const float4*>(acc);
+    const uint4* src4 = reinterpret_cast<const uint4*>(src);
     const uint32_t stride = gridDim.x * (uint32_t)HIST_STEP4;
-    uint32_t base4 = blockIdx.x * (uint32_t)HIST_STEP4;
-    // n4 < 2^30 and stride <= 2^21, so base4 never wraps
-    for (; base4 + HIST_STEP4 <= n4; base4 += stride) {
-        float4 v[HIST_ITERS];
+    // m4 < 2^30 and stride <= 2^21, so base4 never wraps
+    for (; base4 + HIST_STEP4 <= m4; base4 += stride) {
+        uint4 v[HIST_ITERS];
 #pragma unroll
-        for (int it = 0; it < HIST_ITERS; ++it) v[it] = src[base4 + it * HIST_BLOCK + threadIdx.x];
+        for (int it = 0; it < HIST_ITERS; ++it) v[it] = src4[base4 + it * HIST_BLOCK + threadIdx.x];
 #pragma unroll
         for (int it = 0; it < HIST_ITERS; ++it) {
             take(v[it].x); take(v[it].y); take(v[it].z); take(v[it].w);
         }
     }
-    // ragged remainder: at most one partial step, owned by the workgroup whose
-    // walk lands on it
-    if (base4 < n4) {
+    if (base4 < m4) {       // ragged remainder: one partial step, owned by one workgroup
         for (int it = 0; it < HIST_ITERS; ++it) {
             const uint32_t i = base4 + it * HIST_BLOCK + threadIdx.x;
-            if (i < n4) {
-                const float4 x = src[i];
+            if (i < m4) {
+                const uint4 x = src4[i];
                 take(x.x); take(x.y); take(x.z); take(x.w);
             }
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x < (n & 3u)) take(acc[(n4 << 2) + threadIdx.x]);
+    if (blockIdx.x == 0 && threadIdx.x < (m & 3u)) take(src[(m4 << 2) + threadIdx.x]);
     __syncthreads();
     for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) {
         const uint32_t c = s_hist[b];
@@ -76,29 +95,48 @@ __global__ __launch_bounds__(HIST_BLOCK) void radix_hist_kernel(
     }
 }
 
-// Walk one histogram from the top bin down to the bin that holds rank k_rem.
+// Find the bin that holds rank k_rem counting from the top bin down: 256 threads,
+// thread t owns the PER bins below the (t * PER) highest ones; an inclusive scan
+// over the threads' sums names the owner, who walks its own few bins.  The
+// owner (exactly one thread) stores (bin, keys above the bin) to s_result.
+template <int BITS>
+__device__ __forceinline__ void pick_bin(const uint32_t* __restrict__ hist, uint64_t k_rem,
+                                         uint64_t* s_wave_total, uint64_t* s_result) {
+    constexpr int BINS = 1 << BITS;
+    constexpr int PER = BINS / 256;                  // bins per thread (8 or 2)
+    const int t = threadIdx.x, lane = t & (WAVE - 1), wave = t >> 6;
+    uint32_t c[PER];
+    uint64_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        c[j] = hist[BINS - 1 - (t * PER + j)];       // j = 0 is the thread's highest bin
+        mine += c[j];
+    }
+    const uint64_t incl = wave_inclusive_scan<uint64_t>(mine);
+    if (lane == WAVE - 1) s_wave_total[wave] = incl;
+    __syncthreads();
+    uint64_t before = incl - mine;
+    for (int w = 0; w < wave; ++w) before += s_wave_total[w];
+    if (before < k_rem && k_rem <= before + mine) {  // true for exactly one thread
+        uint64_t above = before;
+        int j = 0;
+        while (j < PER - 1 && above + c[j] < k_rem) above += c[j++];
+        s_result[0] = (uint64_t)(BINS - 1 - (t * PER + j));
+        s_result[1] = above;                         // above < k_rem <= above + hist[bin]
+    }
+    __syncthreads();
+}
+
 template <int BITS, bool LAST>
 __global__ __launch_bounds__(256) void radix_pick_kernel(
     RadixState* state, const uint32_t* __restrict__ hist, float* threshold_out,
     uint64_t* count_ge_out) {
-    constexpr int BINS = 1 << BITS;
-    constexpr int PER = BINS / 256;                  // bins per thread (8 or 2)
-    __shared__ uint64_t s_part[256];
-    const int t = threadIdx.x;
-    // thread t owns bins [BINS - (t+1)*PER, BINS - t*PER): thread 0 the top ones
-    uint64_t mine = 0;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) mine += hist[BINS - 1 - (t * PER + j)];
-    s_part[t] = mine;
-    __syncthreads();
-    if (t != 0) return;
+    __shared__ uint64_t s_wave_total[4], s_result[2];
     const uint64_t k_rem = state->k_rem;
-    uint64_t above = 0;
-    int owner = 0;
-    while (owner < 255 && above + s_part[owner] < k_rem) above += s_part[owner++];
-    int bin = BINS - 1 - owner * PER;
-    for (int j = 0; j < PER - 1 && above + hist[bin] < k_rem; ++j) above += hist[bin--];
-    // now above < k_rem <= above + hist[bin]
+    pick_bin<BITS>(hist, k_rem, s_wave_total, s_result);
+    if (threadIdx.x != 0) return;
+    const int bin = (int)s_result[0];
+    const uint64_t above = s_result[1];
     const uint32_t prefix = (state->prefix << BITS) | (uint32_t)bin;
     state->prefix = prefix;
     state->k_rem = k_rem - above;
@@ -109,14 +147,155 @@ __global__ __launch_bounds__(256) void radix_pick_kernel(
     }
 }
 
-__global__ void radix_init_kernel(RadixState* state, uint32_t* hist, uint64_t k) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 3 * RS_MAX_BINS) hist[i] = 0;
+// ---------------------------------------------------------------------------
+// sampling, candidate range, counting pass
+// ---------------------------------------------------------------------------
+// First-digit histogram over every `stride`-th block of 1024 elements.  A
+// workgroup takes SAMPLE_PER_WG sampled blocks with all their loads in flight,
+// so that few workgroups (few global atomics per hot bin) still cover the
+// sample at memory latency.
+constexpr int SAMPLE_PER_WG = 8;
+__global__ __launch_bounds__(HIST_BLOCK) void sample_hist_kernel(
+    const float* __restrict__ acc, uint32_t nblocks_sampled, uint32_t stride,
+    uint32_t* __restrict__ hist) {
+    constexpr int BINS = 1 << RS_BITS1;
+    __shared__ uint32_t s_hist[BINS];
+    for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) s_hist[b] = 0;
+    __syncthreads();
+    // sampled blocks are whole: the host only samples the first floor(n/1024) blocks
+    float4 v[SAMPLE_PER_WG];
+#pragma unroll
+    for (int u = 0; u < SAMPLE_PER_WG; ++u) {
+        const uint32_t j = blockIdx.x * SAMPLE_PER_WG + u;
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j < nblocks_sampled)
+            v[u] = reinterpret_cast<const float4*>(acc)[(size_t)j * stride * 256 + threadIdx.x];
+    }
+#pragma unroll
+    for (int u = 0; u < SAMPLE_PER_WG; ++u) {
+        if (blockIdx.x * SAMPLE_PER_WG + u < nblocks_sampled) {
+            atomicAdd(&s_hist[magnitude_key(v[u].x) >> 20], 1u);
+            atomicAdd(&s_hist[magnitude_key(v[u].y) >> 20], 1u);
+            atomicAdd(&s_hist[magnitude_key(v[u].z) >> 20], 1u);
+            atomicAdd(&s_hist[magnitude_key(v[u].w) >> 20], 1u);
+        }
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) {
+        const uint32_t c = s_hist[b];
+        if (c) atomicAdd(&hist[b], c);
+    }
+}
+
+// From the sample histogram: the first-digit bin that holds the sample rank
+// k' + margin, k' = k * sample / n.  Every key from the bottom of that bin up is
+// a candidate.
+__global__ __launch_bounds__(256) void sample_range_kernel(RadixState* state,
+                                                           const uint32_t* __restrict__ hist,
+                                                           uint64_t sample, uint64_t n, uint64_t k) {
+    __shared__ uint64_t s_wave_total[4], s_result[2];
+    // k' rounded up; margin of 16 standard deviations of a binomial count, and some
+    const uint64_t kp = (k * sample + n - 1) / n;      // k, sample < 2^32: no overflow
+    uint64_t margin = 64;
+    while (margin * margin < 256 * kp) margin += margin / 2 + 1;     // ~ 16 sqrt(k')
+    uint64_t r_lo = kp + margin;                                     // a sample rank safely below the target
+    if (r_lo > sample) r_lo = sample;
+    pick_bin<RS_BITS1>(hist, r_lo, s_wave_total, s_result);
+    const uint32_t bin_lo = (uint32_t)s_result[0];
+    if (threadIdx.x != 0) return;
+    state->cand_lo = bin_lo << 20;
+}
+
+constexpr int CNT_BLOCK = 1024;
+constexpr int CNT_WAVES = CNT_BLOCK / WAVE;
+constexpr int CNT_STASH = 1024;                  // keys per wave between flushes
+constexpr int CNT_U = 4;
+
+// The counting pass: one contiguous piece per wave, as in the select kernel,
+// with the same one-compare-per-element test.  Every key at or above cand_lo is
+// a candidate and is copied to `cand`, in any order (per-wave LDS stash, one
+// global atomic per flush).
+template <typename Test>
+__device__ __forceinline__ void collect_body(const float* __restrict__ acc, uint32_t n,
+                                             uint32_t piece, RadixState* state,
+                                             uint32_t* __restrict__ cand, uint64_t cand_cap,
+                                             Test test, uint32_t (*s_stash)[CNT_STASH]) {
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint64_t start = ((uint64_t)blockIdx.x * CNT_WAVES + wave) * piece;
+    const uint64_t end = start + piece < n ? start + piece : n;
+    uint32_t* mine = s_stash[wave];
+    uint32_t stashed = 0;                        // wave-uniform
+
+    auto flush = [&]() {
+        if (stashed == 0) return;
+        unsigned long long base = 0;
+        if (lane == 0) base = atomicAdd(&state->cand_count, (unsigned long long)stashed);
+        base = __shfl(base, 0, WAVE);
+        for (uint32_t j = lane; j < stashed; j += WAVE)
+            if (base + j < cand_cap) cand[base + j] = mine[j];
+        stashed = 0;
+    };
+    auto round = [&](const float4& v, bool cx, bool cy, bool cz, bool cw) {
+        if (stashed > (uint32_t)(CNT_STASH - 256)) flush();     // room for a whole round
+        stashed = select_round(0u, v, cx, cy, cz, cw, stashed,
+                               [&](uint32_t rank, uint32_t, float x) { mine[rank] = magnitude_key(x); });
+    };
+
+    uint64_t r = start;
+    for (; r + 256 * CNT_U <= end; r += 256 * CNT_U) {
+        const float4* src = reinterpret_cast<const float4*>(acc + r) + lane;
+        float4 v[CNT_U];
+#pragma unroll
+        for (int u = 0; u < CNT_U; ++u) v[u] = src[u * WAVE];
+#pragma unroll
+        for (int u = 0; u < CNT_U; ++u)
+            round(v[u], test(v[u].x), test(v[u].y), test(v[u].z), test(v[u].w));
+    }
+    for (; r < end; r += 256) {
+        const uint64_t i = r + 4u * (uint32_t)lane;
+        float e[4];
+        bool c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool inside = i + j < end;
+            e[j] = inside ? acc[i + j] : 0.0f;
+            c[j] = inside && test(e[j]);
+        }
+        round(make_float4(e[0], e[1], e[2], e[3]), c[0], c[1], c[2], c[3]);
+    }
+    flush();
+}
+
+__global__ __launch_bounds__(CNT_BLOCK) void collect_kernel(
+    const float* __restrict__ acc, uint32_t n, uint32_t piece, RadixState* state,
+    uint32_t* __restrict__ cand, uint64_t cand_cap) {
+    __shared__ uint32_t s_stash[CNT_WAVES][CNT_STASH];
+    const float lo = __uint_as_float(state->cand_lo);       // a key below the Inf/NaN range, or NaN
+    if (lo == lo)
+        collect_body(acc, n, piece, state, cand, cand_cap, TestFloat{lo}, s_stash);
+    else
+        collect_body(acc, n, piece, state, cand, cand_cap, TestKey{state->cand_lo}, s_stash);
+}
+
+// Decide what the radix passes run over.
+__global__ void radix_setup_kernel(RadixState* state, uint64_t n, uint64_t k, uint64_t cand_cap,
+                                   int sampled) {
+    const uint64_t cand = state->cand_count;        // keys at or above cand_lo
+    const bool ok = sampled && k <= cand && cand <= cand_cap;   // rank k is among them
+    state->use_cand = ok ? 1u : 0u;
+    state->m = ok ? cand : n;
+    state->k_rem = k;
+    state->above = 0;
+    state->prefix = 0;
+}
+
+__global__ void radix_init_kernel(RadixState* state, uint32_t* hist, uint32_t words) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) hist[i] = 0;
     if (i == 0) {
-        state->prefix = 0;
-        state->pad = 0;
-        state->k_rem = k;
-        state->above = 0;
+        RadixState z = {};
+        *state = z;
     }
 }
 
@@ -134,25 +313,51 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < threshold_ws_min_bytes())
         return OKT_ERR_WORKSPACE;
     RadixState* state = (RadixState*)d_ws;
-    uint32_t* hist1 = (uint32_t*)((char*)d_ws + RS_STATE_BYTES);
+    uint32_t* hist_sample = (uint32_t*)((char*)d_ws + RS_STATE_BYTES);
+    uint32_t* hist1 = hist_sample + RS_MAX_BINS;
     uint32_t* hist2 = hist1 + RS_MAX_BINS;
     uint32_t* hist3 = hist2 + RS_MAX_BINS;
+    uint32_t* cand = hist3 + RS_MAX_BINS;
+    const uint64_t cand_cap = (ws_bytes - threshold_ws_min_bytes()) / 4;
 
-    const uint64_t steps = ((n >> 2) + HIST_STEP4 - 1) / HIST_STEP4;
-    unsigned grid = (unsigned)(steps < 2048 ? (steps ? steps : 1) : 2048);
+    hipLaunchKernelGGL(radix_init_kernel, dim3(4 * RS_MAX_BINS / 256), dim3(256), 0, s, state,
+                       hist_sample, 4u * RS_MAX_BINS);
 
-    hipLaunchKernelGGL(radix_init_kernel, dim3(3 * RS_MAX_BINS / 256), dim3(256), 0, s, state,
-                       hist1, k);
+    // sampling pays once the vector is long and the workspace can hold the candidates
+    const uint64_t blocks = n / 1024;                       // whole blocks of 1024 elements
+    const bool sampled = n >= RS_SAMPLE_MIN_N && cand_cap >= n / 16;
+    if (sampled) {
+        uint64_t stride = blocks / RS_SAMPLE_BLOCKS;
+        if (stride < 1) stride = 1;
+        const uint64_t nsamp = (blocks + stride - 1) / stride;
+        hipLaunchKernelGGL(sample_hist_kernel,
+                           dim3((unsigned)((nsamp + SAMPLE_PER_WG - 1) / SAMPLE_PER_WG)),
+                           dim3(HIST_BLOCK), 0, s, d_acc, (uint32_t)nsamp, (uint32_t)stride,
+                           hist_sample);
+        hipLaunchKernelGGL(sample_range_kernel, dim3(1), dim3(256), 0, s, state, hist_sample,
+                           nsamp * 1024, n, k);
+        const SelectShape shape = select_shape_for(n, CNT_WAVES, 256u * CNT_U);
+        hipLaunchKernelGGL(collect_kernel, dim3(shape.nseg), dim3(CNT_BLOCK), 0, s, d_acc,
+                           (uint32_t)n, shape.piece, state, cand, cand_cap);
+    }
+    hipLaunchKernelGGL(radix_setup_kernel, dim3(1), dim3(1), 0, s, state, n, k, cand_cap,
+                       sampled ? 1 : 0);
+
+    // the radix passes are sized for the candidates when sampling ran (a failed
+    // check makes them walk the whole vector with the same, smaller grid)
+    const uint64_t expect = sampled ? n / 16 : n;
+    const uint64_t steps = ((expect >> 2) + HIST_STEP4 - 1) / HIST_STEP4;
+    const unsigned grid = (unsigned)(steps < 2048 ? (steps ? steps : 1) : 2048);
     hipLaunchKernelGGL((radix_hist_kernel<20, RS_BITS1, true>), dim3(grid), dim3(HIST_BLOCK), 0, s,
-                       d_acc, (uint32_t)n, state, hist1);
+                       d_acc, cand, state, hist1);
     hipLaunchKernelGGL((radix_pick_kernel<RS_BITS1, false>), dim3(1), dim3(256), 0, s, state,
                        hist1, d_threshold_out, d_count_ge_out);
     hipLaunchKernelGGL((radix_hist_kernel<9, RS_BITS2, false>), dim3(grid), dim3(HIST_BLOCK), 0, s,
-                       d_acc, (uint32_t)n, state, hist2);
+                       d_acc, cand, state, hist2);
     hipLaunchKernelGGL((radix_pick_kernel<RS_BITS2, false>), dim3(1), dim3(256), 0, s, state,
                        hist2, d_threshold_out, d_count_ge_out);
     hipLaunchKernelGGL((radix_hist_kernel<0, RS_BITS3, false>), dim3(grid), dim3(HIST_BLOCK), 0, s,
-                       d_acc, (uint32_t)n, state, hist3);
+                       d_acc, cand, state, hist3);
     hipLaunchKernelGGL((radix_pick_kernel<RS_BITS3, true>), dim3(1), dim3(256), 0, s, state,
                        hist3, d_threshold_out, d_count_ge_out);
     return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;

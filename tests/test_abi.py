@@ -61,7 +61,7 @@ def test_argument_errors_are_found_on_the_host():
     assert lib.okt_residual_accumulate(fake, fake, 1.0, 1 << 32, null) == INVALID
     assert lib.okt_topk_threshold_exact(fake, 10, 0, fake, fake, fake, 1 << 20, null) == INVALID   # k = 0
     assert lib.okt_topk_threshold_exact(fake, 10, 11, fake, fake, fake, 1 << 20, null) == INVALID  # k > n
-    assert lib.okt_topk_threshold_exact(fake, 10, 5, fake, fake, fake, 64, null) == WORKSPACE
+    assert lib.okt_topk_threshold_exact(fake, 10, 5, fake, fake, fake, 4096, null) == WORKSPACE
     assert lib.okt_topk_threshold_exact(fake, 10, 5, fake, fake, null, 1 << 20, null) == WORKSPACE
     assert lib.okt_threshold_select(fake, 10, null, fake, fake, 4, fake, fake, 1 << 20, null) == INVALID
     assert lib.okt_threshold_select(fake, 1 << 20, fake, fake, fake, 4, fake, fake, 8, null) == WORKSPACE

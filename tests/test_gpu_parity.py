@@ -97,9 +97,42 @@ def test_threshold_ties_and_degenerate_inputs():
         assert np.float32(th).view(np.uint32) == np.float32(rth).view(np.uint32) and cnt == rcnt
 
 
+def test_threshold_sampled_path():
+    """Vectors long enough for the sample-then-count path, including inputs on
+    which the sample misleads and the full radix select has to take over."""
+    n = 5_000_011
+    acc = lap(5, n)
+    for k in (1, 50_000, n // 2, n):
+        th, cnt = gpu_threshold(acc, k)
+        rth, rcnt = orc.topk_threshold_exact(acc, k, method="partition")
+        assert np.float32(th).view(np.uint32) == np.float32(rth).view(np.uint32) and cnt == rcnt
+    # the workspace too small for the candidates: same answer without sampling
+    assert gpu_threshold(acc, 50_000, ws_bytes=64 * 1024) == gpu_threshold(acc, 50_000)
+    # every value equal: the candidates are the whole vector and do not fit
+    same = np.full(4_500_000, 0.25, dtype=np.float32)
+    assert gpu_threshold(same, 45_000) == (0.25, 4_500_000)
+    # the large values hide in blocks the sample never looks at (it reads every
+    # 4th block of 1024 elements at this length)
+    hidden = lap(6, n, 1e-6)
+    big = np.random.default_rng(7).laplace(0, 1.0, n).astype(np.float32)
+    blocks = np.arange(n) // 1024
+    mask = (blocks % 4) == 1
+    hidden[mask] = big[mask]
+    for k in (10, 40_000, 1_000_000):
+        th, cnt = gpu_threshold(hidden, k)
+        rth, rcnt = orc.topk_threshold_exact(hidden, k, method="partition")
+        assert np.float32(th).view(np.uint32) == np.float32(rth).view(np.uint32) and cnt == rcnt
+    # heavy ties around rank k inside a long vector
+    tied = lap(8, n)
+    tied[100_000:400_000] = np.float32(3e-3)
+    above = int((np.abs(tied) > np.float32(3e-3)).sum())
+    th, cnt = gpu_threshold(tied, above + 1000)
+    assert th == np.float32(3e-3) and cnt == int((np.abs(tied) >= np.float32(3e-3)).sum())
+
+
 def test_threshold_small_workspace_same_result():
     acc = lap(17, 500_000)
-    assert gpu_threshold(acc, 5000, ws_bytes=32 * 1024) == gpu_threshold(acc, 5000)
+    assert gpu_threshold(acc, 5000, ws_bytes=64 * 1024) == gpu_threshold(acc, 5000)
 
 
 # ---------------------------------------------------------------------- select
