@@ -129,7 +129,7 @@ def main():
     stream = torch.cuda.current_stream()
     counter = {"reduce": 0}
 
-    def run_step(step, ev=None, only=None):
+    def run_step(step, ev=None, only=None, fused=False):
         """One step = ITERS_PER_STEP iterations of one worker.  `ev` collects
         (call, start_event, end_event) for the calls named in `only`."""
         st = workers[step % len(workers)]
@@ -146,12 +146,19 @@ def main():
                 fn()
 
         for it in range(ITERS_PER_STEP):
-            timed("accumulate", lambda: okt.okt_residual_accumulate(st.grads[it], st.residual, w.lr))
-            if it == 0:
-                timed("threshold", lambda: okt.okt_topk_threshold_exact(
-                    st.residual, k, st.th, st.count_ge, st.ws))
-            timed("select", lambda: okt.okt_threshold_select(
-                st.residual, st.th, st.idx, st.val, st.nnz, st.ws, capacity=st.cap))
+            if fused and it != 0:
+                # reuse iteration: the threshold is already known, one pass does both
+                timed("accumulate_select", lambda: okt.okt_accumulate_select(
+                    st.grads[it], st.residual, w.lr, st.th, st.idx, st.val, st.nnz, st.ws,
+                    capacity=st.cap))
+            else:
+                timed("accumulate", lambda: okt.okt_residual_accumulate(
+                    st.grads[it], st.residual, w.lr))
+                if it == 0:
+                    timed("threshold", lambda: okt.okt_topk_threshold_exact(
+                        st.residual, k, st.th, st.count_ge, st.ws))
+                timed("select", lambda: okt.okt_threshold_select(
+                    st.residual, st.th, st.idx, st.val, st.nnz, st.ws, capacity=st.cap))
             if it == 0:
                 timed("partition", lambda: okt.okt_region_partition(
                     st.idx, st.nnz, n, P, st.bounds, st.offsets))
@@ -160,18 +167,24 @@ def main():
             timed("reduce", lambda: okt.okt_sparse_reduce(
                 ci, cv, co, lo, hi, red_idx, red_val, red_nnz, st.ws, dense_out=red_dense))
 
-    def summarise(ev):
+    def summarise(ev, tail=1.0):
+        """name -> (mean, median, count) of the event times in us; `tail` keeps only
+        the last fraction of each call's samples (the first ones run cold)."""
         per = {}
         for name, a, b in ev:
             per.setdefault(name, []).append(a.elapsed_time(b) * 1e3)      # us
-        return {name: (float(np.mean(v)), float(np.median(v)), len(v)) for name, v in per.items()}
+        out = {}
+        for name, v in per.items():
+            v = v[len(v) - max(1, int(len(v) * tail)):]
+            out[name] = (float(np.mean(v)), float(np.median(v)), len(v))
+        return out
 
     # ---------------- warmup (instrumented: finds the dominant call) ----------
     ev = []
     for s in range(args.warmup):
         run_step(s, ev=ev)
     torch.cuda.synchronize()
-    warm = summarise(ev) if ev else {}
+    warm = summarise(ev, tail=0.5) if ev else {}
     nnz_seen = int(workers[0].nnz.cpu().numpy().view(np.uint64)[1]) if args.warmup else k
     calls_per_step = {"accumulate": ITERS_PER_STEP, "threshold": 1, "select": ITERS_PER_STEP,
                       "partition": 1, "reduce": ITERS_PER_STEP}
@@ -230,6 +243,26 @@ def main():
                 "traffic": read_traffic(dominant), "us_per_launch": round(dom_us, 2),
                 "algorithmic_bytes_per_launch": alg_bytes[dominant]}
 
+    # ---------------- the same step with the fused accumulate+select ----------
+    torch.cuda.synchronize()
+    t_f = time.perf_counter()
+    for s in range(args.steps):
+        run_step(args.warmup + s, fused=True)
+    torch.cuda.synchronize()
+    ms_fused = (time.perf_counter() - t_f) * 1e3 / args.steps
+    ev3 = []
+    for s in range(4):
+        run_step(s, ev=ev3, only=("accumulate_select",), fused=True)
+    torch.cuda.synchronize()
+    fs = summarise(ev3)["accumulate_select"]
+    fused_bytes = 12.0 * n + 8.0 * nnz_now
+    fused_path = {"what": "iterations 1-9 of a step call okt_accumulate_select instead of "
+                          "okt_residual_accumulate + okt_threshold_select",
+                  "ms_per_step": ms_fused, "value": ITERS_PER_STEP * n / (ms_fused * 1e-3),
+                  "us_per_call": round(fs[0], 2), "algorithmic_bytes": fused_bytes,
+                  "achieved_GBs": round(fused_bytes / fs[0] * 1e-3, 1),
+                  "frac_of_hbm_peak": round(fused_bytes / fs[0] * 1e-3 / HBM_PEAK_GBS, 4)}
+
     # ---------------- sustained reduce over a batch of regions ----------------
     reduce_batch = time_reduce_batch(args, torch, np, okt, wl, w, lo, hi)
 
@@ -255,6 +288,7 @@ def main():
         "cpu_baseline": cpu,
         "kernels": kernels,
         "reduce_batch": reduce_batch,
+        "fused_path": fused_path,
     }
     print(json.dumps(out), flush=True)
 

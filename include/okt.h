@@ -109,6 +109,23 @@ int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshol
                          uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * The accumulate and the threshold selection of one iteration in a single pass,
+ * for the iterations that reuse a threshold (Sec. 3.1.3: the threshold is
+ * re-evaluated only every tau' iterations, so in between it is known before the
+ * accumulator is).  Same result, bit for bit, as okt_residual_accumulate
+ * followed by okt_threshold_select with the same arguments:
+ *   acc = eps + lr * G (two roundings); S = {i : key(acc[i]) >= key(*d_threshold)};
+ *   outputs as in okt_threshold_select; d_residual_inout ends as acc with +0.0f
+ *   at the emitted entries.
+ * d_grad and d_residual_inout must not overlap.  Moves 12 B per element and 8 B
+ * per selected entry; the residual is written once, densely.
+ */
+int okt_accumulate_select(const float* d_grad, float* d_residual_inout, float lr, uint64_t n,
+                          const float* d_threshold, uint32_t* d_idx_out, float* d_val_out,
+                          uint64_t capacity, uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes,
+                          void* stream);
+
+/*
  * Balanced split of the index space [0, n) into R regions by the local top-k
  * entries (Algorithm 1, lines 5-7, space_repartition; Sec. 3.1.1 "each worker
  * calculates the local boundaries of the P regions by balancing the local top-k

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     OktError,
     library_path,
     load_library,
+    okt_accumulate_select,
     okt_region_partition,
     okt_residual_accumulate,
     okt_sparse_reduce,

@@ -25,6 +25,8 @@ SIGNATURES = {
     "okt_residual_accumulate": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp]),
     "okt_topk_threshold_exact": (c_int, [c_vp, c_u64, c_u64, c_vp, c_vp, c_vp, c_sz, c_vp]),
     "okt_threshold_select": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_sz, c_vp]),
+    "okt_accumulate_select": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp,
+                                      c_sz, c_vp]),
     "okt_region_partition": (c_int, [c_vp, c_vp, c_u64, c_u32, c_vp, c_vp, c_vp]),
     "okt_sparse_reduce": (c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp, c_u64, c_vp,
                                   c_vp, c_vp, c_sz, c_vp]),
@@ -150,6 +152,25 @@ def okt_threshold_select(acc_inout, threshold, idx_out, val_out, nnz_out, ws, ca
     _check("okt_threshold_select", load_library().okt_threshold_select(
         _ptr(acc_inout, torch.float32, "acc_inout"), acc_inout.numel(),
         _ptr(threshold, torch.float32, "threshold"),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
+        _ptr(nnz_out, _u64(torch), "nnz_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
+        _stream(stream)))
+
+
+def okt_accumulate_select(grad, residual_inout, lr: float, threshold, idx_out, val_out, nnz_out, ws,
+                          capacity=None, stream=None) -> None:
+    torch = _torch()
+    _ptr(residual_inout, torch.float32, "residual_inout")
+    if grad.numel() != residual_inout.numel():
+        raise ValueError("grad and residual must have the same length")
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > idx_out.numel() or cap > val_out.numel():
+        raise ValueError("capacity exceeds the output buffers")
+    if nnz_out.numel() < 2 or threshold.numel() < 1:
+        raise ValueError("nnz_out needs two elements, threshold one")
+    _check("okt_accumulate_select", load_library().okt_accumulate_select(
+        _ptr(grad, torch.float32, "grad"), residual_inout.data_ptr(), float(lr),
+        residual_inout.numel(), _ptr(threshold, torch.float32, "threshold"),
         _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
         _ptr(nnz_out, _u64(torch), "nnz_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
         _stream(stream)))

@@ -65,25 +65,24 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(
     const uint32_t region = blockIdx.y;
     const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
     uint32_t* table = (uint32_t*)(ws + (size_t)region * ws_region_bytes + table_offset);
+    // the scan state of the region (header and descriptors, in front of the table)
+    // must be zero when the tile kernel starts
+    uint64_t* scan_state = (uint64_t*)(ws + (size_t)region * ws_region_bytes);
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < table_offset / 8;
+         i += gridDim.x * blockDim.x)
+        scan_state[i] = 0;
     const uint64_t* off = chunk_off + (size_t)region * (P + 1);
     const uint64_t cells = (uint64_t)(r.ntiles + 1) * P;
     for (uint64_t c = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; c < cells;
          c += (uint64_t)gridDim.x * blockDim.x) {
-        const uint32_t t = (uint32_t)(c / P), p = (uint32_t)(c % P);
+        // neighbouring threads search the same contribution for neighbouring
+        // boundaries: their probes share all but the last few levels
+        const uint32_t p = (uint32_t)(c / (r.ntiles + 1)), t = (uint32_t)(c % (r.ntiles + 1));
         uint64_t bound = (uint64_t)r.lo + (uint64_t)t * slots;
         if (bound > r.hi) bound = r.hi;
         const uint64_t cb = off[p], ce = off[p + 1];
-        table[c] = (uint32_t)(lower_bound_idx(idx_cat, cb, ce, (uint32_t)bound) - cb);
+        table[(size_t)t * P + p] = (uint32_t)(lower_bound_idx(idx_cat, cb, ce, (uint32_t)bound) - cb);
     }
-}
-
-// Zero the scan state (header and descriptors) at the head of every region's
-// workspace; the slice table behind it is fully rewritten by every call.
-__global__ __launch_bounds__(256) void reduce_clear_kernel(char* ws, uint32_t ws_region_bytes,
-                                                          uint32_t words) {
-    uint64_t* p = (uint64_t*)(ws + (size_t)blockIdx.y * ws_region_bytes);
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x)
-        p[i] = 0;
 }
 
 // Exclusive prefix over the popcounts of `words` bitmap words into s_wprefix;
@@ -369,15 +368,6 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
     uint64_t tiles = reduce_tiles(max_width, slots);
     if (tiles == 0) tiles = 1;
     const uint32_t table_offset = (uint32_t)(64 + 8 * (tiles + (tiles + 63) / 64));
-    // the scan state of every region (header and descriptors) starts at zero; the
-    // table behind it is fully rewritten
-    {
-        const uint32_t words = table_offset / 8;
-        uint32_t cblocks = (words + 255) / 256;
-        if (cblocks > 64) cblocks = 64;
-        hipLaunchKernelGGL(reduce_clear_kernel, dim3(cblocks, B), dim3(256), 0, s, (char*)d_ws,
-                           (uint32_t)region_bytes, words);
-    }
     const uint64_t cells = (tiles + 1) * P;
     uint64_t sblocks = (cells + 255) / 256;
     if (sblocks > 4096) sblocks = 4096;

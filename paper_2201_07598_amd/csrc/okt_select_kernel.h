@@ -76,15 +76,24 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
     const int lane = lane_id();
     uint32_t count = 0;
     uint64_t r = start;
-    for (; r + 256 * U <= end; r += 256 * U) {            // start is 16-byte aligned
-        const float4* src = reinterpret_cast<const float4*>(acc + r) + lane;
-        float4 v[U];
+    // The sink may store to acc.  Loads and stores retire through one in-order
+    // counter, so the loads of the next batch are issued before this batch is
+    // handed to the sink: they never queue behind its stores.
+    float4 v[U], w[U];
+    auto load_batch = [&](float4* dst, uint64_t at) {     // start is 16-byte aligned
+        const float4* src = reinterpret_cast<const float4*>(acc + at) + lane;
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = src[u * WAVE];
+        for (int u = 0; u < U; ++u) dst[u] = src[u * WAVE];
+    };
+    if (r + 256 * U <= end) load_batch(v, r);
+    for (; r + 256 * U <= end; r += 256 * U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) w[u] = v[u];
+        if (r + 2 * 256 * U <= end) load_batch(v, r + 256 * U);
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            count = select_round((uint32_t)r + 256u * u, v[u], test(v[u].x), test(v[u].y),
-                                 test(v[u].z), test(v[u].w), count, sink);
+            count = select_round((uint32_t)r + 256u * u, w[u], test(w[u].x), test(w[u].y),
+                                 test(w[u].z), test(w[u].w), count, sink);
     }
     for (; r < end; r += 256) {                           // ragged rounds of the last piece
         const uint64_t i = r + 4u * (uint32_t)lane;
@@ -102,37 +111,23 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
     return count;
 }
 
-// Workgroup `seg` (a ticket) owns WAVES consecutive pieces of `piece` elements,
-// one per wave.  A wave streams its piece once, with no barrier and no wait in
-// the loop, and parks the few selected (index, value) pairs in its LDS stash.
-// Then the workgroup publishes its count, learns the count of everything before
-// it from the chained scan, and writes its pairs to their final place, zeroing
-// the residual entries it emitted.  A wave whose piece holds more selected
-// entries than the stash walks its piece a second time and writes directly
-// (dense thresholds only; the residual is still untouched at that point).
-template <int BLOCK, int U, int STASH, bool TICKET, typename Test>
-__device__ __forceinline__ void select_body(
-    float* __restrict__ acc, uint32_t n, Test test, uint32_t* __restrict__ idx_out,
+// Second half of a select: the workgroup publishes its count, learns the count of
+// everything before it from the chained scan, and each wave writes its pairs to
+// their final place.  On entry the wave has seen `count` selected entries in its
+// piece [start, end) and holds the first `stashed` of them (in index order) in
+// its LDS stash, already zeroed in the residual; entries past the stash are
+// untouched.  Entries that do not fit the output are put back.  A wave whose
+// stash did not hold everything puts back what it zeroed and walks its piece a
+// second time, writing directly (dense thresholds only).
+template <int BLOCK, int U, int STASH, typename Test>
+__device__ __forceinline__ void select_finish(
+    float* __restrict__ acc, Test test, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
-    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece,
-    uint32_t seg, StashEntry (*s_stash)[STASH], uint32_t* s_count, uint32_t* s_before) {
+    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t seg,
+    uint64_t start, uint64_t end, uint32_t count, uint32_t stashed, StashEntry* mine,
+    uint32_t* s_count, uint32_t* s_before) {
     constexpr int WAVES = BLOCK / WAVE;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
-    const uint64_t start = ((uint64_t)seg * WAVES + wave) * piece;
-    const uint64_t end = start + piece < n ? start + piece : n;       // start >= n: empty
-
-    // A selected element is parked in the stash and zeroed on the spot, while its
-    // cache line is still close by: zeroing it later costs a read-modify-write of
-    // a line long gone from the caches.  Whatever must not stay zero after all
-    // (output full, stash overflow) is written back from the stash below.
-    StashEntry* mine = s_stash[wave];
-    const uint32_t count =
-        select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
-            if (rank < (uint32_t)STASH) {
-                mine[rank] = StashEntry{i, x};
-                acc[i] = 0.0f;
-            }
-        });
     if (lane == 0) s_count[wave] = count;
     __syncthreads();
     uint32_t aggregate = 0, wave_first = 0;
@@ -156,9 +151,9 @@ __device__ __forceinline__ void select_body(
     if (tid == 0 && group != 0 && seg % SCAN_GROUP == SCAN_GROUP - 1)
         scan_close_group(group_desc, group, exclusive + aggregate);
 
-    // ---- emit in ascending index order, and zero what was emitted ----
+    // ---- emit in ascending index order ----
     const uint64_t first = (uint64_t)exclusive + wave_first;
-    if (count <= (uint32_t)STASH) {
+    if (count == stashed) {
         for (uint32_t j = lane; j < count; j += WAVE) {
             const uint64_t pos = first + j;
             const StashEntry e = mine[j];
@@ -170,8 +165,7 @@ __device__ __forceinline__ void select_body(
             }
         }
     } else {
-        // stash overflow: put back what was zeroed, then walk the piece again
-        for (uint32_t j = lane; j < (uint32_t)STASH; j += WAVE) acc[mine[j].idx] = mine[j].val;
+        for (uint32_t j = lane; j < stashed; j += WAVE) acc[mine[j].idx] = mine[j].val;
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // stores land before the re-read
         select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
             const uint64_t pos = first + rank;
@@ -189,6 +183,130 @@ __device__ __forceinline__ void select_body(
         nnz_out[0] = failed ? ~0ull : (total < capacity ? total : capacity);
         nnz_out[1] = failed ? ~0ull : total;
     }
+}
+
+// Workgroup `seg` (a ticket) owns WAVES consecutive pieces of `piece` elements,
+// one per wave.  A wave streams its piece once, with no barrier and no wait in
+// the loop, parks the few selected (index, value) pairs in its LDS stash and
+// zeroes them on the spot, while their cache line is still close by: zeroing
+// them later costs a read-modify-write of a line long gone from the caches.
+template <int BLOCK, int U, int STASH, bool TICKET, typename Test>
+__device__ __forceinline__ void select_body(
+    float* __restrict__ acc, uint32_t n, Test test, uint32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
+    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece,
+    uint32_t seg, StashEntry (*s_stash)[STASH], uint32_t* s_count, uint32_t* s_before) {
+    constexpr int WAVES = BLOCK / WAVE;
+    const int wave = threadIdx.x >> 6;
+    const uint64_t start = ((uint64_t)seg * WAVES + wave) * piece;
+    const uint64_t end = start + piece < n ? start + piece : n;       // start >= n: empty
+    StashEntry* mine = s_stash[wave];
+    const uint32_t count =
+        select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
+            if (rank < (uint32_t)STASH) {
+                mine[rank] = StashEntry{i, x};
+                acc[i] = 0.0f;
+            }
+        });
+    select_finish<BLOCK, U, STASH>(acc, test, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
+                                   group_desc, nseg, seg, start, end, count,
+                                   count < (uint32_t)STASH ? count : (uint32_t)STASH, mine,
+                                   s_count, s_before);
+}
+
+// The accumulate and the select in one pass (reuse iterations of Ok-Topk SGD,
+// where the threshold is known before the accumulator is): a wave reads its
+// piece of the gradient and of the residual, forms acc = eps + lr * G (product
+// and sum rounded separately), tests it, parks the selected pairs in its stash
+// and writes the new residual -- acc, with zeros at the parked entries -- as
+// whole 16-byte stores.  Every residual line is written once, densely: no
+// scattered zeroing at all.  Rounds met after the stash is full are written
+// unzeroed and left to the second walk of select_finish.
+template <int BLOCK, int U, int STASH, bool TICKET, typename Test>
+__device__ __forceinline__ void accumulate_select_body(
+    const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, Test test,
+    uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
+    uint64_t* __restrict__ nnz_out, ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc,
+    uint32_t nseg, uint32_t piece, uint32_t seg, StashEntry (*s_stash)[STASH], uint32_t* s_count,
+    uint32_t* s_before) {
+    constexpr int WAVES = BLOCK / WAVE;
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
+    const uint64_t start = ((uint64_t)seg * WAVES + wave) * piece;
+    const uint64_t end = start + piece < n ? start + piece : n;
+    StashEntry* mine = s_stash[wave];
+    uint32_t count = 0, stashed = 0;                 // wave-uniform
+
+    // one round of 256 elements whose accumulator values are in `a`; returns the
+    // residual to store
+    auto round = [&](uint32_t first, float4 a, bool sx, bool sy, bool sz, bool sw) -> float4 {
+        const bool room = count <= (uint32_t)(STASH - 256) && count == stashed;
+        const uint32_t now = select_round(first, a, sx, sy, sz, sw, count,
+                                          [&](uint32_t rank, uint32_t i, float x) {
+                                              if (room) mine[rank] = StashEntry{i, x};
+                                          });
+        if (room) {
+            stashed = now;
+            if (sx) a.x = 0.0f;
+            if (sy) a.y = 0.0f;
+            if (sz) a.z = 0.0f;
+            if (sw) a.w = 0.0f;
+        }
+        count = now;
+        return a;
+    };
+    auto fma2 = [&](float e, float g) { return __fadd_rn(e, __fmul_rn(lr, g)); };
+
+    // The loads of the next batch are issued before the stores of this one: loads
+    // and stores retire through one in-order counter, so a load queued behind a
+    // store would wait for the store's acknowledgement on every trip.
+    uint64_t r = start;
+    float4 g[U], e[U];
+    auto load_batch = [&](uint64_t at) {
+        const float4* gsrc = reinterpret_cast<const float4*>(grad + at) + lane;
+        const float4* esrc = reinterpret_cast<const float4*>(res + at) + lane;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            g[u] = gsrc[u * WAVE];
+            e[u] = esrc[u * WAVE];
+        }
+    };
+    if (r + 256 * U <= end) load_batch(r);
+    for (; r + 256 * U <= end; r += 256 * U) {
+        float4 a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u].x = fma2(e[u].x, g[u].x);
+            a[u].y = fma2(e[u].y, g[u].y);
+            a[u].z = fma2(e[u].z, g[u].z);
+            a[u].w = fma2(e[u].w, g[u].w);
+        }
+        if (r + 2 * 256 * U <= end) load_batch(r + 256 * U);
+        float4* edst = reinterpret_cast<float4*>(res + r) + lane;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            edst[u * WAVE] = round((uint32_t)r + 256u * u, a[u], test(a[u].x), test(a[u].y),
+                                   test(a[u].z), test(a[u].w));
+    }
+    for (; r < end; r += 256) {                      // ragged rounds of the last piece
+        const uint64_t i = r + 4u * (uint32_t)lane;
+        float a[4];
+        bool s[4], inside[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            inside[c] = i + c < end;
+            a[c] = inside[c] ? fma2(res[i + c], grad[i + c]) : 0.0f;
+            s[c] = inside[c] && test(a[c]);
+        }
+        const float4 out = round((uint32_t)r, make_float4(a[0], a[1], a[2], a[3]), s[0], s[1],
+                                 s[2], s[3]);
+        if (inside[0]) res[i] = out.x;
+        if (inside[1]) res[i + 1] = out.y;
+        if (inside[2]) res[i + 2] = out.z;
+        if (inside[3]) res[i + 3] = out.w;
+    }
+    select_finish<BLOCK, U, STASH>(res, test, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
+                                   group_desc, nseg, seg, start, end, count, stashed, mine,
+                                   s_count, s_before);
 }
 
 template <int BLOCK, int U, int STASH, bool TICKET>
@@ -219,6 +337,34 @@ __global__ __launch_bounds__(BLOCK) void select_kernel(
         select_body<BLOCK, U, STASH, TICKET>(acc, n, TestKey{magnitude_key(th)}, idx_out, val_out,
                                              capacity, nnz_out, hdr, seg_desc, group_desc, nseg,
                                              piece, seg, s_stash, s_count, s_before);
+    }
+}
+
+template <int BLOCK, int U, int STASH, bool TICKET>
+__global__ __launch_bounds__(BLOCK) void accumulate_select_kernel(
+    const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n,
+    const float* __restrict__ d_threshold, uint32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
+    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece) {
+    constexpr int WAVES = BLOCK / WAVE;
+    __shared__ StashEntry s_stash[WAVES][STASH];
+    __shared__ uint32_t s_count[WAVES];
+    __shared__ uint32_t s_seg;
+    __shared__ uint32_t s_before[2];
+    if (TICKET) {
+        if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+        __syncthreads();
+    }
+    const uint32_t seg = TICKET ? s_seg : blockIdx.x;
+    const float th = *d_threshold;
+    if (th == th) {
+        accumulate_select_body<BLOCK, U, STASH, TICKET>(
+            grad, res, lr, n, TestFloat{__builtin_fabsf(th)}, idx_out, val_out, capacity, nnz_out,
+            hdr, seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
+    } else {
+        accumulate_select_body<BLOCK, U, STASH, TICKET>(
+            grad, res, lr, n, TestKey{magnitude_key(th)}, idx_out, val_out, capacity, nnz_out,
+            hdr, seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     }
 }
 

@@ -199,6 +199,58 @@ def test_select_is_deterministic():
     assert all(np.array_equal(x, y) for x, y in zip(a[:3], b[:3])) and a[3:] == b[3:]
 
 
+# ------------------------------------------------------- accumulate + select
+def check_fused(g, e, lr, th, capacity):
+    d_e = to_dev(e) if e.size else torch.zeros(1, dtype=torch.float32, device=DEV)[:0]
+    d_g = to_dev(g) if g.size else torch.zeros(1, dtype=torch.float32, device=DEV)[:0]
+    d_th = to_dev(np.array([th], dtype=np.float32))
+    idx = torch.full((max(capacity, 1),), -1, dtype=torch.int32, device=DEV)
+    val = torch.zeros(max(capacity, 1), dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    ws = workspace(okt.okt_workspace_bytes(max(g.size, 1), 0))
+    okt.okt_accumulate_select(d_g, d_e, lr, d_th, idx, val, nnz, ws, capacity=capacity)
+    c = u64(nnz)
+    acc = orc.residual_accumulate(g, e, lr)
+    ridx, rval, rres, rtotal = orc.threshold_select(acc, th, capacity=capacity)
+    assert (int(c[0]), int(c[1])) == (ridx.size, rtotal)
+    assert np.array_equal(u32(idx[:ridx.size]), ridx)
+    assert bits_equal(val[:ridx.size].cpu().numpy(), rval)
+    assert bits_equal(d_e.cpu().numpy(), rres)
+    assert bits_equal(d_g.cpu().numpy(), g)          # the gradient is read only
+    return rtotal
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 1023, 4096, 4097, 70_001, 1_000_003, (1 << 22) + 5])
+def test_accumulate_select_matches_the_two_calls(n):
+    g, e = lap(n + 3, n), lap(n + 4, n, 2e-3)
+    e[::5] = 0
+    lr = 0.25
+    if n == 0:
+        check_fused(g, e, lr, np.float32(1.0), 4)
+        return
+    acc = orc.residual_accumulate(g, e, lr)
+    k = max(1, n // 100)
+    th, cnt = orc.topk_threshold_exact(acc, k)
+    assert check_fused(g, e, lr, th, 4 * k) == cnt
+
+
+def test_accumulate_select_degenerate_and_truncated():
+    n = 300_007
+    g, e = lap(1, n), lap(2, n, 3e-3)
+    assert check_fused(g, e, 1.0, np.float32(np.inf), 8) == 0
+    assert check_fused(g, e, 1.0, np.float32(0.0), n) == n          # dense: second walk of every piece
+    assert check_fused(g, e, 1.0, np.float32(0.0), 1000) == n       # dense and truncated
+    total = check_fused(g, e, 0.5, np.float32(2e-3), n)
+    assert total > 5000
+    check_fused(g, e, 0.5, np.float32(2e-3), 1000)                  # output full: entries put back
+    check_fused(g, e, 0.5, np.float32(2e-3), 0)
+    check_fused(g, e, 0.5, np.float32(-2e-3), total - 1)
+    # not fused: lr*g rounds to 1 + 2^-11, which the residual cancels exactly
+    gg = np.full(5000, 1.0 + 2.0 ** -12, dtype=np.float32)
+    ee = np.full(5000, -(1.0 + 2.0 ** -11), dtype=np.float32)
+    assert check_fused(gg, ee, 1.0 + 2.0 ** -12, np.float32(1e-30), 5000) == 0
+
+
 # ------------------------------------------------------------------- partition
 def gpu_partition(idx, n, R):
     d_idx = to_dev(idx) if idx.size else torch.zeros(1, dtype=torch.int32, device=DEV)
@@ -387,7 +439,7 @@ def test_reduce_batch_matches_single_regions():
 
 
 # ----------------------------------------------------------- the whole hot path
-def run_loop(w, iterations, R):
+def run_loop(w, iterations, R, fused=False):
     """Alternate the GPU path and the oracle over `iterations` of Ok-Topk SGD's
     local part and compare every intermediate result bit for bit."""
     gpu = GpuPath(w.n, 4 * w.k)
@@ -396,15 +448,20 @@ def run_loop(w, iterations, R):
     counts = []
     for it in range(iterations):
         g = wl.gradient(w, it)
-        gpu.accumulate(to_dev(g), w.lr)
         acc = orc.residual_accumulate(g, res, w.lr)
-        assert bits_equal(gpu.residual.cpu().numpy(), acc), f"acc it={it}"
-        if w.refresh(it):
-            gpu.threshold(w.k)
-            th, cnt = orc.topk_threshold_exact(acc, w.k, method="partition")
-            assert gpu.th.cpu().numpy().view(np.uint32)[0] == np.float32(th).view(np.uint32)
-            assert int(u64(gpu.count_ge)[0]) == cnt
-        gpu.select()
+        if fused and not w.refresh(it):
+            # reuse iteration: accumulate and select in one call
+            okt.okt_accumulate_select(to_dev(g), gpu.residual, w.lr, gpu.th, gpu.idx, gpu.val,
+                                      gpu.nnz, gpu.ws, capacity=gpu.capacity)
+        else:
+            gpu.accumulate(to_dev(g), w.lr)
+            assert bits_equal(gpu.residual.cpu().numpy(), acc), f"acc it={it}"
+            if w.refresh(it):
+                gpu.threshold(w.k)
+                th, cnt = orc.topk_threshold_exact(acc, w.k, method="partition")
+                assert gpu.th.cpu().numpy().view(np.uint32)[0] == np.float32(th).view(np.uint32)
+                assert int(u64(gpu.count_ge)[0]) == cnt
+            gpu.select()
         ridx, rval, res, total = orc.threshold_select(acc, th, capacity=4 * w.k)
         idx, val, emitted, gtotal = gpu.selected()
         assert (emitted, gtotal) == (ridx.size, total), f"nnz it={it}"
@@ -421,11 +478,12 @@ def run_loop(w, iterations, R):
     return counts, rb
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("name,n,iters", [("cfg1", 1_048_576, 1), ("cfg2", 2_000_003, 10),
                                           ("cfg3", 1_500_001, 34), ("cfg4", 4_000_007, 3)])
-def test_hot_path_loop_scaled(name, n, iters):
+def test_hot_path_loop_scaled(name, n, iters, fused):
     w = wl.WORKLOADS[name].scaled(n)
-    counts, _ = run_loop(w, iters, w.P)
+    counts, _ = run_loop(w, iters, w.P, fused=fused)
     # threshold reuse keeps the selected count near k on these stationary inputs
     # (the paper reports an average deviation below 11 %); reported, not a bar
     print(name, "max |nnz-k|/k =", max(abs(c - w.k) / w.k for c in counts))
