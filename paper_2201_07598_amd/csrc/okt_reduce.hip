@@ -128,6 +128,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     __shared__ double s_sum[RED_C];
     __shared__ uint32_t s_bits[RED_WORDS_MAX];
     __shared__ uint16_t s_wprefix[RED_WORDS_MAX];
+    __shared__ uint16_t s_slot[RED_C];            // ranked tiles: slot of accumulator [rank]
     __shared__ uint64_t s_start[RED_CHUNKS];      // slice starts of the current sweep
     __shared__ uint32_t s_len[RED_CHUNKS];        // slice lengths
     __shared__ uint32_t s_loaded_p0;              // which sweep they belong to
@@ -306,34 +307,26 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
                 if (slot >= tslots) return;
                 const uint32_t below = s_bits[slot >> 5] & ((1u << (slot & 31)) - 1u);
                 const uint32_t rank = (uint32_t)s_wprefix[slot >> 5] + (uint32_t)__popc(below) - r0;
-                if (rank < RED_C)
+                if (rank < RED_C) {
                     __hip_atomic_fetch_add(&s_sum[rank], (double)x, __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
+                    s_slot[rank] = (uint16_t)slot;       // every hit of the slot writes the same
+                }
             };
             for_each_entry(Yes{}, add);
             __syncthreads();
             if (round == 0) exclusive = place_tile(distinct);
-            // values: accumulators are already in output order
+            // accumulators and their slots are already in output order
             const uint32_t in_round = distinct - r0 < RED_C ? distinct - r0 : RED_C;
             for (uint32_t k = tid; k < in_round; k += RED_BLOCK) {
                 const uint64_t pos = (uint64_t)exclusive + r0 + k;
-                if (pos < capacity) val_out[pos] = (float)s_sum[k];
-            }
-            // indices (and the dense copy): walk the bitmap
-            for (uint32_t w = tid; w < words; w += RED_BLOCK) {
-                uint32_t bits = s_bits[w];
-                uint32_t rank = s_wprefix[w];
-                while (bits) {
-                    const int bit = __ffs(bits) - 1;
-                    bits &= bits - 1;
-                    const uint32_t slot = w * 32u + bit;
-                    if (rank - r0 < RED_C) {
-                        const uint64_t pos = (uint64_t)exclusive + rank;
-                        if (pos < capacity) idx_out[pos] = a + slot;
-                        if (dense) dense[slot] = (float)s_sum[rank - r0];
-                    }
-                    ++rank;
+                const uint32_t slot = s_slot[k];
+                const float x = (float)s_sum[k];
+                if (pos < capacity) {
+                    idx_out[pos] = a + slot;
+                    val_out[pos] = x;
                 }
+                if (dense) dense[slot] = x;
             }
         }
         if (rounds == 0) exclusive = place_tile(0u);   // an empty tile is still a link of the chain
