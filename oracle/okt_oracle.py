@@ -1,6 +1,6 @@
 """CPU oracle for the Ok-Topk one-GPU hot path.  TEST INFRASTRUCTURE ONLY.
 
-This file is the plain, slow, obviously-correct statement of what the five
+This file is the plain, slow, obviously-correct statement of what the
 library calls compute.  Only tests, the smoke check and the benchmark's
 cpu_baseline leg may import it; the product path never does, and this file
 imports nothing from the HIP side.  It is written from the paper's
@@ -19,6 +19,11 @@ What the paper fixes, and where:
                       top-k entries                     (Sec. 3.1.1)
   * local reduction   plain sum of the sparse pieces received for
                       the own region                    (Sec. 3.1, 3.1.1)
+  * global select     the same threshold comparison on the reduced
+                      sparse values of the own region   (Sec. 3.1.2;
+                                                        Algorithm 1, line 13)
+  * indexes           local top-k indexes intersected with the global
+                      top-k indexes                     (Algorithm 1, line 14)
 
 Readings taken where the paper is silent (listed again in the design notes):
   magnitude order is the order of the fp32 bit pattern with the sign bit
@@ -173,6 +178,44 @@ def sparse_reduce(idx_cat: np.ndarray, val_cat: np.ndarray, chunk_off: np.ndarra
         "abs_sum": A[present].copy(),
         "hits": hits[present].copy(),
     }
+
+
+def coo_threshold_select(idx: np.ndarray, val: np.ndarray, th, capacity: int | None = None):
+    """Global top-k selection on a reduced sparse region (Sec. 3.1.2: each
+    worker selects the global top-k values from the reduced top-k values of its
+    region, by the global threshold, and packages them into a consecutive
+    buffer; Algorithm 1, line 13).
+
+    Keeps the entries (idx[j], val[j]) with |val[j]| >= th, in their order; the
+    input is not changed.  With a capacity only the first `capacity` of them are
+    emitted.  Returns (idx uint32, val fp32, total).
+    """
+    idx = np.asarray(idx, dtype=np.uint32)
+    val = np.ascontiguousarray(val, dtype=np.float32)
+    th_key = magnitude_key(np.array([th], dtype=np.float32))[0]
+    keep = np.flatnonzero(magnitude_key(val) >= th_key)
+    total = int(keep.size)
+    if capacity is not None:
+        keep = keep[:capacity]
+    return idx[keep].copy(), val[keep].copy(), total
+
+
+def index_intersection(local_idx: np.ndarray, global_idx: np.ndarray) -> np.ndarray:
+    """indexes = local_topk_indexes ∩ global_topk_indexes (Algorithm 1, line 14):
+    the positions whose local value contributed to a global top-k value.
+    Ascending uint32."""
+    local_idx = np.asarray(local_idx, dtype=np.uint32)
+    global_idx = np.asarray(global_idx, dtype=np.uint32)
+    member = np.isin(local_idx, global_idx)
+    return np.sort(local_idx[member]).astype(np.uint32)
+
+
+def residual_update(acc: np.ndarray, indexes: np.ndarray) -> np.ndarray:
+    """eps = acc - acc(indexes) (Algorithm 2, line 6): the accumulator with the
+    entries marked by `indexes` set to +0.0, everything else kept."""
+    eps = np.array(acc, dtype=np.float32, copy=True)
+    eps[np.asarray(indexes, dtype=np.int64)] = np.float32(0.0)
+    return eps
 
 
 def k_from_density(n: int, num: int, den: int) -> int:

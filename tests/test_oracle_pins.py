@@ -393,3 +393,103 @@ def test_reduce_equals_dense_sum_of_densified_inputs():
     assert np.allclose(out["dense"], dense[1000:4000], rtol=1e-6, atol=0)
     assert math.isclose(float(out["val"].astype(np.float64).sum()),
                         float(dense[1000:4000].sum()), rel_tol=1e-4)
+
+
+# ------------------------------------------- global select, indexes, residual
+def test_coo_select_vs_python_filter_and_dense_select():
+    rng = np.random.default_rng(71)
+    n = 5000
+    idx = np.sort(rng.choice(n, 700, replace=False)).astype(np.uint32)
+    val = rand_f32(rng, idx.size)
+    val[::50] = 0.0
+    val[7] = -val[8]                               # a tie in magnitude
+    for th in (abs(float(val[8])), 1e-3, 0.0, 1e9, float(np.abs(val).max())):
+        gi, gv, total = orc.coo_threshold_select(idx, val, th)
+        th_key = bits(f32(th)) & 0x7FFFFFFF
+        want = [(int(i), float(v)) for i, v in zip(idx, val) if (bits(v) & 0x7FFFFFFF) >= th_key]
+        assert total == len(want)
+        assert [(int(i), float(v)) for i, v in zip(gi, gv)] == want
+        if th > 0:
+            # absent entries are zeros, below any positive threshold: the dense
+            # select of the densified region sees the same set
+            dense = np.zeros(n, dtype=np.float32)
+            dense[idx] = val
+            di, dv, _, dtotal = orc.threshold_select(dense, th)
+            assert dtotal == total and np.array_equal(di, gi)
+            assert np.array_equal(dv.view(np.uint32), gv.view(np.uint32))
+    gi, gv, total = orc.coo_threshold_select(idx, val, 1e-3, capacity=5)
+    full_i, full_v, full_total = orc.coo_threshold_select(idx, val, 1e-3)
+    assert total == full_total and np.array_equal(gi, full_i[:5]) and np.array_equal(gv, full_v[:5])
+    ei, ev, et = orc.coo_threshold_select(idx[:0], val[:0], 1e-3)
+    assert ei.size == 0 and ev.size == 0 and et == 0
+
+
+def test_index_intersection_vs_python_sets():
+    rng = np.random.default_rng(72)
+    for na, nb in ((0, 0), (0, 9), (9, 0), (40, 40), (300, 57), (57, 300)):
+        a = np.sort(rng.choice(500, na, replace=False)).astype(np.uint32)
+        b = np.sort(rng.choice(500, nb, replace=False)).astype(np.uint32)
+        got = orc.index_intersection(a, b)
+        assert got.dtype == np.uint32
+        assert [int(x) for x in got] == sorted(set(map(int, a)) & set(map(int, b)))
+    a = np.arange(0, 100, 2, dtype=np.uint32)
+    assert orc.index_intersection(a, a + 1).size == 0          # disjoint
+    assert np.array_equal(orc.index_intersection(a, a), a)     # identical
+    assert np.array_equal(orc.index_intersection(a, np.arange(100, dtype=np.uint32)), a)
+
+
+def test_residual_update_keeps_everything_but_indexes():
+    rng = np.random.default_rng(73)
+    acc = rand_f32(rng, 2000)
+    acc[5] = -0.0
+    indexes = np.sort(rng.choice(acc.size, 100, replace=False)).astype(np.uint32)
+    eps = orc.residual_update(acc, indexes)
+    marked = set(map(int, indexes))
+    for i in range(acc.size):
+        assert bits(eps[i]) == (0 if i in marked else bits(acc[i])), i
+    # all locally selected entries reach the global top-k (one worker, or a
+    # global threshold at or below the local one): the update is the plain
+    # "zero what was selected" of the local select
+    th, _ = orc.topk_threshold_exact(acc, 150)
+    li, _, res, _ = orc.threshold_select(acc, th)
+    assert np.array_equal(orc.residual_update(acc, orc.index_intersection(li, li)).view(np.uint32),
+                          res.view(np.uint32))
+
+
+def test_what_leaves_the_residuals_is_what_is_applied():
+    # Algorithm 1 + Algorithm 2 line 6 over P simulated workers with dyadic
+    # values, so every sum is exact: u_t = Topk(sum_i Topk(acc_i)) densified must
+    # equal sum_i (acc_i - eps_i) element by element, and a locally selected
+    # entry that did not reach the global top-k must still be in its residual.
+    rng = np.random.default_rng(74)
+    n, P, k = 3000, 4, 90
+    accs = [(rng.integers(-2000, 2001, n) / 64.0).astype(np.float32) for _ in range(P)]
+    local, chunks_i, chunks_v, off = [], [], [], [0]
+    for acc in accs:
+        th, _ = orc.topk_threshold_exact(acc, k)
+        li, lv, _, _ = orc.threshold_select(acc, th)
+        local.append(li)
+        chunks_i.append(li)
+        chunks_v.append(lv)
+        off.append(off[-1] + li.size)
+    red = orc.sparse_reduce(np.concatenate(chunks_i), np.concatenate(chunks_v),
+                            np.array(off, dtype=np.uint64), 0, n)
+    gth, _ = orc.topk_threshold_exact(red["val"], k)
+    gi, gv, _ = orc.coo_threshold_select(red["idx"], red["val"], gth)
+    assert k <= gi.size < red["idx"].size           # something is filtered out
+    u = [Fraction(0)] * n
+    for i, v in zip(gi, gv):
+        u[int(i)] = Fraction(float(v))
+    left = [Fraction(0)] * n
+    kept_back = 0
+    gset = set(map(int, gi))
+    for acc, li in zip(accs, local):
+        eps = orc.residual_update(acc, orc.index_intersection(li, gi))
+        for i in range(n):
+            left[i] += Fraction(float(acc[i])) - Fraction(float(eps[i]))
+        for i in map(int, li):
+            if i not in gset:
+                kept_back += 1
+                assert bits(eps[i]) == bits(acc[i])
+    assert left == u
+    assert kept_back > 0
