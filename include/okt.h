@@ -25,7 +25,8 @@
  *     order of |x| for finite x (+-0 lowest; Inf above finite; NaN above Inf).
  *   - Return value: OKT_OK, or a negative okt_status.  Argument errors are found
  *     on the host before anything is launched; then no output is touched.
- *     OKT_ERR_HIP means a launch failed (hipGetLastError has the reason).
+ *     OKT_ERR_HIP means the HIP runtime refused a launch; okt_last_hip_error
+ *     gives its reason.
  */
 #ifndef OKT_H
 #define OKT_H
@@ -46,6 +47,12 @@ typedef enum okt_status {
 
 /* Text for a status code; never NULL; static storage. */
 const char* okt_status_string(int status);
+
+/*
+ * The HIP runtime's text for the error behind the calling thread's most recent
+ * OKT_ERR_HIP ("no error" if there was none); never NULL; static storage.
+ */
+const char* okt_last_hip_error(void);
 
 /* Library version, major * 10000 + minor * 100 + patch. */
 int okt_version(void);
@@ -196,6 +203,63 @@ int okt_sparse_reduce_batch(const uint32_t* d_idx_cat, const float* d_val_cat,
                             uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
                             uint64_t* d_nnz_out, float* d_dense_out_or_null,
                             void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Global top-k selection on the reduced sparse values of the own region
+ * (Sec. 3.1.2, "balance and allgatherv": each worker selects the global top-k
+ * values from the reduced top-k values of its region by the global threshold and
+ * packages them, with their indexes, into a consecutive buffer; Algorithm 1,
+ * line 13, the local part).  The threshold comparison of okt_threshold_select
+ * over a sorted COO list instead of a dense vector; the input is not modified.
+ *   d_idx_in, d_val_in  in  uint32/fp32[max_nnz]  the reduced region (the output
+ *                       of okt_sparse_reduce); d_val_in 16-byte aligned
+ *   d_nnz_in            in  uint64[1] on the device: entries present; more than
+ *                       max_nnz is read as max_nnz
+ *   max_nnz             host-side bound of *d_nnz_in (sizes the launch), < 2^32
+ *   d_threshold         in  fp32[1] the global threshold (its sign is ignored)
+ *   d_idx_out, d_val_out out uint32/fp32[capacity]  the entries j, in order, with
+ *                       key(val[j]) >= key(*d_threshold); bit copies
+ *   d_nnz_out           out uint64[2] {emitted = min(selected, capacity), selected}
+ * Workspace: okt_workspace_bytes(max_nnz, 0).  max_nnz = 0 gives {0, 0}.
+ * The global threshold itself (Algorithm 1, lines 9-12) is
+ * okt_topk_threshold_exact applied to the value array of the gathered reduced
+ * entries; the gather is a collective and not part of this library.
+ */
+int okt_coo_threshold_select(const uint32_t* d_idx_in, const float* d_val_in,
+                             const uint64_t* d_nnz_in, uint64_t max_nnz,
+                             const float* d_threshold, uint32_t* d_idx_out, float* d_val_out,
+                             uint64_t capacity, uint64_t* d_nnz_out, void* d_ws,
+                             size_t ws_bytes, void* stream);
+
+/*
+ * indexes = local top-k indexes intersected with the global top-k indexes
+ * (Algorithm 1, line 14), and the residual update eps = acc - acc(indexes)
+ * (Algorithm 2, line 6) completed on a residual that okt_threshold_select or
+ * okt_accumulate_select left with ALL locally selected entries zeroed: a locally
+ * selected entry whose index is not among the global top-k indexes did not
+ * contribute to the applied update, so its value is written back.
+ *   d_residual_inout  in/out fp32[n]  on exit +0.0f exactly at `indexes`
+ *   d_local_idx, d_local_val  in  the sorted COO the select emitted
+ *   d_local_nnz       in  uint64[1] on the device (d_nnz_out of the select);
+ *                     more than max_local is read as max_local
+ *   d_global_idx      in  uint32[...] ascending: the indexes of the global top-k
+ *                     values u_t (all regions, as the allgatherv returns them)
+ *   d_global_nnz      in  uint64[1] on the device, clamped to max_global
+ *   max_local, max_global  host-side bounds (< 2^32) of the two counts
+ *   d_indexes_out_or_null  out uint32[max_local] the intersection, ascending;
+ *                     NULL if only the residual is wanted
+ *   d_count_out       out uint64[1] the size of the intersection
+ * Local indices must be strictly ascending and below n, global indices ascending
+ * (anything else is undefined, except that an index >= n is never written to).
+ * Workspace: okt_workspace_bytes(max_local, 0).
+ */
+int okt_index_intersect_restore(float* d_residual_inout, uint64_t n,
+                                const uint32_t* d_local_idx, const float* d_local_val,
+                                const uint64_t* d_local_nnz, uint64_t max_local,
+                                const uint32_t* d_global_idx, const uint64_t* d_global_nnz,
+                                uint64_t max_global, uint32_t* d_indexes_out_or_null,
+                                uint64_t* d_count_out, void* d_ws, size_t ws_bytes,
+                                void* stream);
 
 #ifdef __cplusplus
 }

@@ -8,6 +8,9 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     okt_accumulate_select,
+    okt_coo_threshold_select,
+    okt_index_intersect_restore,
+    okt_last_hip_error,
     okt_region_partition,
     okt_residual_accumulate,
     okt_sparse_reduce,

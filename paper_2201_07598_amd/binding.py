@@ -19,6 +19,7 @@ c_u32, c_u64, c_sz, c_vp, c_f32, c_int = (ctypes.c_uint32, ctypes.c_uint64, ctyp
 # name -> (restype, argtypes); mirrors include/okt.h
 SIGNATURES = {
     "okt_status_string": (ctypes.c_char_p, [c_int]),
+    "okt_last_hip_error": (ctypes.c_char_p, []),
     "okt_version": (c_int, []),
     "okt_workspace_bytes": (c_sz, [c_u64, c_u32]),
     "okt_sparse_reduce_batch_workspace_bytes": (c_sz, [c_u32, c_u32, c_u32]),
@@ -27,6 +28,10 @@ SIGNATURES = {
     "okt_threshold_select": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_sz, c_vp]),
     "okt_accumulate_select": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp,
                                       c_sz, c_vp]),
+    "okt_coo_threshold_select": (c_int, [c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp,
+                                         c_sz, c_vp]),
+    "okt_index_intersect_restore": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_u64,
+                                            c_vp, c_vp, c_vp, c_sz, c_vp]),
     "okt_region_partition": (c_int, [c_vp, c_vp, c_u64, c_u32, c_vp, c_vp, c_vp]),
     "okt_sparse_reduce": (c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp, c_u64, c_vp,
                                   c_vp, c_vp, c_sz, c_vp]),
@@ -53,6 +58,9 @@ def load_library() -> ctypes.CDLL:
         if not os.path.exists(path):
             raise OktError("load_library", -100,
                            f"{path} is missing: run `python -m paper_2201_07598_amd.build`")
+        # torch first: the library must bind to the HIP runtime torch brings along,
+        # the one that owns the streams and the device memory it is handed
+        _torch()
         lib = ctypes.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
@@ -63,6 +71,10 @@ def load_library() -> ctypes.CDLL:
 
 def okt_status_string(status: int) -> str:
     return load_library().okt_status_string(int(status)).decode()
+
+
+def okt_last_hip_error() -> str:
+    return load_library().okt_last_hip_error().decode()
 
 
 def okt_version() -> int:
@@ -106,7 +118,10 @@ def _stream(stream):
 
 def _check(call, status):
     if status != 0:
-        raise OktError(call, status, okt_status_string(status))
+        text = okt_status_string(status)
+        if status == -3:
+            text += ": " + okt_last_hip_error()
+        raise OktError(call, status, text)
 
 
 def _u64(torch):
@@ -224,3 +239,44 @@ def okt_sparse_reduce_batch(idx_cat, val_cat, chunk_off, lo_hi, B: int, P: int, 
         int(capacity), _ptr(nnz_out, _u64(torch), "nnz_out"),
         _ptr(dense_out, torch.float32, "dense_out", allow_none=True),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(stream)))
+
+
+def okt_coo_threshold_select(idx_in, val_in, nnz_in, threshold, idx_out, val_out, nnz_out, ws,
+                             max_nnz=None, capacity=None, stream=None) -> None:
+    torch = _torch()
+    bound = min(idx_in.numel(), val_in.numel()) if max_nnz is None else int(max_nnz)
+    if bound > idx_in.numel() or bound > val_in.numel():
+        raise ValueError("max_nnz exceeds the input buffers")
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > idx_out.numel() or cap > val_out.numel():
+        raise ValueError("capacity exceeds the output buffers")
+    if nnz_out.numel() < 2 or threshold.numel() < 1 or nnz_in.numel() < 1:
+        raise ValueError("nnz_out needs two elements, threshold and nnz_in one")
+    _check("okt_coo_threshold_select", load_library().okt_coo_threshold_select(
+        _ptr(idx_in, _u32(torch), "idx_in"), _ptr(val_in, torch.float32, "val_in"),
+        _ptr(nnz_in, _u64(torch), "nnz_in"), bound, _ptr(threshold, torch.float32, "threshold"),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
+        _ptr(nnz_out, _u64(torch), "nnz_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
+        _stream(stream)))
+
+
+def okt_index_intersect_restore(residual_inout, local_idx, local_val, local_nnz, global_idx,
+                                global_nnz, count_out, ws, indexes_out=None, max_local=None,
+                                max_global=None, stream=None) -> None:
+    torch = _torch()
+    bound_l = min(local_idx.numel(), local_val.numel()) if max_local is None else int(max_local)
+    bound_g = global_idx.numel() if max_global is None else int(max_global)
+    if bound_l > local_idx.numel() or bound_l > local_val.numel() or bound_g > global_idx.numel():
+        raise ValueError("max_local / max_global exceed the input buffers")
+    if indexes_out is not None and indexes_out.numel() < bound_l:
+        raise ValueError("indexes_out needs max_local elements")
+    if count_out.numel() < 1 or local_nnz.numel() < 1 or global_nnz.numel() < 1:
+        raise ValueError("count_out, local_nnz and global_nnz need one element")
+    _check("okt_index_intersect_restore", load_library().okt_index_intersect_restore(
+        _ptr(residual_inout, torch.float32, "residual_inout"), residual_inout.numel(),
+        _ptr(local_idx, _u32(torch), "local_idx"), _ptr(local_val, torch.float32, "local_val"),
+        _ptr(local_nnz, _u64(torch), "local_nnz"), bound_l,
+        _ptr(global_idx, _u32(torch), "global_idx"), _ptr(global_nnz, _u64(torch), "global_nnz"),
+        bound_g, _ptr(indexes_out, _u32(torch), "indexes_out", allow_none=True),
+        _ptr(count_out, _u64(torch), "count_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
+        _stream(stream)))

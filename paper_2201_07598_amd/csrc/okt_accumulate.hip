@@ -73,5 +73,5 @@ extern "C" int okt_residual_accumulate(const float* d_grad, float* d_residual_in
     const uint64_t blocks = n4 / ACC_TILE4 + 1;
     hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)blocks), dim3(ACC_BLOCK), 0,
                        (hipStream_t)stream, d_grad, d_residual_inout, lr, (uint32_t)n);
-    return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
+    return launch_status();
 }

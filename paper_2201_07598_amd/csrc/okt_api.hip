@@ -4,6 +4,18 @@
 
 namespace okt {
 
+static thread_local hipError_t g_last_hip_error = hipSuccess;
+
+int launch_failed(hipError_t e) {
+    g_last_hip_error = e;
+    return OKT_ERR_HIP;
+}
+
+int launch_status() {
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? OKT_OK : launch_failed(e);
+}
+
 __global__ void zero_words_kernel(uint64_t* p, uint64_t words) {
     uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
@@ -16,12 +28,16 @@ hipError_t launch_zero_words(void* p, uint64_t words, hipStream_t stream) {
     if (blocks > 1024) blocks = 1024;
     hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
                        (uint64_t*)p, words);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) launch_failed(e);
+    return e;
 }
 
 }  // namespace okt
 
 extern "C" {
+
+const char* okt_last_hip_error(void) { return hipGetErrorString(okt::g_last_hip_error); }
 
 const char* okt_status_string(int status) {
     switch (status) {
@@ -39,6 +55,8 @@ size_t okt_workspace_bytes(uint64_t n_max, uint32_t P_max) {
     if (P_max == 0) P_max = 1;
     size_t need = okt::threshold_ws_bytes(n_max);
     size_t s = okt::select_ws_bytes(n_max);
+    if (s > need) need = s;
+    s = okt::restore_ws_bytes(n_max);
     if (s > need) need = s;
     s = okt::reduce_ws_bytes(1, n_max, P_max);
     if (s > need) need = s;

@@ -160,6 +160,11 @@ __global__ void zero_words_kernel(uint64_t* p, uint64_t words);
 
 hipError_t launch_zero_words(void* p, uint64_t words, hipStream_t stream);
 
+// Status of the launches an entry point has just made: OKT_OK, or OKT_ERR_HIP
+// with the runtime's error kept for okt_last_hip_error.
+int launch_status();
+int launch_failed(hipError_t e);
+
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 }  // namespace okt

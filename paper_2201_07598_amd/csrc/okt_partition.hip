@@ -54,5 +54,5 @@ extern "C" int okt_region_partition(const uint32_t* d_idx, const uint64_t* d_nnz
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(partition_kernel, dim3((unsigned)blocks), dim3(256), 0,
                        (hipStream_t)stream, d_idx, d_nnz, n, R, d_bounds_out, d_offsets_out);
-    return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
+    return launch_status();
 }

@@ -371,7 +371,7 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
                        d_idx_cat, d_val_cat, d_chunk_off, d_lo_hi, lo, hi, P, max_width, slots,
                        d_idx_out, d_val_out, capacity, d_nnz_out, d_dense, (char*)d_ws,
                        (uint32_t)region_bytes, table_offset);
-    return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
+    return launch_status();
 }
 
 }  // namespace okt

@@ -32,7 +32,7 @@ extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float*
     if (n > 0xffffffffull) return OKT_ERR_INVALID_ARG;
     if (n == 0) {
         hipLaunchKernelGGL(select_empty_kernel, dim3(1), dim3(1), 0, s, d_nnz_out);
-        return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
+        return launch_status();
     }
     if (!d_acc_inout || !d_threshold || !aligned(d_acc_inout, 16) || !aligned(d_threshold, 4))
         return OKT_ERR_INVALID_ARG;
@@ -50,7 +50,7 @@ extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float*
                        dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_acc_inout, (uint32_t)n,
                        d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out, hdr, seg_desc,
                        group_desc, shape.nseg, shape.piece);
-    return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
+    return launch_status();
 }
 
 extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inout, float lr,
@@ -63,7 +63,7 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
     if (n > 0xffffffffull) return OKT_ERR_INVALID_ARG;
     if (n == 0) {
         hipLaunchKernelGGL(select_empty_kernel, dim3(1), dim3(1), 0, s, d_nnz_out);
-        return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
+        return launch_status();
     }
     if (!d_grad || !d_residual_inout || !d_threshold || d_grad == d_residual_inout ||
         !aligned(d_grad, 16) || !aligned(d_residual_inout, 16) || !aligned(d_threshold, 4))
@@ -82,5 +82,39 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
                        dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout, lr,
                        (uint32_t)n, d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out, hdr,
                        seg_desc, group_desc, shape.nseg, shape.piece);
-    return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
+    return launch_status();
+}
+
+extern "C" int okt_coo_threshold_select(const uint32_t* d_idx_in, const float* d_val_in,
+                                        const uint64_t* d_nnz_in, uint64_t max_nnz,
+                                        const float* d_threshold, uint32_t* d_idx_out,
+                                        float* d_val_out, uint64_t capacity, uint64_t* d_nnz_out,
+                                        void* d_ws, size_t ws_bytes, void* stream) {
+    using namespace okt;
+    hipStream_t s = (hipStream_t)stream;
+    if (!d_nnz_out || !aligned(d_nnz_out, 8)) return OKT_ERR_INVALID_ARG;
+    if (max_nnz > 0xffffffffull) return OKT_ERR_INVALID_ARG;
+    if (max_nnz == 0) {
+        hipLaunchKernelGGL(select_empty_kernel, dim3(1), dim3(1), 0, s, d_nnz_out);
+        return launch_status();
+    }
+    if (!d_idx_in || !d_val_in || !d_nnz_in || !d_threshold || !aligned(d_idx_in, 4) ||
+        !aligned(d_val_in, 16) || !aligned(d_nnz_in, 8) || !aligned(d_threshold, 4))
+        return OKT_ERR_INVALID_ARG;
+    if (capacity > 0 && (!d_idx_out || !d_val_out || !aligned(d_idx_out, 4) ||
+                         !aligned(d_val_out, 4)))
+        return OKT_ERR_INVALID_ARG;
+    const SelectShape shape = select_shape(max_nnz);
+    if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(max_nnz))
+        return OKT_ERR_WORKSPACE;
+    ScanHeader* hdr = (ScanHeader*)d_ws;
+    uint64_t* seg_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
+    uint64_t* group_desc = seg_desc + shape.nseg;
+    if (launch_zero_words(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
+        return OKT_ERR_HIP;
+    hipLaunchKernelGGL((coo_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET>),
+                       dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_idx_in, d_val_in, d_nnz_in,
+                       (uint32_t)max_nnz, d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out,
+                       hdr, seg_desc, group_desc, shape.nseg, shape.piece);
+    return launch_status();
 }

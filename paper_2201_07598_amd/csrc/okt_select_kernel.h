@@ -111,6 +111,20 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
     return count;
 }
 
+// What the select runs over.  DenseSource: a dense vector whose selected elements
+// are zeroed in place (the residual update) and whose positions are the output
+// indices.  CooSource: the value array of a sorted COO list, left untouched; the
+// output index of position i is idx_in[i].
+struct DenseSource {
+    static constexpr bool zero = true;
+    __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return i; }
+};
+struct CooSource {
+    static constexpr bool zero = false;
+    const uint32_t* idx_in;
+    __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return idx_in[i]; }
+};
+
 // Second half of a select: the workgroup publishes its count, learns the count of
 // everything before it from the chained scan, and each wave writes its pairs to
 // their final place.  On entry the wave has seen `count` selected entries in its
@@ -119,9 +133,9 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
 // untouched.  Entries that do not fit the output are put back.  A wave whose
 // stash did not hold everything puts back what it zeroed and walks its piece a
 // second time, writing directly (dense thresholds only).
-template <int BLOCK, int U, int STASH, typename Test>
+template <int BLOCK, int U, int STASH, typename Test, typename Source>
 __device__ __forceinline__ void select_finish(
-    float* __restrict__ acc, Test test, uint32_t* __restrict__ idx_out,
+    float* __restrict__ acc, Test test, Source source, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t seg,
     uint64_t start, uint64_t end, uint32_t count, uint32_t stashed, StashEntry* mine,
@@ -158,21 +172,23 @@ __device__ __forceinline__ void select_finish(
             const uint64_t pos = first + j;
             const StashEntry e = mine[j];
             if (pos < capacity) {
-                idx_out[pos] = e.idx;
+                idx_out[pos] = source.out_index(e.idx);
                 val_out[pos] = e.val;
-            } else {
+            } else if (Source::zero) {
                 acc[e.idx] = e.val;         // output full: the entry stays in the residual
             }
         }
     } else {
-        for (uint32_t j = lane; j < stashed; j += WAVE) acc[mine[j].idx] = mine[j].val;
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // stores land before the re-read
+        if (Source::zero) {
+            for (uint32_t j = lane; j < stashed; j += WAVE) acc[mine[j].idx] = mine[j].val;
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // stores land before the re-read
+        }
         select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
             const uint64_t pos = first + rank;
             if (pos < capacity) {
-                idx_out[pos] = i;
+                idx_out[pos] = source.out_index(i);
                 val_out[pos] = x;
-                acc[i] = 0.0f;
+                if (Source::zero) acc[i] = 0.0f;
             }
         });
     }
@@ -190,9 +206,9 @@ __device__ __forceinline__ void select_finish(
 // the loop, parks the few selected (index, value) pairs in its LDS stash and
 // zeroes them on the spot, while their cache line is still close by: zeroing
 // them later costs a read-modify-write of a line long gone from the caches.
-template <int BLOCK, int U, int STASH, bool TICKET, typename Test>
+template <int BLOCK, int U, int STASH, bool TICKET, typename Test, typename Source>
 __device__ __forceinline__ void select_body(
-    float* __restrict__ acc, uint32_t n, Test test, uint32_t* __restrict__ idx_out,
+    float* __restrict__ acc, uint32_t n, Test test, Source source, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece,
     uint32_t seg, StashEntry (*s_stash)[STASH], uint32_t* s_count, uint32_t* s_before) {
@@ -205,10 +221,10 @@ __device__ __forceinline__ void select_body(
         select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
             if (rank < (uint32_t)STASH) {
                 mine[rank] = StashEntry{i, x};
-                acc[i] = 0.0f;
+                if (Source::zero) acc[i] = 0.0f;
             }
         });
-    select_finish<BLOCK, U, STASH>(acc, test, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
+    select_finish<BLOCK, U, STASH>(acc, test, source, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
                                    group_desc, nseg, seg, start, end, count,
                                    count < (uint32_t)STASH ? count : (uint32_t)STASH, mine,
                                    s_count, s_before);
@@ -304,7 +320,7 @@ __device__ __forceinline__ void accumulate_select_body(
         if (inside[2]) res[i + 2] = out.z;
         if (inside[3]) res[i + 3] = out.w;
     }
-    select_finish<BLOCK, U, STASH>(res, test, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
+    select_finish<BLOCK, U, STASH>(res, test, DenseSource{}, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
                                    group_desc, nseg, seg, start, end, count, stashed, mine,
                                    s_count, s_before);
 }
@@ -329,14 +345,51 @@ __global__ __launch_bounds__(BLOCK) void select_kernel(
     const uint32_t seg = TICKET ? s_seg : blockIdx.x;
     const float th = *d_threshold;
     if (th == th) {
-        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestFloat{__builtin_fabsf(th)}, idx_out,
+        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestFloat{__builtin_fabsf(th)}, DenseSource{}, idx_out,
                                              val_out, capacity, nnz_out, hdr, seg_desc,
                                              group_desc, nseg, piece, seg, s_stash, s_count,
                                              s_before);
     } else {
-        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestKey{magnitude_key(th)}, idx_out, val_out,
+        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestKey{magnitude_key(th)}, DenseSource{}, idx_out, val_out,
                                              capacity, nnz_out, hdr, seg_desc, group_desc, nseg,
                                              piece, seg, s_stash, s_count, s_before);
+    }
+}
+
+// The same selection over the values of a sorted COO list whose length is on the
+// device (at most max_nnz): entries at or above the threshold are copied, in
+// order, with their indices; the input is not modified.
+template <int BLOCK, int U, int STASH, bool TICKET>
+__global__ __launch_bounds__(BLOCK) void coo_select_kernel(
+    const uint32_t* __restrict__ idx_in, const float* __restrict__ val_in,
+    const uint64_t* __restrict__ d_nnz_in, uint32_t max_nnz,
+    const float* __restrict__ d_threshold, uint32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
+    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece) {
+    constexpr int WAVES = BLOCK / WAVE;
+    __shared__ StashEntry s_stash[WAVES][STASH];
+    __shared__ uint32_t s_count[WAVES];
+    __shared__ uint32_t s_seg;
+    __shared__ uint32_t s_before[2];
+    if (TICKET) {
+        if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+        __syncthreads();
+    }
+    const uint32_t seg = TICKET ? s_seg : blockIdx.x;
+    const uint64_t have = *d_nnz_in;
+    const uint32_t n = have < max_nnz ? (uint32_t)have : max_nnz;
+    float* vals = const_cast<float*>(val_in);         // CooSource never writes
+    const float th = *d_threshold;
+    if (th == th) {
+        select_body<BLOCK, U, STASH, TICKET>(vals, n, TestFloat{__builtin_fabsf(th)},
+                                             CooSource{idx_in}, idx_out, val_out, capacity,
+                                             nnz_out, hdr, seg_desc, group_desc, nseg, piece, seg,
+                                             s_stash, s_count, s_before);
+    } else {
+        select_body<BLOCK, U, STASH, TICKET>(vals, n, TestKey{magnitude_key(th)},
+                                             CooSource{idx_in}, idx_out, val_out, capacity,
+                                             nnz_out, hdr, seg_desc, group_desc, nseg, piece, seg,
+                                             s_stash, s_count, s_before);
     }
 }
 

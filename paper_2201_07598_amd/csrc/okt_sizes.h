@@ -55,6 +55,18 @@ inline size_t select_ws_bytes(uint64_t n) {       // header, segment and group d
     return 64 + 8 * (size_t)(t + (t + 63) / 64);
 }
 
+// ---- index intersection and residual restore ----
+constexpr int RST_BLOCK = 256;
+constexpr int RST_ROWS = 4;                              // entries per thread
+constexpr uint32_t RST_TILE = RST_BLOCK * RST_ROWS;      // local entries per workgroup
+inline uint64_t restore_tiles(uint64_t max_local) {
+    return max_local == 0 ? 1 : (max_local + RST_TILE - 1) / RST_TILE;
+}
+inline size_t restore_ws_bytes(uint64_t max_local) {
+    const uint64_t t = restore_tiles(max_local);
+    return 64 + 8 * (size_t)(t + (t + 63) / 64);
+}
+
 // ---- exact threshold (radix select over the 31-bit magnitude key) ----
 constexpr int RS_BITS1 = 11, RS_BITS2 = 11, RS_BITS3 = 9;   // 11 + 11 + 9 = 31
 constexpr int RS_MAX_BINS = 1 << 11;

@@ -360,5 +360,5 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
                        d_acc, cand, state, hist3);
     hipLaunchKernelGGL((radix_pick_kernel<RS_BITS3, true>), dim3(1), dim3(256), 0, s, state,
                        hist3, d_threshold_out, d_count_ge_out);
-    return hipGetLastError() == hipSuccess ? OKT_OK : OKT_ERR_HIP;
+    return launch_status();
 }
