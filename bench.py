@@ -266,6 +266,9 @@ def main():
     # ---------------- sustained reduce over a batch of regions ----------------
     reduce_batch = time_reduce_batch(args, torch, np, okt, wl, w, lo, hi)
 
+    # ---------------- the global stage on this worker's share -----------------
+    global_stage = time_global_stage(torch, np, okt, w, workers, red_idx, red_val, red_nnz)
+
     # ---------------- the oracle on the host cores ----------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -289,6 +292,7 @@ def main():
         "kernels": kernels,
         "reduce_batch": reduce_batch,
         "fused_path": fused_path,
+        "global_stage": global_stage,
     }
     print(json.dumps(out), flush=True)
 
@@ -356,6 +360,62 @@ def time_reduce_batch(args, torch, np, okt, wl, w, lo, hi):
             "algorithmic_bytes": nbytes, "achieved_GBs": round(nbytes / us * 1e-3, 1),
             "frac_of_hbm_peak": round(nbytes / us * 1e-3 / HBM_PEAK_GBS, 4),
             "entries_per_s": B * E1 / (us * 1e-6)}
+
+
+def time_global_stage(torch, np, okt, w, workers, red_idx, red_val, red_nnz):
+    """The calls that follow the reduce (outside the step): global threshold over the
+    reduced values of the own region, global selection on that region, and
+    indexes = local ∩ global with the residual restore.  The global index list is
+    synthetic: every other locally selected index of this worker plus the
+    selection of another simulated worker, about 1.5 k ascending indices."""
+    dev = "cuda:0"
+    st, other = workers[0], workers[1 % len(workers)]
+    U = int(red_nnz.cpu().numpy().view(np.uint64)[0])
+    L = int(st.nnz.cpu().numpy().view(np.uint64)[0])
+    Lo = int(other.nnz.cpu().numpy().view(np.uint64)[0])
+    kg = max(w.k // w.P, 1)
+    g_idx = torch.unique(torch.cat([st.idx[:L:2], other.idx[:Lo]]), sorted=True).contiguous()
+    G = int(g_idx.numel())
+    g_nnz = torch.tensor([G], dtype=torch.int64, device=dev)
+    gth = torch.zeros(1, dtype=torch.float32, device=dev)
+    gcnt = torch.zeros(1, dtype=torch.int64, device=dev)
+    sel_idx = torch.zeros(max(U, 1), dtype=torch.int32, device=dev)
+    sel_val = torch.zeros(max(U, 1), dtype=torch.float32, device=dev)
+    sel_nnz = torch.zeros(2, dtype=torch.int64, device=dev)
+    inter = torch.zeros(st.cap, dtype=torch.int32, device=dev)
+    icnt = torch.zeros(1, dtype=torch.int64, device=dev)
+    vals = red_val[:U]
+    sel_idx2 = torch.zeros(st.cap, dtype=torch.int32, device=dev)
+    sel_val2 = torch.zeros(st.cap, dtype=torch.float32, device=dev)
+    sel_nnz2 = torch.zeros(2, dtype=torch.int64, device=dev)
+    calls = {
+        "global_threshold": lambda: okt.okt_topk_threshold_exact(vals, min(kg, U), gth, gcnt, st.ws),
+        "global_select": lambda: okt.okt_coo_threshold_select(
+            red_idx, red_val, red_nnz[:1], gth, sel_idx, sel_val, sel_nnz, st.ws, max_nnz=U),
+        "intersect_restore": lambda: okt.okt_index_intersect_restore(
+            st.residual, st.idx, st.val, st.nnz[:1], g_idx, g_nnz, icnt, st.ws, indexes_out=inter,
+            max_local=L),
+        "intersect_zero": lambda: okt.okt_index_intersect_zero(
+            other.residual, st.idx, st.nnz[:1], g_idx, g_nnz, icnt, st.ws, indexes_out=inter,
+            max_local=L),
+        "select_copy": lambda: okt.okt_threshold_select_copy(
+            workers[2 % len(workers)].residual, st.th, sel_idx2, sel_val2, sel_nnz2, st.ws),
+    }
+    out = {"reduced_entries": U, "region_k": min(kg, U), "local_entries": L, "global_entries": G}
+    for name, fn in calls.items():
+        times = []
+        for rep in range(10):
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b) * 1e3)
+        out[name + "_us"] = round(float(np.median(times[2:])), 2)
+    out["global_selected"] = int(sel_nnz.cpu().numpy().view(np.uint64)[1])
+    out["intersection"] = int(icnt.cpu().numpy().view(np.uint64)[0])
+    return out
 
 
 def cpu_baseline(np, w, grads, contrib, lo, hi):

@@ -116,6 +116,17 @@ int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshol
                          uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same selection and packaging without the residual update: d_acc is only
+ * read.  For callers that follow Algorithm 2, line 6 to the letter and zero the
+ * entries of `indexes` (the locally selected entries that reached the global
+ * top-k) after the allreduce, with okt_index_intersect_zero; the pass then has
+ * no scattered store into the dense vector.  Outputs as okt_threshold_select.
+ */
+int okt_threshold_select_copy(const float* d_acc, uint64_t n, const float* d_threshold,
+                              uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                              uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
  * The accumulate and the threshold selection of one iteration in a single pass,
  * for the iterations that reuse a threshold (Sec. 3.1.3: the threshold is
  * re-evaluated only every tau' iterations, so in between it is known before the
@@ -260,6 +271,19 @@ int okt_index_intersect_restore(float* d_residual_inout, uint64_t n,
                                 uint64_t max_global, uint32_t* d_indexes_out_or_null,
                                 uint64_t* d_count_out, void* d_ws, size_t ws_bytes,
                                 void* stream);
+
+/*
+ * The same `indexes`, applied to an accumulator that was left untouched by
+ * okt_threshold_select_copy: eps = acc with +0.0f written at `indexes`
+ * (Algorithm 2, line 6, literally).  Arguments as okt_index_intersect_restore,
+ * without the local values.  Ends in the same residual, bit for bit, as
+ * okt_threshold_select followed by okt_index_intersect_restore.
+ */
+int okt_index_intersect_zero(float* d_acc_inout, uint64_t n, const uint32_t* d_local_idx,
+                             const uint64_t* d_local_nnz, uint64_t max_local,
+                             const uint32_t* d_global_idx, const uint64_t* d_global_nnz,
+                             uint64_t max_global, uint32_t* d_indexes_out_or_null,
+                             uint64_t* d_count_out, void* d_ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

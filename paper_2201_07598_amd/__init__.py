@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     okt_accumulate_select,
     okt_coo_threshold_select,
     okt_index_intersect_restore,
+    okt_index_intersect_zero,
     okt_last_hip_error,
     okt_region_partition,
     okt_residual_accumulate,
@@ -18,6 +19,7 @@ from .binding import (  # noqa: F401
     okt_sparse_reduce_batch_workspace_bytes,
     okt_status_string,
     okt_threshold_select,
+    okt_threshold_select_copy,
     okt_topk_threshold_exact,
     okt_version,
     okt_workspace_bytes,

@@ -26,6 +26,9 @@ SIGNATURES = {
     "okt_residual_accumulate": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp]),
     "okt_topk_threshold_exact": (c_int, [c_vp, c_u64, c_u64, c_vp, c_vp, c_vp, c_sz, c_vp]),
     "okt_threshold_select": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_sz, c_vp]),
+    "okt_threshold_select_copy": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_sz, c_vp]),
+    "okt_index_intersect_zero": (c_int, [c_vp, c_u64, c_vp, c_vp, c_u64, c_vp, c_vp, c_u64, c_vp, c_vp,
+                                         c_vp, c_sz, c_vp]),
     "okt_accumulate_select": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp,
                                       c_sz, c_vp]),
     "okt_coo_threshold_select": (c_int, [c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp,
@@ -157,19 +160,25 @@ def okt_topk_threshold_exact(acc, k: int, threshold_out, count_ge_out, ws, strea
 
 
 def okt_threshold_select(acc_inout, threshold, idx_out, val_out, nnz_out, ws, capacity=None,
-                         stream=None) -> None:
+                         stream=None, _call="okt_threshold_select") -> None:
     torch = _torch()
     cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
     if cap > idx_out.numel() or cap > val_out.numel():
         raise ValueError("capacity exceeds the output buffers")
     if nnz_out.numel() < 2 or threshold.numel() < 1:
         raise ValueError("nnz_out needs two elements, threshold one")
-    _check("okt_threshold_select", load_library().okt_threshold_select(
+    _check(_call, getattr(load_library(), _call)(
         _ptr(acc_inout, torch.float32, "acc_inout"), acc_inout.numel(),
         _ptr(threshold, torch.float32, "threshold"),
         _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
         _ptr(nnz_out, _u64(torch), "nnz_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
         _stream(stream)))
+
+
+def okt_threshold_select_copy(acc, threshold, idx_out, val_out, nnz_out, ws, capacity=None,
+                              stream=None) -> None:
+    okt_threshold_select(acc, threshold, idx_out, val_out, nnz_out, ws, capacity=capacity,
+                         stream=stream, _call="okt_threshold_select_copy")
 
 
 def okt_accumulate_select(grad, residual_inout, lr: float, threshold, idx_out, val_out, nnz_out, ws,
@@ -278,5 +287,27 @@ def okt_index_intersect_restore(residual_inout, local_idx, local_val, local_nnz,
         _ptr(local_nnz, _u64(torch), "local_nnz"), bound_l,
         _ptr(global_idx, _u32(torch), "global_idx"), _ptr(global_nnz, _u64(torch), "global_nnz"),
         bound_g, _ptr(indexes_out, _u32(torch), "indexes_out", allow_none=True),
+        _ptr(count_out, _u64(torch), "count_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
+        _stream(stream)))
+
+
+def okt_index_intersect_zero(acc_inout, local_idx, local_nnz, global_idx, global_nnz, count_out, ws,
+                             indexes_out=None, max_local=None, max_global=None,
+                             stream=None) -> None:
+    torch = _torch()
+    bound_l = local_idx.numel() if max_local is None else int(max_local)
+    bound_g = global_idx.numel() if max_global is None else int(max_global)
+    if bound_l > local_idx.numel() or bound_g > global_idx.numel():
+        raise ValueError("max_local / max_global exceed the input buffers")
+    if indexes_out is not None and indexes_out.numel() < bound_l:
+        raise ValueError("indexes_out needs max_local elements")
+    if count_out.numel() < 1 or local_nnz.numel() < 1 or global_nnz.numel() < 1:
+        raise ValueError("count_out, local_nnz and global_nnz need one element")
+    _check("okt_index_intersect_zero", load_library().okt_index_intersect_zero(
+        _ptr(acc_inout, torch.float32, "acc_inout"), acc_inout.numel(),
+        _ptr(local_idx, _u32(torch), "local_idx"), _ptr(local_nnz, _u64(torch), "local_nnz"),
+        bound_l, _ptr(global_idx, _u32(torch), "global_idx"),
+        _ptr(global_nnz, _u64(torch), "global_nnz"), bound_g,
+        _ptr(indexes_out, _u32(torch), "indexes_out", allow_none=True),
         _ptr(count_out, _u64(torch), "count_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
         _stream(stream)))

@@ -22,19 +22,21 @@ __global__ void select_empty_kernel(uint64_t* nnz_out) {
 
 }  // namespace okt
 
-extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshold,
-                                    uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
-                                    uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes,
-                                    void* stream) {
-    using namespace okt;
-    hipStream_t s = (hipStream_t)stream;
+namespace okt {
+
+// The dense select, with (Source = DenseSource) or without (DenseCopySource) the
+// zeroing of the emitted entries.
+template <typename Source>
+static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshold,
+                               uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                               uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes, hipStream_t s) {
     if (!d_nnz_out || !aligned(d_nnz_out, 8)) return OKT_ERR_INVALID_ARG;
     if (n > 0xffffffffull) return OKT_ERR_INVALID_ARG;
     if (n == 0) {
         hipLaunchKernelGGL(select_empty_kernel, dim3(1), dim3(1), 0, s, d_nnz_out);
         return launch_status();
     }
-    if (!d_acc_inout || !d_threshold || !aligned(d_acc_inout, 16) || !aligned(d_threshold, 4))
+    if (!d_acc || !d_threshold || !aligned(d_acc, 16) || !aligned(d_threshold, 4))
         return OKT_ERR_INVALID_ARG;
     if (capacity > 0 && (!d_idx_out || !d_val_out || !aligned(d_idx_out, 4) ||
                          !aligned(d_val_out, 4)))
@@ -46,11 +48,32 @@ extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float*
     uint64_t* group_desc = seg_desc + shape.nseg;
     if (launch_zero_words(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
-    hipLaunchKernelGGL((select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET>),
-                       dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_acc_inout, (uint32_t)n,
-                       d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out, hdr, seg_desc,
-                       group_desc, shape.nseg, shape.piece);
+    hipLaunchKernelGGL((select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET, Source>),
+                       dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_acc, (uint32_t)n, d_threshold,
+                       d_idx_out, d_val_out, capacity, d_nnz_out, hdr, seg_desc, group_desc,
+                       shape.nseg, shape.piece);
     return launch_status();
+}
+
+}  // namespace okt
+
+extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshold,
+                                    uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                                    uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes,
+                                    void* stream) {
+    return okt::launch_dense_select<okt::DenseSource>(d_acc_inout, n, d_threshold, d_idx_out,
+                                                      d_val_out, capacity, d_nnz_out, d_ws,
+                                                      ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int okt_threshold_select_copy(const float* d_acc, uint64_t n, const float* d_threshold,
+                                         uint32_t* d_idx_out, float* d_val_out,
+                                         uint64_t capacity, uint64_t* d_nnz_out, void* d_ws,
+                                         size_t ws_bytes, void* stream) {
+    // DenseCopySource never writes through the pointer
+    return okt::launch_dense_select<okt::DenseCopySource>(
+        const_cast<float*>(d_acc), n, d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out, d_ws,
+        ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inout, float lr,

@@ -113,10 +113,14 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
 
 // What the select runs over.  DenseSource: a dense vector whose selected elements
 // are zeroed in place (the residual update) and whose positions are the output
-// indices.  CooSource: the value array of a sorted COO list, left untouched; the
+// indices; DenseCopySource: the same without the zeroing.  CooSource: the value array of a sorted COO list, left untouched; the
 // output index of position i is idx_in[i].
 struct DenseSource {
     static constexpr bool zero = true;
+    __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return i; }
+};
+struct DenseCopySource {                     // a dense vector that is only read
+    static constexpr bool zero = false;
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return i; }
 };
 struct CooSource {
@@ -325,7 +329,7 @@ __device__ __forceinline__ void accumulate_select_body(
                                    s_count, s_before);
 }
 
-template <int BLOCK, int U, int STASH, bool TICKET>
+template <int BLOCK, int U, int STASH, bool TICKET, typename Source = DenseSource>
 __global__ __launch_bounds__(BLOCK) void select_kernel(
     float* __restrict__ acc, uint32_t n, const float* __restrict__ d_threshold,
     uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
@@ -345,12 +349,12 @@ __global__ __launch_bounds__(BLOCK) void select_kernel(
     const uint32_t seg = TICKET ? s_seg : blockIdx.x;
     const float th = *d_threshold;
     if (th == th) {
-        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestFloat{__builtin_fabsf(th)}, DenseSource{}, idx_out,
+        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestFloat{__builtin_fabsf(th)}, Source{}, idx_out,
                                              val_out, capacity, nnz_out, hdr, seg_desc,
                                              group_desc, nseg, piece, seg, s_stash, s_count,
                                              s_before);
     } else {
-        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestKey{magnitude_key(th)}, DenseSource{}, idx_out, val_out,
+        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestKey{magnitude_key(th)}, Source{}, idx_out, val_out,
                                              capacity, nnz_out, hdr, seg_desc, group_desc, nseg,
                                              piece, seg, s_stash, s_count, s_before);
     }

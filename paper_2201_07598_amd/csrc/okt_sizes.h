@@ -59,6 +59,7 @@ inline size_t select_ws_bytes(uint64_t n) {       // header, segment and group d
 constexpr int RST_BLOCK = 256;
 constexpr int RST_ROWS = 4;                              // entries per thread
 constexpr uint32_t RST_TILE = RST_BLOCK * RST_ROWS;      // local entries per workgroup
+constexpr uint32_t RST_WINDOW = 4096;                    // global entries a workgroup stages in LDS
 inline uint64_t restore_tiles(uint64_t max_local) {
     return max_local == 0 ? 1 : (max_local + RST_TILE - 1) / RST_TILE;
 }

@@ -99,14 +99,15 @@ def test_coo_select_device_count_capacity_and_odd_thresholds():
 
 
 # ----------------------------------------------- indexes and residual update
-def gpu_restore(acc, local_idx, global_idx, want_indexes=True, slack_l=0, slack_g=0):
-    """The residual as the select leaves it (all local entries zeroed), then the
-    library's intersect + restore."""
-    n = acc.size
+def gpu_restore(acc, local_idx, global_idx, want_indexes=True, slack_l=0, slack_g=0, zero=False):
+    """zero=False: the residual as the select leaves it (all local entries
+    zeroed), then the library's intersect + restore.  zero=True: the untouched
+    accumulator, then the library's intersect + zero."""
     residual = acc.copy()
-    residual[local_idx.astype(np.int64)] = 0.0
+    if not zero:
+        residual[local_idx.astype(np.int64)] = 0.0
     local_val = acc[local_idx.astype(np.int64)]
-    d_res = to_dev(residual) if n else torch.zeros(1, dtype=torch.float32, device=DEV)[:0]
+    d_res = to_dev(residual)
     d_li = padded(local_idx, slack_l + 1, 0)
     d_lv = padded(local_val, slack_l + 1, np.float32(123.0))
     d_gi = padded(global_idx, slack_g + 1, 0)
@@ -116,8 +117,13 @@ def gpu_restore(acc, local_idx, global_idx, want_indexes=True, slack_l=0, slack_
     out = torch.full((max(bound_l, 1),), -1, dtype=torch.int32, device=DEV) if want_indexes else None
     cnt = torch.full((1,), -5, dtype=torch.int64, device=DEV)
     ws = workspace(okt.okt_workspace_bytes(max(bound_l, 1), 0))
-    okt.okt_index_intersect_restore(d_res, d_li, d_lv, d_ln, d_gi, d_gn, cnt, ws, indexes_out=out,
-                                    max_local=bound_l, max_global=global_idx.size + slack_g)
+    if zero:
+        okt.okt_index_intersect_zero(d_res, d_li, d_ln, d_gi, d_gn, cnt, ws, indexes_out=out,
+                                     max_local=bound_l, max_global=global_idx.size + slack_g)
+    else:
+        okt.okt_index_intersect_restore(d_res, d_li, d_lv, d_ln, d_gi, d_gn, cnt, ws,
+                                        indexes_out=out, max_local=bound_l,
+                                        max_global=global_idx.size + slack_g)
     torch.cuda.synchronize()
     c = int(u64(cnt)[0])
     return d_res.cpu().numpy(), (u32(out[:c]) if want_indexes else None), c
@@ -125,8 +131,9 @@ def gpu_restore(acc, local_idx, global_idx, want_indexes=True, slack_l=0, slack_
 
 @pytest.mark.parametrize("nl,ng", [(0, 0), (0, 50), (50, 0), (1, 1), (1023, 700), (1024, 1024),
                                    (1025, 3), (5000, 5000), (200_003, 150_001),
-                                   (64 * 1024 + 1, 400_000), (300_000, 17)])
-def test_intersect_restore_bitwise(nl, ng):
+                                   (64 * 1024 + 1, 400_000), (300_000, 17), (900, 3_000_000)])
+@pytest.mark.parametrize("zero", [False, True])
+def test_intersect_restore_bitwise(nl, ng, zero):
     n = max(4 * max(nl, ng), 64)
     acc = lap(nl * 7 + ng, n)
     local_idx = sorted_indices(nl + 11, n, nl)
@@ -137,12 +144,12 @@ def test_intersect_restore_bitwise(nl, ng):
     global_idx = np.unique(np.concatenate([from_local, others]).astype(np.uint32))
     indexes = orc.index_intersection(local_idx, global_idx)
     eps = orc.residual_update(acc, indexes)
-    res, gidx, count = gpu_restore(acc, local_idx, global_idx)
+    res, gidx, count = gpu_restore(acc, local_idx, global_idx, zero=zero)
     assert count == indexes.size
     assert np.array_equal(gidx, indexes)
     assert bits_equal(res, eps)
     res, _, count = gpu_restore(acc, local_idx, global_idx, want_indexes=False, slack_l=333,
-                                slack_g=77)
+                                slack_g=77, zero=zero)
     assert count == indexes.size and bits_equal(res, eps)
 
 
@@ -163,10 +170,33 @@ def test_intersect_restore_special_lists():
     }
     for name, global_idx in cases.items():
         indexes = orc.index_intersection(local_idx, global_idx)
-        res, gidx, count = gpu_restore(acc, local_idx, global_idx)
-        assert count == indexes.size, name
-        assert np.array_equal(gidx, indexes), name
-        assert bits_equal(res, orc.residual_update(acc, indexes)), name
+        for zero in (False, True):
+            res, gidx, count = gpu_restore(acc, local_idx, global_idx, zero=zero)
+            assert count == indexes.size, name
+            assert np.array_equal(gidx, indexes), name
+            assert bits_equal(res, orc.residual_update(acc, indexes)), name
+
+
+@pytest.mark.parametrize("n", [1, 255, 4097, 1_000_003, 5_000_011])
+def test_select_copy_leaves_the_accumulator(n):
+    acc = lap(n + 9, n)
+    k = max(n // 100, 1)
+    th, _ = orc.topk_threshold_exact(acc, k, method="partition")
+    for cap in (None, k // 2):
+        ri, rv, _, rtotal = orc.threshold_select(acc, th, capacity=cap)
+        d_acc = to_dev(acc)
+        size = max(2 * k if cap is None else cap, 1)
+        idx = torch.full((size,), -1, dtype=torch.int32, device=DEV)
+        val = torch.zeros(size, dtype=torch.float32, device=DEV)
+        nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+        ws = workspace(okt.okt_workspace_bytes(n, 0))
+        okt.okt_threshold_select_copy(d_acc, to_dev(np.array([th], dtype=np.float32)), idx, val,
+                                      nnz, ws, capacity=(size if cap is None else cap))
+        torch.cuda.synchronize()
+        c = u64(nnz)
+        assert (int(c[0]), int(c[1])) == (ri.size, rtotal)
+        assert np.array_equal(u32(idx[:ri.size]), ri) and bits_equal(val[:ri.size].cpu().numpy(), rv)
+        assert bits_equal(d_acc.cpu().numpy(), acc)
 
 
 # ------------------------------------------------ the whole algorithm, P workers
@@ -190,7 +220,11 @@ def test_allreduce_and_residuals_over_simulated_workers(name, n, P):
         path = GpuPath(n, 2 * k)
         path.accumulate(to_dev(g), w.lr)
         path.threshold(k)
-        path.select()
+        if p % 2 == 0:
+            path.select()                            # zero now, put back later
+        else:                                        # keep acc, zero `indexes` later
+            okt.okt_threshold_select_copy(path.residual, path.th, path.idx, path.val, path.nnz,
+                                          path.ws, capacity=path.capacity)
         gi, gv, emitted, total = path.selected()
         assert total == li.size and np.array_equal(gi, li) and bits_equal(gv, lv)
         gpu_paths.append(path)
@@ -245,8 +279,12 @@ def test_allreduce_and_residuals_over_simulated_workers(name, n, P):
         eps = orc.residual_update(accs[p], indexes)
         out = torch.full((path.capacity,), -1, dtype=torch.int32, device=DEV)
         cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
-        okt.okt_index_intersect_restore(path.residual, path.idx, path.val, path.nnz[:1], d_u, d_un,
-                                        cnt, path.ws, indexes_out=out)
+        if p % 2 == 0:
+            okt.okt_index_intersect_restore(path.residual, path.idx, path.val, path.nnz[:1], d_u,
+                                            d_un, cnt, path.ws, indexes_out=out)
+        else:
+            okt.okt_index_intersect_zero(path.residual, path.idx, path.nnz[:1], d_u, d_un, cnt,
+                                         path.ws, indexes_out=out)
         c = int(u64(cnt)[0])
         assert c == indexes.size and np.array_equal(u32(out[:c]), indexes), p
         assert bits_equal(path.residual.cpu().numpy(), eps), p
