@@ -150,7 +150,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
     uint64_t* nnz = nnz_out + 2 * (size_t)region;
     const bool ranked = slots > RED_C;           // accumulators indexed by rank, not by slot
-    const uint32_t words_all = slots / 32;       // slots is a multiple of RED_C
+    const uint32_t words_all = slots / 32;       // slots is a multiple of 32
     for (uint32_t w = tid; w < words_all; w += RED_BLOCK) s_bits[w] = 0;
     __syncthreads();
     const uint32_t tile = s_tile;
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
                 for (uint32_t q = tid; q < np; q += RED_BLOCK) {
                     const uint32_t b = row0[p0 + q], e = row1[p0 + q];
                     s_start[q] = off[p0 + q] + b;
-                    s_len[q] = e - b;
+                    s_len[q] = e > b ? e - b : 0u;      // e < b only for unsorted input
                 }
                 __syncthreads();
                 if (tid == 0) s_loaded_p0 = p0;

@@ -107,15 +107,18 @@ constexpr uint32_t RED_S_MAX = OKT_RED_S_MAX;   // widest tile (bits in the bitm
 constexpr int RED_CHUNKS = 256;                 // contributions handled per sweep
 
 // Tile width for a region `width` wide whose union is expected to hold at most
-// `expected` entries: the widest power-of-two multiple of RED_C that keeps the
-// expected number of hit slots per tile below 70 % of the accumulators.
+// `expected` entries: RED_C slots where the region is densely hit (accumulator =
+// slot), else as wide - any multiple of 32 slots up to RED_S_MAX - as keeps the
+// expected number of hit slots per tile at OKT_RED_FILL of the accumulators.
+#ifndef OKT_RED_FILL
+#define OKT_RED_FILL 0.9
+#endif
 inline uint32_t reduce_tile_slots(uint64_t width, uint64_t expected) {
-    uint32_t slots = RED_C;
-    if (width == 0) return slots;
-    while (slots < RED_S_MAX && slots < width &&
-           (double)(2 * slots) * (double)expected <= 0.7 * RED_C * (double)width)
-        slots *= 2;
-    return slots;
+    if (width == 0 || expected == 0) return expected == 0 && width > RED_C ? RED_S_MAX : RED_C;
+    const double want = OKT_RED_FILL * RED_C * (double)width / (double)expected;
+    if (want >= RED_S_MAX) return RED_S_MAX;
+    const uint32_t slots = (uint32_t)want / 32 * 32;
+    return slots < RED_C ? RED_C : slots;
 }
 inline uint64_t reduce_tiles(uint64_t width, uint32_t slots) { return (width + slots - 1) / slots; }
 // per region: a 64-byte header, one descriptor per tile and one per 64 tiles,

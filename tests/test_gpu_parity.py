@@ -381,6 +381,62 @@ def test_reduce_tile_modes():
     assert got["total"] == cl.size
 
 
+def test_reduce_paper_shaped_regions():
+    """The shapes of the paper's runs (16 .. 64 contributions hitting 6 .. 30 % of a
+    region) and what can go wrong around them, steered by the density estimate
+    (the capacity) and the data: identical supports (many entries per hit slot),
+    more hit slots than accumulators (several rounds), accumulator = slot, tile
+    widths that are no power of two and end inside a 32-slot bitmap word, empty
+    tiles between full ones, empty contributions, a region of one slot."""
+    rng = np.random.default_rng(123)
+    # 16 contributions, 16 % of the slots hit: the shape of a ResNet-sized run
+    width, P, m = 100_003, 16, 1000
+    parts = [np.sort(rng.choice(width, m, replace=False)).astype(np.uint32) + np.uint32(77) for _ in range(P)]
+    cat_i = np.concatenate(parts)
+    cat_v = lap(500, cat_i.size)
+    off = np.arange(P + 1, dtype=np.uint64) * m
+    got, ref = check_reduce(cat_i, cat_v, off, 77, 77 + width)
+    assert ref["hits"].max() >= 2
+    check_reduce(cat_i, cat_v, off, 77, 77 + width, capacity=P * m // 3)   # truncated output
+    check_reduce(cat_i, cat_v, off, 5077, 60_001)                       # entries outside the region
+    # every contribution has the same support: 12 x the entries a tile's registers hold
+    same = np.sort(rng.choice(60_000, 6000, replace=False)).astype(np.uint32)
+    cat_i = np.tile(same, 12)
+    cat_v = lap(501, cat_i.size)
+    off = np.arange(13, dtype=np.uint64) * same.size
+    got, ref = check_reduce(cat_i, cat_v, off, 0, 60_000, capacity=6000)
+    assert got["total"] == 6000 and ref["hits"].min() == 12
+    # estimated sparse (wide ranked tiles), in fact every slot hit: 16 rounds per tile
+    full = np.arange(300, 50_300, dtype=np.uint32)
+    cat_i = np.tile(full, 3)
+    cat_v = lap(502, cat_i.size)
+    off = np.arange(4, dtype=np.uint64) * full.size
+    got, _ = check_reduce(cat_i, cat_v, off, 300, 50_300, capacity=2500)
+    assert got["total"] == 50_000 and got["emitted"] == 2500
+    check_reduce(cat_i, cat_v, off, 0, 70_001, capacity=70_001)         # accumulator = slot
+    # a cluster and a desert in one region
+    cl = np.unique(np.concatenate([np.arange(20_000, 23_000), rng.choice(400_000, 30_000, replace=False)]))
+    cl = cl.astype(np.uint32)
+    cl = cl[(cl < 100_000) | (cl > 200_000)]
+    two = [cl, cl[::3]]
+    cat_i = np.concatenate(two)
+    got, _ = check_reduce(cat_i, lap(503, cat_i.size), np.array([0, cl.size, cat_i.size], np.uint64),
+                          0, 400_000)
+    assert got["total"] == cl.size
+    # 64 and 65 contributions take different kernels and must agree with the oracle alike
+    for P in (64, 65):
+        parts = [np.sort(rng.choice(80_000, 300, replace=False)).astype(np.uint32) for _ in range(P)]
+        cat_i = np.concatenate(parts)
+        check_reduce(cat_i, lap(504 + P, cat_i.size), np.arange(P + 1, dtype=np.uint64) * 300, 0, 80_000)
+    # empty contributions among the 64, a single entry, a region of one slot
+    lens = np.array([0, 5, 0, 0, 700, 0, 1] + [0] * 57)
+    parts = [np.sort(rng.choice(9000, n, replace=False)).astype(np.uint32) for n in lens]
+    cat_i = np.concatenate(parts)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint64)
+    check_reduce(cat_i, lap(600, cat_i.size), off, 0, 9000)
+    check_reduce(cat_i, lap(600, cat_i.size), off, int(cat_i[5]), int(cat_i[5]) + 1)
+
+
 def test_reduce_disjoint_contributions_fill_in():
     # non-overlapping indexes: the union is the sum of the sizes and every value
     # is a bit copy (the fill-in arithmetic of the paper's Introduction)
