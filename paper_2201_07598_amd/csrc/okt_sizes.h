@@ -104,7 +104,10 @@ constexpr uint32_t RED_C = OKT_RED_C;           // accumulators per tile and rou
 #define OKT_RED_S_MAX 32768
 #endif
 constexpr uint32_t RED_S_MAX = OKT_RED_S_MAX;   // widest tile (bits in the bitmap)
-constexpr int RED_CHUNKS = 256;                 // contributions handled per sweep
+#ifndef OKT_RED_CHUNKS
+#define OKT_RED_CHUNKS 256
+#endif
+constexpr int RED_CHUNKS = OKT_RED_CHUNKS;      // contributions handled per sweep
 
 // Tile width for a region `width` wide whose union is expected to hold at most
 // `expected` entries: RED_C slots where the region is densely hit (accumulator =
