@@ -195,6 +195,27 @@ int okt_sparse_reduce(const uint32_t* d_idx_cat, const float* d_val_cat,
                       void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same reduction with the contributions given as P arbitrary slices
+ * [d_seg_begin[p], d_seg_end[p]) of d_idx_cat / d_val_cat (both uint64[P] on the
+ * device; an end below its begin reads as an empty slice).  This is the shape of
+ * a reduction that takes its contributions in buckets and overlaps with the
+ * exchange (Sec. 3.1.1, bucketing): the partial result of the buckets so far is
+ * one more slice of the next call.  With two buffers in turn nothing is copied:
+ * a call writes its output to the front of the other buffer, where the pieces of
+ * the next bucket are received behind it, and its d_nnz_out points at the end
+ * word of that slice (begin 0, so the emitted count is the end; the word after it
+ * takes the total, so the partial result is listed last and the vector has one
+ * spare word).  Each call rounds its sums to fp32 once; over K buckets a value is
+ * rounded K times.
+ */
+int okt_sparse_reduce_segments(const uint32_t* d_idx_cat, const float* d_val_cat,
+                               const uint64_t* d_seg_begin, const uint64_t* d_seg_end,
+                               uint32_t P, uint32_t lo, uint32_t hi, uint32_t* d_idx_out,
+                               float* d_val_out, uint64_t capacity, uint64_t* d_nnz_out,
+                               float* d_dense_out_or_null, void* d_ws, size_t ws_bytes,
+                               void* stream);
+
+/*
  * The same reduction for B independent regions in one launch (all regions a
  * worker owns in one bucket, or the regions of several simulated workers).
  * Region j has P contributions described by d_chunk_off[j*(P+1) .. j*(P+1)+P]

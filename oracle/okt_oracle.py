@@ -180,6 +180,26 @@ def sparse_reduce(idx_cat: np.ndarray, val_cat: np.ndarray, chunk_off: np.ndarra
     }
 
 
+def sparse_reduce_bucketed(buckets, lo: int, hi: int):
+    """The local reduction taken bucket by bucket (Sec. 3.1.1: the exchange is cut
+    into buckets so that the reduction of one overlaps the transfer of the next).
+    `buckets` is a list of (idx_cat, val_cat, chunk_off) triples.  The partial
+    result so far - already rounded to fp32 - joins the next bucket as one more
+    contribution, listed last; each step is sparse_reduce.  Returns the final dict
+    of sparse_reduce (abs_sum and hits of the last step only)."""
+    partial = None
+    for idx_cat, val_cat, chunk_off in buckets:
+        idx_cat = np.asarray(idx_cat, dtype=np.uint32)
+        val_cat = np.asarray(val_cat, dtype=np.float32)
+        chunk_off = np.asarray(chunk_off, dtype=np.uint64)
+        if partial is not None:
+            idx_cat = np.concatenate([idx_cat, partial["idx"]])
+            val_cat = np.concatenate([val_cat, partial["val"]])
+            chunk_off = np.concatenate([chunk_off, [chunk_off[-1] + np.uint64(partial["idx"].size)]])
+        partial = sparse_reduce(idx_cat, val_cat, chunk_off.astype(np.uint64), lo, hi)
+    return partial
+
+
 def coo_threshold_select(idx: np.ndarray, val: np.ndarray, th, capacity: int | None = None):
     """Global top-k selection on a reduced sparse region (Sec. 3.1.2: each
     worker selects the global top-k values from the reduced top-k values of its

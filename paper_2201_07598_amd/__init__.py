@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     okt_sparse_reduce,
     okt_sparse_reduce_batch,
     okt_sparse_reduce_batch_workspace_bytes,
+    okt_sparse_reduce_segments,
     okt_status_string,
     okt_threshold_select,
     okt_threshold_select_copy,

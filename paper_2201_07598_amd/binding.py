@@ -38,6 +38,8 @@ SIGNATURES = {
     "okt_region_partition": (c_int, [c_vp, c_vp, c_u64, c_u32, c_vp, c_vp, c_vp]),
     "okt_sparse_reduce": (c_int, [c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp, c_u64, c_vp,
                                   c_vp, c_vp, c_sz, c_vp]),
+    "okt_sparse_reduce_segments": (c_int, [c_vp, c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp, c_u64,
+                                           c_vp, c_vp, c_vp, c_sz, c_vp]),
     "okt_sparse_reduce_batch": (c_int, [c_vp, c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp,
                                         c_u64, c_vp, c_vp, c_vp, c_sz, c_vp]),
 }
@@ -311,3 +313,26 @@ def okt_index_intersect_zero(acc_inout, local_idx, local_nnz, global_idx, global
         _ptr(indexes_out, _u32(torch), "indexes_out", allow_none=True),
         _ptr(count_out, _u64(torch), "count_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
         _stream(stream)))
+
+
+def okt_sparse_reduce_segments(idx_cat, val_cat, seg_begin, seg_end, P: int, lo: int, hi: int,
+                               idx_out, val_out, nnz_out, ws, dense_out=None, capacity=None,
+                               stream=None) -> None:
+    torch = _torch()
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > idx_out.numel() or cap > val_out.numel():
+        raise ValueError("capacity exceeds the output buffers")
+    if seg_begin.numel() < P or seg_end.numel() < P:
+        raise ValueError("seg_begin and seg_end need P elements")
+    if dense_out is not None and dense_out.numel() < hi - lo:
+        raise ValueError("dense_out needs hi-lo elements")
+    if nnz_out.numel() < 2 or val_cat.numel() != idx_cat.numel():
+        raise ValueError("nnz_out needs two elements; idx_cat and val_cat the same length")
+    _check("okt_sparse_reduce_segments", load_library().okt_sparse_reduce_segments(
+        _ptr(idx_cat, _u32(torch), "idx_cat"), _ptr(val_cat, torch.float32, "val_cat"),
+        _ptr(seg_begin, _u64(torch), "seg_begin"), _ptr(seg_end, _u64(torch), "seg_end"),
+        int(P), int(lo), int(hi),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
+        _ptr(nnz_out, _u64(torch), "nnz_out"),
+        _ptr(dense_out, torch.float32, "dense_out", allow_none=True),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(stream)))

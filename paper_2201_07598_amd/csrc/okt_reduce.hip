@@ -58,7 +58,8 @@ __device__ __forceinline__ RegionView region_view(const uint32_t* lo_hi, uint32_
 // table[region][t][p] = number of entries of contribution p with index below
 // lo + t * slots (clipped to hi), for t = 0 .. ntiles.
 __global__ __launch_bounds__(256) void reduce_slices_kernel(
-    const uint32_t* __restrict__ idx_cat, const uint64_t* __restrict__ chunk_off,
+    const uint32_t* __restrict__ idx_cat, const uint64_t* __restrict__ seg_begin,
+    const uint64_t* __restrict__ seg_end, uint32_t seg_stride,
     const uint32_t* __restrict__ lo_hi, uint32_t lo0, uint32_t hi0, uint32_t P,
     uint32_t max_width, uint32_t slots, char* ws, uint32_t ws_region_bytes,
     uint32_t table_offset) {
@@ -71,7 +72,8 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < table_offset / 8;
          i += gridDim.x * blockDim.x)
         scan_state[i] = 0;
-    const uint64_t* off = chunk_off + (size_t)region * (P + 1);
+    const uint64_t* begin = seg_begin + (size_t)region * seg_stride;
+    const uint64_t* end = seg_end + (size_t)region * seg_stride;
     const uint64_t cells = (uint64_t)(r.ntiles + 1) * P;
     for (uint64_t c = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; c < cells;
          c += (uint64_t)gridDim.x * blockDim.x) {
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(
         const uint32_t p = (uint32_t)(c / (r.ntiles + 1)), t = (uint32_t)(c % (r.ntiles + 1));
         uint64_t bound = (uint64_t)r.lo + (uint64_t)t * slots;
         if (bound > r.hi) bound = r.hi;
-        const uint64_t cb = off[p], ce = off[p + 1];
+        const uint64_t cb = begin[p], ce = end[p] > cb ? end[p] : cb;
         table[(size_t)t * P + p] = (uint32_t)(lower_bound_idx(idx_cat, cb, ce, (uint32_t)bound) - cb);
     }
 }
@@ -118,10 +120,12 @@ __device__ __forceinline__ uint32_t bitmap_prefix(const uint32_t* s_bits, uint16
 }
 
 // grid = (tiles of the widest region, B).  Region j: chunk offsets at
-// chunk_off + j*(P+1); bounds from lo_hi[2j..] if lo_hi != NULL else (lo0, hi0).
+// seg_begin / seg_end + j * seg_stride; bounds from lo_hi[2j..] if lo_hi != NULL else
+// (lo0, hi0).
 __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     const uint32_t* __restrict__ idx_cat, const float* __restrict__ val_cat,
-    const uint64_t* __restrict__ chunk_off, const uint32_t* __restrict__ lo_hi, uint32_t lo0,
+    const uint64_t* __restrict__ seg_begin, uint32_t seg_stride,
+    const uint32_t* __restrict__ lo_hi, uint32_t lo0,
     uint32_t hi0, uint32_t P, uint32_t max_width, uint32_t slots, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     float* __restrict__ dense_out, char* ws, uint32_t ws_region_bytes, uint32_t table_offset) {
@@ -165,7 +169,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     const uint32_t a = r.lo + tile * slots;                       // first index of the tile
     const uint32_t tslots = (r.hi - a) < slots ? (r.hi - a) : slots;
     const uint32_t words = (tslots + 31) / 32;
-    const uint64_t* off = chunk_off + (size_t)region * (P + 1);
+    const uint64_t* off = seg_begin + (size_t)region * seg_stride;
     const uint32_t* row0 = table + (size_t)tile * P;              // slice starts
     const uint32_t* row1 = row0 + P;                              // slice ends
     idx_out += (size_t)region * capacity;
@@ -341,15 +345,17 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
 }
 
 static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
-                         const uint64_t* d_chunk_off, const uint32_t* d_lo_hi, uint32_t lo,
+                         const uint64_t* d_seg_begin, const uint64_t* d_seg_end,
+                         uint32_t seg_stride, const uint32_t* d_lo_hi, uint32_t lo,
                          uint32_t hi, uint32_t B, uint32_t P, uint32_t max_width,
                          uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
                          uint64_t* d_nnz_out, float* d_dense, void* d_ws, size_t ws_bytes,
                          hipStream_t s) {
-    if (!d_idx_cat || !d_val_cat || !d_chunk_off || !d_nnz_out) return OKT_ERR_INVALID_ARG;
+    if (!d_idx_cat || !d_val_cat || !d_seg_begin || !d_seg_end || !d_nnz_out)
+        return OKT_ERR_INVALID_ARG;
     if (P == 0 || P > 65535 || B == 0 || B > 65535) return OKT_ERR_INVALID_ARG;
     if (capacity > 0 && (!d_idx_out || !d_val_out)) return OKT_ERR_INVALID_ARG;
-    if (!aligned(d_idx_cat, 4) || !aligned(d_val_cat, 4) || !aligned(d_chunk_off, 8) ||
+    if (!aligned(d_idx_cat, 4) || !aligned(d_val_cat, 4) || !aligned(d_seg_begin, 8) || !aligned(d_seg_end, 8) ||
         !aligned(d_nnz_out, 8) || !aligned(d_idx_out, 4) || !aligned(d_val_out, 4) ||
         !aligned(d_dense, 4) || !aligned(d_lo_hi, 4))
         return OKT_ERR_INVALID_ARG;
@@ -365,10 +371,12 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
     uint64_t sblocks = (cells + 255) / 256;
     if (sblocks > 4096) sblocks = 4096;
     hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)sblocks, B), dim3(256), 0, s,
-                       d_idx_cat, d_chunk_off, d_lo_hi, lo, hi, P, max_width, slots, (char*)d_ws,
+                       d_idx_cat, d_seg_begin, d_seg_end, seg_stride, d_lo_hi, lo, hi, P, max_width,
+                       slots, (char*)d_ws,
                        (uint32_t)region_bytes, table_offset);
     hipLaunchKernelGGL(reduce_tile_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,
-                       d_idx_cat, d_val_cat, d_chunk_off, d_lo_hi, lo, hi, P, max_width, slots,
+                       d_idx_cat, d_val_cat, d_seg_begin, seg_stride, d_lo_hi, lo, hi, P, max_width,
+                       slots,
                        d_idx_out, d_val_out, capacity, d_nnz_out, d_dense, (char*)d_ws,
                        (uint32_t)region_bytes, table_offset);
     return launch_status();
@@ -382,7 +390,10 @@ extern "C" int okt_sparse_reduce(const uint32_t* d_idx_cat, const float* d_val_c
                                  uint64_t* d_nnz_out, float* d_dense_out_or_null, void* d_ws,
                                  size_t ws_bytes, void* stream) {
     if (lo > hi) return OKT_ERR_INVALID_ARG;
-    return okt::reduce_launch(d_idx_cat, d_val_cat, d_chunk_off, nullptr, lo, hi, 1, P, hi - lo,
+    if (!d_chunk_off) return OKT_ERR_INVALID_ARG;
+    // contribution p = [off[p], off[p+1]): the same vector is the begins and, one on, the ends
+    return okt::reduce_launch(d_idx_cat, d_val_cat, d_chunk_off, d_chunk_off + 1, P + 1, nullptr,
+                              lo, hi, 1, P, hi - lo,
                               d_idx_out, d_val_out, capacity, d_nnz_out, d_dense_out_or_null,
                               d_ws, ws_bytes, (hipStream_t)stream);
 }
@@ -393,8 +404,21 @@ extern "C" int okt_sparse_reduce_batch(const uint32_t* d_idx_cat, const float* d
                                        uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
                                        uint64_t* d_nnz_out, float* d_dense_out_or_null,
                                        void* d_ws, size_t ws_bytes, void* stream) {
-    if (!d_lo_hi) return OKT_ERR_INVALID_ARG;
-    return okt::reduce_launch(d_idx_cat, d_val_cat, d_chunk_off, d_lo_hi, 0, 0, B, P, max_width,
+    if (!d_lo_hi || !d_chunk_off) return OKT_ERR_INVALID_ARG;
+    return okt::reduce_launch(d_idx_cat, d_val_cat, d_chunk_off, d_chunk_off + 1, P + 1, d_lo_hi,
+                              0, 0, B, P, max_width,
                               d_idx_out, d_val_out, capacity, d_nnz_out, d_dense_out_or_null,
                               d_ws, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int okt_sparse_reduce_segments(const uint32_t* d_idx_cat, const float* d_val_cat,
+                                          const uint64_t* d_seg_begin, const uint64_t* d_seg_end,
+                                          uint32_t P, uint32_t lo, uint32_t hi,
+                                          uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                                          uint64_t* d_nnz_out, float* d_dense_out_or_null,
+                                          void* d_ws, size_t ws_bytes, void* stream) {
+    if (lo > hi) return OKT_ERR_INVALID_ARG;
+    return okt::reduce_launch(d_idx_cat, d_val_cat, d_seg_begin, d_seg_end, P, nullptr, lo, hi, 1, P,
+                              hi - lo, d_idx_out, d_val_out, capacity, d_nnz_out,
+                              d_dense_out_or_null, d_ws, ws_bytes, (hipStream_t)stream);
 }

@@ -82,5 +82,8 @@ def test_argument_errors_are_found_on_the_host():
     assert lib.okt_threshold_select_copy(fake, 1 << 20, fake, fake, fake, 4, fake, fake, 8, null) == WORKSPACE
     assert lib.okt_index_intersect_zero(null, 100, fake, fake, 10, fake, fake, 10, null, fake, fake, 1 << 20, null) == INVALID
     assert lib.okt_index_intersect_zero(fake, 100, fake, fake, 1 << 20, fake, fake, 10, null, fake, fake, 8, null) == WORKSPACE
+    assert lib.okt_sparse_reduce_segments(fake, fake, fake, null, 4, 0, 10, fake, fake, 4, fake, null, fake, 1 << 20, null) == INVALID
+    assert lib.okt_sparse_reduce_segments(fake, fake, fake, fake, 4, 20, 10, fake, fake, 4, fake, null, fake, 1 << 20, null) == INVALID
+    assert lib.okt_sparse_reduce_segments(fake, fake, fake, fake, 4, 0, 1 << 20, fake, fake, 4, fake, null, fake, 64, null) == WORKSPACE
     with pytest.raises(TypeError):
         okt.okt_residual_accumulate(None, None, 1.0)

@@ -437,6 +437,92 @@ def test_reduce_paper_shaped_regions():
     check_reduce(cat_i, lap(600, cat_i.size), off, int(cat_i[5]), int(cat_i[5]) + 1)
 
 
+def test_reduce_segments_in_any_order():
+    rng = np.random.default_rng(31)
+    n, m = 50_000, 900
+    parts = [np.sort(rng.choice(n, m - 100 * p, replace=False)).astype(np.uint32) for p in range(5)]
+    vals = [lap(40 + p, parts[p].size) for p in range(5)]
+    # the buffer holds the contributions out of order, with gaps, and one slice
+    # whose end lies below its begin (empty)
+    order, gap = [3, 0, 4, 1, 2], 37
+    begin, end = [0] * 6, [0] * 6
+    buf_i, buf_v, at = [], [], 11
+    buf_i.append(np.full(at, 0xFFFFFFFF, np.uint32)); buf_v.append(np.full(at, 9e9, np.float32))
+    for p in order:
+        begin[p], end[p] = at, at + parts[p].size
+        buf_i += [parts[p], np.full(gap, 0xFFFFFFFF, np.uint32)]
+        buf_v += [vals[p], np.full(gap, 9e9, np.float32)]
+        at += parts[p].size + gap
+    begin[5], end[5] = 500, 400
+    cat_i, cat_v = np.concatenate(buf_i), np.concatenate(buf_v)
+    ref = orc.sparse_reduce(np.concatenate(parts), np.concatenate(vals),
+                            np.concatenate([[0], np.cumsum([q.size for q in parts])]).astype(np.uint64),
+                            1000, 45_001)
+    U = ref["idx"].size
+    out_i = torch.full((U + 5,), -1, dtype=torch.int32, device=DEV)
+    out_v = torch.zeros(U + 5, dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    ws = workspace(okt.okt_workspace_bytes(44_001, 6))
+    okt.okt_sparse_reduce_segments(to_dev(cat_i), to_dev(cat_v), to_dev(np.array(begin, np.uint64)),
+                                   to_dev(np.array(end, np.uint64)), 6, 1000, 45_001, out_i, out_v,
+                                   nnz, ws)
+    c = u64(nnz)
+    assert int(c[0]) == int(c[1]) == U
+    assert np.array_equal(u32(out_i[:U]), ref["idx"])
+    err = np.abs(out_v[:U].cpu().numpy().astype(np.float64) - ref["val"])
+    assert np.all(err <= reduce_tolerance(ref))
+
+
+@pytest.mark.parametrize("exact", [True, False])
+def test_reduce_in_buckets_with_carried_partial(exact):
+    """Three buckets of four contributions; the partial result is the last slice of
+    the next call and is never copied: two buffers in turn, the count written
+    straight into the end word of that slice."""
+    rng = np.random.default_rng(32)
+    lo, hi, m, per, nb = 5000, 205_000, 3000, 4, 3
+    cap = per * nb * m
+    buckets = []
+    for b in range(nb):
+        parts = [np.sort(rng.choice(hi - lo, m, replace=False)).astype(np.uint32) + np.uint32(lo)
+                 for _ in range(per)]
+        if exact:
+            vals = [(rng.integers(-2048, 2049, m) / 128.0).astype(np.float32) for _ in range(per)]
+        else:
+            vals = [lap(900 + 10 * b + p, m) for p in range(per)]
+        buckets.append((np.concatenate(parts), np.concatenate(vals), np.arange(per + 1, dtype=np.uint64) * m))
+    ref = orc.sparse_reduce_bucketed(buckets, lo, hi)
+
+    size = cap + per * m
+    buf_i = [torch.zeros(size, dtype=torch.int32, device=DEV) for _ in range(2)]
+    buf_v = [torch.zeros(size, dtype=torch.float32, device=DEV) for _ in range(2)]
+    begin = to_dev(np.array([cap + p * m for p in range(per)] + [0], dtype=np.uint64))
+    ends = [to_dev(np.array([cap + (p + 1) * m for p in range(per)] + [0, 0], dtype=np.uint64))
+            for _ in range(2)]                       # [.., end of the carried slice, spare word]
+    ws = workspace(okt.okt_workspace_bytes(hi - lo, per + 1))
+    for b, (ci, cv, _) in enumerate(buckets):
+        src, dst = b % 2, (b + 1) % 2
+        buf_i[src][cap:] = to_dev(ci)                # "received" behind the carried partial
+        buf_v[src][cap:] = to_dev(cv)
+        okt.okt_sparse_reduce_segments(buf_i[src], buf_v[src], begin, ends[src], per + 1, lo, hi,
+                                       buf_i[dst][:cap], buf_v[dst][:cap], ends[dst][per:per + 2], ws)
+    torch.cuda.synchronize()
+    final = nb % 2
+    counts = u64(ends[final][per:per + 2])
+    U = ref["idx"].size
+    assert int(counts[0]) == int(counts[1]) == U
+    assert np.array_equal(u32(buf_i[final][:U]), ref["idx"])
+    got = buf_v[final][:U].cpu().numpy()
+    if exact:
+        assert bits_equal(got, ref["val"])
+    else:
+        # every call is within the stated tolerance of its own exact sums; over the
+        # chain the bound is taken against the sum of all magnitudes, once per bucket
+        one = orc.sparse_reduce(np.concatenate([b[0] for b in buckets]), np.concatenate([b[1] for b in buckets]),
+                                np.arange(per * nb + 1, dtype=np.uint64) * m, lo, hi)
+        err = np.abs(got.astype(np.float64) - ref["val"].astype(np.float64))
+        assert np.all(err <= nb * 1e-6 * one["abs_sum"])
+
+
 def test_reduce_disjoint_contributions_fill_in():
     # non-overlapping indexes: the union is the sum of the sizes and every value
     # is a bit copy (the fill-in arithmetic of the paper's Introduction)

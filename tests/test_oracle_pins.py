@@ -493,3 +493,31 @@ def test_what_leaves_the_residuals_is_what_is_applied():
                 assert bits(eps[i]) == bits(acc[i])
     assert left == u
     assert kept_back > 0
+
+
+def test_bucketed_reduce_equals_one_shot_when_sums_are_exact():
+    # dyadic values: every partial sum is exact in fp32, so rounding between the
+    # buckets changes nothing and the bucketed reduction must equal the one-shot
+    # reduction bit for bit; the index set is the same for any values
+    rng = np.random.default_rng(81)
+    n, P, m = 5000, 12, 400
+    parts = [np.sort(rng.choice(n, m, replace=False)).astype(np.uint32) for _ in range(P)]
+    dy = [(rng.integers(-4096, 4097, m) / 256.0).astype(np.float32) for _ in range(P)]
+    fl = [rand_f32(rng, m) for _ in range(P)]
+    off = np.arange(P + 1, dtype=np.uint64) * m
+    for vals, exact in ((dy, True), (fl, False)):
+        one = orc.sparse_reduce(np.concatenate(parts), np.concatenate(vals), off, 100, 4000)
+        buckets = []
+        for b in range(0, P, 4):
+            buckets.append((np.concatenate(parts[b:b + 4]), np.concatenate(vals[b:b + 4]),
+                            np.arange(5, dtype=np.uint64) * m))
+        got = orc.sparse_reduce_bucketed(buckets, 100, 4000)
+        assert np.array_equal(got["idx"], one["idx"])
+        if exact:
+            assert np.array_equal(got["val"].view(np.uint32), one["val"].view(np.uint32))
+        else:
+            # three roundings instead of one: within 3 ulp-sized steps of sum|v|
+            assert np.all(np.abs(got["val"].astype(np.float64) - one["val"]) <= 3 * 2.0 ** -24 * one["abs_sum"])
+    # one bucket is the plain reduction
+    single = orc.sparse_reduce_bucketed([(np.concatenate(parts), np.concatenate(fl), off)], 100, 4000)
+    assert np.array_equal(single["val"].view(np.uint32), one["val"].view(np.uint32))
