@@ -306,6 +306,37 @@ int okt_index_intersect_zero(float* d_acc_inout, uint64_t n, const uint32_t* d_l
                              uint64_t max_global, uint32_t* d_indexes_out_or_null,
                              uint64_t* d_count_out, void* d_ws, size_t ws_bytes, void* stream);
 
+/*
+ * The communication scheme of the data-balancing step before the allgatherv of
+ * the global top-k values (Sec. 3.1.2, "balance and allgatherv": each worker uses
+ * the gathered buffer sizes to generate which chunk is sent to which worker), and
+ * the rule for taking the step at all (Sec. 5.3: when the largest buffer is more
+ * than four times the average).  HOST pointers; pure host arithmetic, no GPU.
+ *   h_sizes          in   uint64[P]  entries in each worker's packed buffer (< 2^32)
+ *   h_triggered_out  out  1 if max(sizes) * P > 4 * sum(sizes), else 0
+ *   h_plan_out       out  the chunks, in list order, if triggered (else none):
+ *                         the P buffers in worker order are one list of T entries,
+ *                         which is re-cut into consecutive pieces of floor or ceil
+ *                         T / P entries, worker j getting list positions
+ *                         [floor(j T / P), floor((j+1) T / P)).  A chunk says that
+ *                         `count` entries from position src_offset of worker src's
+ *                         old buffer become the entries from position dst_offset of
+ *                         worker dst's new buffer; src == dst is the part a worker
+ *                         keeps (possibly shifted).  The order of the list, hence
+ *                         of the indexes, is kept.
+ *   plan_capacity    chunks h_plan_out can hold; 2 P - 1 always suffice, fewer is
+ *                    OKT_ERR_INVALID_ARG if the plan does not fit
+ *   h_plan_len_out   out  number of chunks written
+ * Moving the chunks is communication and not part of this library.
+ */
+typedef struct okt_chunk {
+    uint32_t src, dst;
+    uint64_t src_offset, dst_offset, count;
+} okt_chunk;
+
+int okt_balance_plan(const uint64_t* h_sizes, uint32_t P, okt_chunk* h_plan_out,
+                     uint32_t plan_capacity, uint32_t* h_plan_len_out, int* h_triggered_out);
+
 #ifdef __cplusplus
 }
 #endif

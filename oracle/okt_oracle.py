@@ -200,6 +200,32 @@ def sparse_reduce_bucketed(buckets, lo: int, hi: int):
     return partial
 
 
+def balance_plan(sizes):
+    """Data balancing before the allgatherv of the global top-k values
+    (Sec. 3.1.2), taken when the largest buffer is more than four times the
+    average (Sec. 5.3).  The P buffers in worker order are one list of T entries;
+    balanced, worker j holds list positions [floor(j T / P), floor((j+1) T / P)).
+    Every pair (old buffer i, new buffer j) whose ranges of list positions overlap
+    gives one chunk (src, dst, src_offset, dst_offset, count).
+    Returns (triggered, chunks in list order); no chunks when not triggered."""
+    sizes = [int(x) for x in sizes]
+    P, T = len(sizes), sum(sizes)
+    triggered = max(sizes) * P > 4 * T
+    if not triggered:
+        return False, []
+    old_first = [sum(sizes[:i]) for i in range(P)]
+    new_first = [(j * T) // P for j in range(P + 1)]
+    chunks = []
+    for i in range(P):
+        for j in range(P):
+            a = max(old_first[i], new_first[j])
+            b = min(old_first[i] + sizes[i], new_first[j + 1])
+            if b > a:
+                chunks.append((i, j, a - old_first[i], a - new_first[j], b - a))
+    chunks.sort(key=lambda c: old_first[c[0]] + c[2])
+    return True, chunks
+
+
 def coo_threshold_select(idx: np.ndarray, val: np.ndarray, th, capacity: int | None = None):
     """Global top-k selection on a reduced sparse region (Sec. 3.1.2: each
     worker selects the global top-k values from the reduced top-k values of its

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     okt_accumulate_select,
+    okt_balance_plan,
     okt_coo_threshold_select,
     okt_index_intersect_restore,
     okt_index_intersect_zero,

@@ -40,9 +40,15 @@ SIGNATURES = {
                                   c_vp, c_vp, c_sz, c_vp]),
     "okt_sparse_reduce_segments": (c_int, [c_vp, c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp, c_u64,
                                            c_vp, c_vp, c_vp, c_sz, c_vp]),
+    "okt_balance_plan": (c_int, [c_vp, c_u32, c_vp, c_u32, c_vp, c_vp]),
     "okt_sparse_reduce_batch": (c_int, [c_vp, c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp,
                                         c_u64, c_vp, c_vp, c_vp, c_sz, c_vp]),
 }
+
+
+class OktChunk(ctypes.Structure):
+    _fields_ = [("src", c_u32), ("dst", c_u32), ("src_offset", c_u64), ("dst_offset", c_u64),
+                ("count", c_u64)]
 
 
 class OktError(RuntimeError):
@@ -336,3 +342,17 @@ def okt_sparse_reduce_segments(idx_cat, val_cat, seg_begin, seg_end, P: int, lo:
         _ptr(nnz_out, _u64(torch), "nnz_out"),
         _ptr(dense_out, torch.float32, "dense_out", allow_none=True),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(stream)))
+
+
+def okt_balance_plan(sizes):
+    """Host-side: returns (triggered, [(src, dst, src_offset, dst_offset, count), ...])."""
+    P = len(sizes)
+    h_sizes = (c_u64 * max(P, 1))(*[int(x) for x in sizes])
+    plan = (OktChunk * max(2 * P, 1))()
+    n = c_u32(0)
+    triggered = c_int(0)
+    _check("okt_balance_plan", load_library().okt_balance_plan(
+        ctypes.cast(h_sizes, c_vp), P, ctypes.cast(plan, c_vp), 2 * P, ctypes.cast(ctypes.pointer(n), c_vp),
+        ctypes.cast(ctypes.pointer(triggered), c_vp)))
+    return bool(triggered.value), [(c.src, c.dst, c.src_offset, c.dst_offset, c.count)
+                                   for c in plan[:n.value]]

@@ -5,7 +5,10 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
+
+from oracle import okt_oracle as orc
 
 import paper_2201_07598_amd as okt
 from paper_2201_07598_amd import binding
@@ -87,3 +90,20 @@ def test_argument_errors_are_found_on_the_host():
     assert lib.okt_sparse_reduce_segments(fake, fake, fake, fake, 4, 0, 1 << 20, fake, fake, 4, fake, null, fake, 64, null) == WORKSPACE
     with pytest.raises(TypeError):
         okt.okt_residual_accumulate(None, None, 1.0)
+
+
+def test_balance_plan_library_matches_the_oracle():
+    # host logic of the library (no GPU involved) against the oracle
+    rng = np.random.default_rng(92)
+    cases = [[10_000] + [0] * 7, [0] * 7 + [10_000], [3, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1],
+             [5, 5, 5, 5, 5], [0] * 6, [2 ** 32 - 1] + [1] * 9]
+    for P in (5, 9, 16, 64, 200):
+        for _ in range(20):
+            s = rng.integers(0, 30, P)
+            s[rng.integers(0, P)] = rng.integers(100, 5000)
+            cases.append([int(x) for x in s])
+    for sizes in cases:
+        want = orc.balance_plan(sizes)
+        got = okt.okt_balance_plan(sizes)
+        assert got[0] == want[0], sizes
+        assert [tuple(int(x) for x in c) for c in got[1]] == [tuple(c) for c in want[1]], sizes

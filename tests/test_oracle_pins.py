@@ -521,3 +521,62 @@ def test_bucketed_reduce_equals_one_shot_when_sums_are_exact():
     # one bucket is the plain reduction
     single = orc.sparse_reduce_bucketed([(np.concatenate(parts), np.concatenate(fl), off)], 100, 4000)
     assert np.array_equal(single["val"].view(np.uint32), one["val"].view(np.uint32))
+
+
+# --------------------------------------------------------------- data balancing
+def apply_plan(buffers, chunks):
+    """Move labelled entries as the plan says; returns the new buffers."""
+    P = len(buffers)
+    new = [dict() for _ in range(P)]
+    for src, dst, so, do, count in chunks:
+        for t in range(count):
+            assert do + t not in new[dst]
+            new[dst][do + t] = buffers[src][so + t]
+    return [[b[t] for t in range(len(b))] for b in new]
+
+
+def test_balance_plan_moves_every_entry_once_and_keeps_the_order():
+    rng = np.random.default_rng(91)
+    for P in (5, 8, 16, 33):
+        for trial in range(6):
+            sizes = [0] * P
+            heavy = rng.choice(P, 1 + trial % 2, replace=False)
+            for h in heavy:
+                sizes[h] = int(rng.integers(200, 900))
+            for i in range(P):
+                if i not in heavy:
+                    sizes[i] = int(rng.integers(0, 12))
+            triggered, chunks = orc.balance_plan(sizes)
+            T = sum(sizes)
+            assert triggered == (max(sizes) * P > 4 * T)
+            if not triggered:
+                assert chunks == []
+                continue
+            buffers = [[(i, t) for t in range(sizes[i])] for i in range(P)]
+            new = apply_plan(buffers, chunks)
+            # nothing lost, nothing doubled, list order kept
+            assert [e for b in new for e in b] == [e for b in buffers for e in b]
+            # balanced: floor or ceil of T / P each
+            assert all(len(b) in (T // P, -(-T // P)) for b in new)
+            assert len(chunks) <= 2 * P - 1
+
+
+def test_balance_plan_extreme_case_and_trigger_rule():
+    # Sec. 3.1.2: all global top-k values on one worker; balancing then moves
+    # k (P-1)/P entries = 2k (P-1)/P words, one chunk to every other worker
+    k, P = 10_000, 8
+    for owner in (0, 3, P - 1):
+        sizes = [0] * P
+        sizes[owner] = k
+        triggered, chunks = orc.balance_plan(sizes)
+        assert triggered
+        moved = [c for c in chunks if c[0] != c[1]]
+        assert len(moved) == P - 1 and {c[1] for c in moved} == set(range(P)) - {owner}
+        assert sum(c[4] for c in moved) == k * (P - 1) // P
+        assert 2 * sum(c[4] for c in moved) == 2 * k * (P - 1) // P
+    # "more than four times the average": exactly four times does not trigger
+    assert orc.balance_plan([40, 10, 10, 10, 10, 10, 10, 10, 10, 10, 10, 10, 10])[0] is False   # avg 12.3, 4x = 49.2
+    assert orc.balance_plan([16, 0, 0, 0])[0] is False            # P = 4: the max is at most 4 x avg
+    assert orc.balance_plan([32, 8, 8, 8, 8, 0, 0, 0])[0] is False   # avg 8, max = 4 x avg
+    assert orc.balance_plan([33, 8, 8, 8, 7, 0, 0, 0])[0] is True
+    assert orc.balance_plan([0, 0, 0, 0, 0, 0])[0] is False
