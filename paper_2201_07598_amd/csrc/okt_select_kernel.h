@@ -95,7 +95,11 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
             count = select_round((uint32_t)r + 256u * u, w[u], test(w[u].x), test(w[u].y),
                                  test(w[u].z), test(w[u].w), count, sink);
     }
-    for (; r < end; r += 256) {                           // ragged rounds of the last piece
+    for (; r + 256 <= end; r += 256) {                    // whole rounds short of a batch
+        const float4 x = reinterpret_cast<const float4*>(acc + r)[lane];
+        count = select_round((uint32_t)r, x, test(x.x), test(x.y), test(x.z), test(x.w), count, sink);
+    }
+    for (; r < end; r += 256) {                           // the ragged end of the vector
         const uint64_t i = r + 4u * (uint32_t)lane;
         float e[4];
         bool s[4];
@@ -307,7 +311,15 @@ __device__ __forceinline__ void accumulate_select_body(
             edst[u * WAVE] = round((uint32_t)r + 256u * u, a[u], test(a[u].x), test(a[u].y),
                                    test(a[u].z), test(a[u].w));
     }
-    for (; r < end; r += 256) {                      // ragged rounds of the last piece
+    for (; r + 256 <= end; r += 256) {               // whole rounds short of a batch
+        const float4 gq = reinterpret_cast<const float4*>(grad + r)[lane];
+        const float4 eq = reinterpret_cast<const float4*>(res + r)[lane];
+        const float4 a = make_float4(fma2(eq.x, gq.x), fma2(eq.y, gq.y), fma2(eq.z, gq.z),
+                                     fma2(eq.w, gq.w));
+        reinterpret_cast<float4*>(res + r)[lane] =
+            round((uint32_t)r, a, test(a.x), test(a.y), test(a.z), test(a.w));
+    }
+    for (; r < end; r += 256) {                      // the ragged end of the vector
         const uint64_t i = r + 4u * (uint32_t)lane;
         float a[4];
         bool s[4], inside[4];
@@ -329,8 +341,13 @@ __device__ __forceinline__ void accumulate_select_body(
                                    s_count, s_before);
 }
 
+#ifndef OKT_SEL_WAVES_PER_EU
+#define OKT_SEL_ATTR
+#else
+#define OKT_SEL_ATTR __attribute__((amdgpu_waves_per_eu(OKT_SEL_WAVES_PER_EU, OKT_SEL_WAVES_PER_EU)))
+#endif
 template <int BLOCK, int U, int STASH, bool TICKET, typename Source = DenseSource>
-__global__ __launch_bounds__(BLOCK) void select_kernel(
+__global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void select_kernel(
     float* __restrict__ acc, uint32_t n, const float* __restrict__ d_threshold,
     uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
     uint64_t* __restrict__ nnz_out, ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc,
@@ -398,7 +415,7 @@ __global__ __launch_bounds__(BLOCK) void coo_select_kernel(
 }
 
 template <int BLOCK, int U, int STASH, bool TICKET>
-__global__ __launch_bounds__(BLOCK) void accumulate_select_kernel(
+__global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void accumulate_select_kernel(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n,
     const float* __restrict__ d_threshold, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,

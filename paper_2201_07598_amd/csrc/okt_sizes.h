@@ -10,18 +10,14 @@ namespace okt {
 // ---- threshold select + compaction ----
 // A workgroup of SEL_BLOCK threads owns SEL_WAVES consecutive pieces of the
 // vector, one per wave; a wave streams its piece in rounds of 256 elements,
-// SEL_U rounds in flight.  The piece length is chosen so that about
-// SEL_TARGET_WGS workgroups (32 waves per CU on 256 CUs) cover the vector, but never
-// above SEL_PIECE_MAX, which keeps the selected entries of a piece inside the
-// wave's LDS stash up to a density of SEL_STASH / SEL_PIECE_MAX = 3.7 %.
+// SEL_U rounds in flight.  The piece length (select_shape below) is never above
+// SEL_PIECE_MAX, which keeps the selected entries of a piece inside the wave's
+// LDS stash up to a density of SEL_STASH / SEL_PIECE_MAX = 3.7 %.
 #ifndef OKT_SEL_U
 #define OKT_SEL_U 4
 #endif
 #ifndef OKT_SEL_TICKET
 #define OKT_SEL_TICKET true
-#endif
-#ifndef OKT_SEL_TARGET_WGS
-#define OKT_SEL_TARGET_WGS 512
 #endif
 #ifndef OKT_SEL_BLOCK
 #define OKT_SEL_BLOCK 1024
@@ -33,7 +29,6 @@ constexpr int SEL_STASH = 608;                 // entries per wave: 32 waves fit
 constexpr bool SEL_TICKET = OKT_SEL_TICKET;    // false: measurement builds only
 constexpr uint32_t SEL_ROUND = 256u * SEL_U;
 constexpr uint32_t SEL_PIECE_MAX = 16384;
-constexpr uint32_t SEL_TARGET_WGS = OKT_SEL_TARGET_WGS;
 
 struct SelectShape { uint32_t nseg, piece; };
 // Pieces of a multiple of `round` elements, one per wave, `waves` per workgroup,
@@ -47,11 +42,30 @@ inline SelectShape select_shape_for(uint64_t n, int waves, uint32_t round,
     const uint64_t per_wg = piece * waves;
     return SelectShape{(uint32_t)((n + per_wg - 1) / per_wg), (uint32_t)piece};
 }
+// The select kernels run one 1024-thread workgroup per CU at a time, and a
+// workgroup streams for tens of microseconds, so a last round of workgroups that
+// fills only part of the chip costs as much as a full one.  The vector is
+// therefore cut for whole rounds: `rounds` x SEL_CUS workgroups of equal pieces
+// (a multiple of 256 elements, at most SEL_PIECE_MAX).
+#ifndef OKT_SEL_CUS
+#define OKT_SEL_CUS 256
+#endif
+constexpr uint32_t SEL_CUS = OKT_SEL_CUS;
+inline uint64_t select_rounds(uint64_t n) {
+    const uint64_t per_round = (uint64_t)SEL_CUS * SEL_WAVES * SEL_PIECE_MAX;
+    const uint64_t rounds = (n + per_round - 1) / per_round;
+    return rounds ? rounds : 1;
+}
 inline SelectShape select_shape(uint64_t n) {
-    return select_shape_for(n, SEL_WAVES, SEL_ROUND, SEL_TARGET_WGS, SEL_PIECE_MAX);
+    const uint64_t waves = (uint64_t)SEL_CUS * SEL_WAVES * select_rounds(n);
+    uint64_t piece = ((n + waves - 1) / waves + 255) / 256 * 256;
+    if (piece < SEL_ROUND) piece = SEL_ROUND;
+    const uint64_t per_wg = piece * SEL_WAVES;
+    return SelectShape{(uint32_t)((n + per_wg - 1) / per_wg), (uint32_t)piece};
 }
 inline size_t select_ws_bytes(uint64_t n) {       // header, segment and group descriptors
-    const uint64_t t = select_shape(n).nseg;
+    // never more workgroups than whole rounds: a bound that grows with n
+    const uint64_t t = (uint64_t)SEL_CUS * select_rounds(n);
     return 64 + 8 * (size_t)(t + (t + 63) / 64);
 }
 
