@@ -31,17 +31,6 @@ constexpr uint32_t SEL_ROUND = 256u * SEL_U;
 constexpr uint32_t SEL_PIECE_MAX = 16384;
 
 struct SelectShape { uint32_t nseg, piece; };
-// Pieces of a multiple of `round` elements, one per wave, `waves` per workgroup,
-// about `target_wgs` workgroups, no piece above `piece_max`.
-inline SelectShape select_shape_for(uint64_t n, int waves, uint32_t round,
-                                    uint32_t target_wgs = 512, uint32_t piece_max = 1u << 20) {
-    uint64_t per_wave = (n + (uint64_t)target_wgs * waves - 1) / ((uint64_t)target_wgs * waves);
-    uint64_t piece = (per_wave + round - 1) / round * round;
-    if (piece < round) piece = round;
-    if (piece > piece_max) piece = piece_max;
-    const uint64_t per_wg = piece * waves;
-    return SelectShape{(uint32_t)((n + per_wg - 1) / per_wg), (uint32_t)piece};
-}
 // The select kernels run one 1024-thread workgroup per CU at a time, and a
 // workgroup streams for tens of microseconds, so a last round of workgroups that
 // fills only part of the chip costs as much as a full one.  The vector is

@@ -213,13 +213,15 @@ constexpr int CNT_U = 4;
 
 // The counting pass: one contiguous piece per wave, as in the select kernel,
 // with the same one-compare-per-element test.  Every key at or above cand_lo is
-// a candidate and is copied to `cand`, in any order (per-wave LDS stash, one
-// global atomic per flush).
+// a candidate and is copied to `cand`, in any order (per-wave LDS stash; a stash
+// that fills up is flushed with an atomic of its own, the rest of a workgroup
+// with one atomic at the end).
 template <typename Test>
 __device__ __forceinline__ void collect_body(const float* __restrict__ acc, uint32_t n,
                                              uint32_t piece, RadixState* state,
                                              uint32_t* __restrict__ cand, uint64_t cand_cap,
-                                             Test test, uint32_t (*s_stash)[CNT_STASH]) {
+                                             Test test, uint32_t (*s_stash)[CNT_STASH],
+                                             uint32_t* s_left, unsigned long long* s_base) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
     const uint64_t start = ((uint64_t)blockIdx.x * CNT_WAVES + wave) * piece;
@@ -252,7 +254,11 @@ __device__ __forceinline__ void collect_body(const float* __restrict__ acc, uint
         for (int u = 0; u < CNT_U; ++u)
             round(v[u], test(v[u].x), test(v[u].y), test(v[u].z), test(v[u].w));
     }
-    for (; r < end; r += 256) {
+    for (; r + 256 <= end; r += 256) {                    // whole rounds short of a batch
+        const float4 v = reinterpret_cast<const float4*>(acc + r)[lane];
+        round(v, test(v.x), test(v.y), test(v.z), test(v.w));
+    }
+    for (; r < end; r += 256) {                           // the ragged end of the vector
         const uint64_t i = r + 4u * (uint32_t)lane;
         float e[4];
         bool c[4];
@@ -264,18 +270,36 @@ __device__ __forceinline__ void collect_body(const float* __restrict__ acc, uint
         }
         round(make_float4(e[0], e[1], e[2], e[3]), c[0], c[1], c[2], c[3]);
     }
-    flush();
+    // What is left goes out with ONE atomic per workgroup: atomics on a single
+    // address retire one after the other, and one per wave (tens of thousands on a
+    // long vector) would outlast the whole pass.
+    if (lane == 0) s_left[wave] = stashed;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t total = 0;
+#pragma unroll
+        for (int w = 0; w < CNT_WAVES; ++w) total += s_left[w];
+        *s_base = total ? atomicAdd(&state->cand_count, (unsigned long long)total) : 0ull;
+    }
+    __syncthreads();
+    unsigned long long base = *s_base;
+    for (uint32_t w = 0; w < wave; ++w) base += s_left[w];
+    for (uint32_t j = lane; j < stashed; j += WAVE)
+        if (base + j < cand_cap) cand[base + j] = mine[j];
 }
 
 __global__ __launch_bounds__(CNT_BLOCK) void collect_kernel(
     const float* __restrict__ acc, uint32_t n, uint32_t piece, RadixState* state,
     uint32_t* __restrict__ cand, uint64_t cand_cap) {
     __shared__ uint32_t s_stash[CNT_WAVES][CNT_STASH];
+    __shared__ uint32_t s_left[CNT_WAVES];
+    __shared__ unsigned long long s_base;
     const float lo = __uint_as_float(state->cand_lo);       // a key below the Inf/NaN range, or NaN
     if (lo == lo)
-        collect_body(acc, n, piece, state, cand, cand_cap, TestFloat{lo}, s_stash);
+        collect_body(acc, n, piece, state, cand, cand_cap, TestFloat{lo}, s_stash, s_left, &s_base);
     else
-        collect_body(acc, n, piece, state, cand, cand_cap, TestKey{state->cand_lo}, s_stash);
+        collect_body(acc, n, piece, state, cand, cand_cap, TestKey{state->cand_lo}, s_stash, s_left,
+                     &s_base);
 }
 
 // Decide what the radix passes run over.
@@ -336,7 +360,8 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
                            hist_sample);
         hipLaunchKernelGGL(sample_range_kernel, dim3(1), dim3(256), 0, s, state, hist_sample,
                            nsamp * 1024, n, k);
-        const SelectShape shape = select_shape_for(n, CNT_WAVES, 256u * CNT_U);
+        static_assert(CNT_WAVES == SEL_WAVES, "the collect pass is cut like the select");
+        const SelectShape shape = select_shape(n);
         hipLaunchKernelGGL(collect_kernel, dim3(shape.nseg), dim3(CNT_BLOCK), 0, s, d_acc,
                            (uint32_t)n, shape.piece, state, cand, cand_cap);
     }
