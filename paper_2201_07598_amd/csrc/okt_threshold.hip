@@ -14,6 +14,8 @@
 //      11 + 11 + 9 bits, runs over the candidates only.  Otherwise, or when the
 //      vector is short or the workspace small, the same radix select runs over
 //      the whole vector (three more passes).
+// Six launches at most: wherever a complete histogram has to be read, the
+// workgroup that added its counts last does the reading, in the same launch.
 // Either way the answer is the exact order statistic: all arithmetic is integer
 // counting, the sample only decides how much is read.  State lives in the
 // workspace on the device; the host never waits.
@@ -32,12 +34,64 @@ struct RadixState {
     uint32_t cand_lo;      // every key >= cand_lo is a candidate
     uint32_t pad;
     unsigned long long cand_count;    // number of candidates found by the counting pass
+    uint32_t done[4];      // workgroups that have handed in their histogram: sample, digits 1-3
 };
 static_assert(sizeof(RadixState) <= RS_STATE_BYTES, "state fits its slot");
 
 constexpr int HIST_BLOCK = 256;
 constexpr int HIST_ITERS = 4;                              // float4 per thread per step
 constexpr int HIST_STEP4 = HIST_BLOCK * HIST_ITERS;        // float4 per workgroup per step
+
+// Find the bin that holds rank k_rem counting from the top bin down: 256 threads,
+// thread t owns the PER bins below the (t * PER) highest ones; an inclusive scan
+// over the threads' sums names the owner, who walks its own few bins.  The
+// owner (exactly one thread) stores (bin, keys above the bin) to s_result.
+template <int BITS>
+__device__ __forceinline__ void pick_bin(const uint32_t* __restrict__ hist, uint64_t k_rem,
+                                         uint64_t* s_wave_total, uint64_t* s_result) {
+    constexpr int BINS = 1 << BITS;
+    constexpr int PER = BINS / 256;                  // bins per thread (8 or 2)
+    const int t = threadIdx.x, lane = t & (WAVE - 1), wave = t >> 6;
+    uint32_t c[PER];
+    uint64_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        // j = 0 is the thread's highest bin; the counts were added by other workgroups
+        c[j] = __hip_atomic_load(&hist[BINS - 1 - (t * PER + j)], __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+        mine += c[j];
+    }
+    const uint64_t incl = wave_inclusive_scan<uint64_t>(mine);
+    if (lane == WAVE - 1) s_wave_total[wave] = incl;
+    __syncthreads();
+    uint64_t before = incl - mine;
+    for (int w = 0; w < wave; ++w) before += s_wave_total[w];
+    if (before < k_rem && k_rem <= before + mine) {  // true for exactly one thread
+        uint64_t above = before;
+        int j = 0;
+        while (j < PER - 1 && above + c[j] < k_rem) above += c[j++];
+        s_result[0] = (uint64_t)(BINS - 1 - (t * PER + j));
+        s_result[1] = above;                         // above < k_rem <= above + hist[bin]
+    }
+    __syncthreads();
+}
+
+// Adds a workgroup's count to the global histogram and waits for the answer: an
+// atomic that has returned has been carried out where every CU sees it, which a
+// release fence would only achieve by writing the whole L2 back.
+__device__ __forceinline__ void add_count(uint32_t* bin, uint32_t c) {
+    const uint32_t before = atomicAdd(bin, c);
+    asm volatile("" ::"v"(before));
+}
+// True in exactly one workgroup of the grid: the one that comes last.  Called by
+// every workgroup once its add_count calls have returned; the last one may then
+// read the complete histogram (with device-scope loads).
+__device__ __forceinline__ bool last_workgroup(uint32_t* counter, uint32_t* s_flag) {
+    __syncthreads();
+    if (threadIdx.x == 0) *s_flag = atomicAdd(counter, 1u) == gridDim.x - 1 ? 1u : 0u;
+    __syncthreads();
+    return *s_flag != 0;
+}
 
 // ---------------------------------------------------------------------------
 // radix passes (over the candidates, or over the whole vector)
@@ -46,19 +100,40 @@ constexpr int HIST_STEP4 = HIST_BLOCK * HIST_ITERS;        // float4 per workgro
 // above the digit equal state->prefix (always, for the first digit).  The source
 // is the candidate array or the vector itself, as the state says; both are
 // arrays of 32-bit words whose low 31 bits are the key.
-template <int SHIFT, int BITS, bool FIRST>
+// The first pass also decides what the passes run over: the candidates, if the
+// counting pass ran and rank k is among them, else the whole vector.  The
+// workgroup that hands in its counts last picks the digit (the bin that holds
+// the rank still sought) and leaves the state for the next pass; after the last
+// digit it writes the threshold and its count.
+template <int SHIFT, int BITS, int PASS>
 __global__ __launch_bounds__(HIST_BLOCK) void radix_hist_kernel(
-    const float* __restrict__ acc, const uint32_t* __restrict__ cand,
-    const RadixState* __restrict__ state, uint32_t* __restrict__ hist) {
+    const float* __restrict__ acc, const uint32_t* __restrict__ cand, RadixState* state,
+    uint32_t* __restrict__ hist, uint64_t n, uint64_t k, uint64_t cand_cap, int sampled,
+    float* threshold_out, uint64_t* count_ge_out) {
     constexpr int BINS = 1 << BITS;
+    constexpr bool FIRST = PASS == 1, LAST = PASS == 3;
+    static_assert(HIST_BLOCK == 256, "pick_bin is written for 256 threads");
     __shared__ uint32_t s_hist[BINS];
-    const uint32_t* src = state->use_cand ? cand : reinterpret_cast<const uint32_t*>(acc);
-    const uint32_t m = (uint32_t)state->m;
+    __shared__ uint64_t s_wave_total[4], s_result[2];
+    __shared__ uint32_t s_flag;
+    uint32_t use_cand;
+    uint64_t m64;
+    if (FIRST) {
+        const uint64_t found = state->cand_count;           // keys at or above cand_lo
+        use_cand = sampled && k <= found && found <= cand_cap ? 1u : 0u;   // rank k is among them
+        m64 = use_cand ? found : n;
+    } else {
+        use_cand = state->use_cand;
+        m64 = state->m;
+    }
+    const uint32_t* src = use_cand ? cand : reinterpret_cast<const uint32_t*>(acc);
+    const uint32_t m = (uint32_t)m64;
     const uint32_t m4 = m >> 2;
     uint32_t base4 = blockIdx.x * (uint32_t)HIST_STEP4;
-    if (base4 >= m4 && !(blockIdx.x == 0)) return;          // nothing for this workgroup
     for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) s_hist[b] = 0;
     const uint32_t prefix = FIRST ? 0u : state->prefix;
+    const uint64_t k_rem = FIRST ? k : state->k_rem;
+    const uint64_t above_so_far = FIRST ? 0ull : state->above;
     __syncthreads();
 
     auto take = [&](uint32_t word) {
@@ -91,59 +166,27 @@ __global__ __launch_bounds__(HIST_BLOCK) void radix_hist_kernel(
     __syncthreads();
     for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) {
         const uint32_t c = s_hist[b];
-        if (c) atomicAdd(&hist[b], c);
+        if (c) add_count(&hist[b], c);
     }
-}
+    if (!last_workgroup(&state->done[PASS], &s_flag)) return;
 
-// Find the bin that holds rank k_rem counting from the top bin down: 256 threads,
-// thread t owns the PER bins below the (t * PER) highest ones; an inclusive scan
-// over the threads' sums names the owner, who walks its own few bins.  The
-// owner (exactly one thread) stores (bin, keys above the bin) to s_result.
-template <int BITS>
-__device__ __forceinline__ void pick_bin(const uint32_t* __restrict__ hist, uint64_t k_rem,
-                                         uint64_t* s_wave_total, uint64_t* s_result) {
-    constexpr int BINS = 1 << BITS;
-    constexpr int PER = BINS / 256;                  // bins per thread (8 or 2)
-    const int t = threadIdx.x, lane = t & (WAVE - 1), wave = t >> 6;
-    uint32_t c[PER];
-    uint64_t mine = 0;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        c[j] = hist[BINS - 1 - (t * PER + j)];       // j = 0 is the thread's highest bin
-        mine += c[j];
-    }
-    const uint64_t incl = wave_inclusive_scan<uint64_t>(mine);
-    if (lane == WAVE - 1) s_wave_total[wave] = incl;
-    __syncthreads();
-    uint64_t before = incl - mine;
-    for (int w = 0; w < wave; ++w) before += s_wave_total[w];
-    if (before < k_rem && k_rem <= before + mine) {  // true for exactly one thread
-        uint64_t above = before;
-        int j = 0;
-        while (j < PER - 1 && above + c[j] < k_rem) above += c[j++];
-        s_result[0] = (uint64_t)(BINS - 1 - (t * PER + j));
-        s_result[1] = above;                         // above < k_rem <= above + hist[bin]
-    }
-    __syncthreads();
-}
-
-template <int BITS, bool LAST>
-__global__ __launch_bounds__(256) void radix_pick_kernel(
-    RadixState* state, const uint32_t* __restrict__ hist, float* threshold_out,
-    uint64_t* count_ge_out) {
-    __shared__ uint64_t s_wave_total[4], s_result[2];
-    const uint64_t k_rem = state->k_rem;
+    // ---- the complete histogram: pick the digit ----
     pick_bin<BITS>(hist, k_rem, s_wave_total, s_result);
     if (threadIdx.x != 0) return;
     const int bin = (int)s_result[0];
     const uint64_t above = s_result[1];
-    const uint32_t prefix = (state->prefix << BITS) | (uint32_t)bin;
-    state->prefix = prefix;
+    const uint32_t found = (prefix << BITS) | (uint32_t)bin;
+    state->prefix = found;
     state->k_rem = k_rem - above;
-    state->above += above;
+    state->above = above_so_far + above;
+    if (FIRST) {
+        state->use_cand = use_cand;
+        state->m = m64;
+    }
     if (LAST) {
-        *threshold_out = __uint_as_float(prefix);
-        *count_ge_out = state->above + hist[bin];
+        *threshold_out = __uint_as_float(found);
+        *count_ge_out = above_so_far + above +
+                        __hip_atomic_load(&hist[bin], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -153,13 +196,18 @@ __global__ __launch_bounds__(256) void radix_pick_kernel(
 // First-digit histogram over every `stride`-th block of 1024 elements.  A
 // workgroup takes SAMPLE_PER_WG sampled blocks with all their loads in flight,
 // so that few workgroups (few global atomics per hot bin) still cover the
-// sample at memory latency.
+// sample at memory latency.  The workgroup that comes last reads the bound off
+// the complete histogram: the first-digit bin that holds the sample rank
+// k' + margin, k' = k * sample / n; every key from the bottom of that bin up is
+// a candidate.
 constexpr int SAMPLE_PER_WG = 8;
 __global__ __launch_bounds__(HIST_BLOCK) void sample_hist_kernel(
     const float* __restrict__ acc, uint32_t nblocks_sampled, uint32_t stride,
-    uint32_t* __restrict__ hist) {
+    uint32_t* __restrict__ hist, RadixState* state, uint64_t n, uint64_t k) {
     constexpr int BINS = 1 << RS_BITS1;
     __shared__ uint32_t s_hist[BINS];
+    __shared__ uint64_t s_wave_total[4], s_result[2];
+    __shared__ uint32_t s_flag;
     for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) s_hist[b] = 0;
     __syncthreads();
     // sampled blocks are whole: the host only samples the first floor(n/1024) blocks
@@ -183,17 +231,11 @@ __global__ __launch_bounds__(HIST_BLOCK) void sample_hist_kernel(
     __syncthreads();
     for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) {
         const uint32_t c = s_hist[b];
-        if (c) atomicAdd(&hist[b], c);
+        if (c) add_count(&hist[b], c);
     }
-}
+    if (!last_workgroup(&state->done[0], &s_flag)) return;
 
-// From the sample histogram: the first-digit bin that holds the sample rank
-// k' + margin, k' = k * sample / n.  Every key from the bottom of that bin up is
-// a candidate.
-__global__ __launch_bounds__(256) void sample_range_kernel(RadixState* state,
-                                                           const uint32_t* __restrict__ hist,
-                                                           uint64_t sample, uint64_t n, uint64_t k) {
-    __shared__ uint64_t s_wave_total[4], s_result[2];
+    const uint64_t sample = (uint64_t)nblocks_sampled * 1024;
     // k' rounded up; margin of 16 standard deviations of a binomial count, and some
     const uint64_t kp = (k * sample + n - 1) / n;      // k, sample < 2^32: no overflow
     uint64_t margin = 64;
@@ -201,9 +243,7 @@ __global__ __launch_bounds__(256) void sample_range_kernel(RadixState* state,
     uint64_t r_lo = kp + margin;                                     // a sample rank safely below the target
     if (r_lo > sample) r_lo = sample;
     pick_bin<RS_BITS1>(hist, r_lo, s_wave_total, s_result);
-    const uint32_t bin_lo = (uint32_t)s_result[0];
-    if (threadIdx.x != 0) return;
-    state->cand_lo = bin_lo << 20;
+    if (threadIdx.x == 0) state->cand_lo = (uint32_t)s_result[0] << 20;
 }
 
 constexpr int CNT_BLOCK = 1024;
@@ -302,18 +342,6 @@ __global__ __launch_bounds__(CNT_BLOCK) void collect_kernel(
                      &s_base);
 }
 
-// Decide what the radix passes run over.
-__global__ void radix_setup_kernel(RadixState* state, uint64_t n, uint64_t k, uint64_t cand_cap,
-                                   int sampled) {
-    const uint64_t cand = state->cand_count;        // keys at or above cand_lo
-    const bool ok = sampled && k <= cand && cand <= cand_cap;   // rank k is among them
-    state->use_cand = ok ? 1u : 0u;
-    state->m = ok ? cand : n;
-    state->k_rem = k;
-    state->above = 0;
-    state->prefix = 0;
-}
-
 __global__ void radix_init_kernel(RadixState* state, uint32_t* hist, uint32_t words) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < words) hist[i] = 0;
@@ -357,33 +385,27 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
         hipLaunchKernelGGL(sample_hist_kernel,
                            dim3((unsigned)((nsamp + SAMPLE_PER_WG - 1) / SAMPLE_PER_WG)),
                            dim3(HIST_BLOCK), 0, s, d_acc, (uint32_t)nsamp, (uint32_t)stride,
-                           hist_sample);
-        hipLaunchKernelGGL(sample_range_kernel, dim3(1), dim3(256), 0, s, state, hist_sample,
-                           nsamp * 1024, n, k);
+                           hist_sample, state, n, k);
         static_assert(CNT_WAVES == SEL_WAVES, "the collect pass is cut like the select");
         const SelectShape shape = select_shape(n);
         hipLaunchKernelGGL(collect_kernel, dim3(shape.nseg), dim3(CNT_BLOCK), 0, s, d_acc,
                            (uint32_t)n, shape.piece, state, cand, cand_cap);
     }
-    hipLaunchKernelGGL(radix_setup_kernel, dim3(1), dim3(1), 0, s, state, n, k, cand_cap,
-                       sampled ? 1 : 0);
 
     // the radix passes are sized for the candidates when sampling ran (a failed
     // check makes them walk the whole vector with the same, smaller grid)
     const uint64_t expect = sampled ? n / 16 : n;
     const uint64_t steps = ((expect >> 2) + HIST_STEP4 - 1) / HIST_STEP4;
     const unsigned grid = (unsigned)(steps < 2048 ? (steps ? steps : 1) : 2048);
-    hipLaunchKernelGGL((radix_hist_kernel<20, RS_BITS1, true>), dim3(grid), dim3(HIST_BLOCK), 0, s,
-                       d_acc, cand, state, hist1);
-    hipLaunchKernelGGL((radix_pick_kernel<RS_BITS1, false>), dim3(1), dim3(256), 0, s, state,
-                       hist1, d_threshold_out, d_count_ge_out);
-    hipLaunchKernelGGL((radix_hist_kernel<9, RS_BITS2, false>), dim3(grid), dim3(HIST_BLOCK), 0, s,
-                       d_acc, cand, state, hist2);
-    hipLaunchKernelGGL((radix_pick_kernel<RS_BITS2, false>), dim3(1), dim3(256), 0, s, state,
-                       hist2, d_threshold_out, d_count_ge_out);
-    hipLaunchKernelGGL((radix_hist_kernel<0, RS_BITS3, false>), dim3(grid), dim3(HIST_BLOCK), 0, s,
-                       d_acc, cand, state, hist3);
-    hipLaunchKernelGGL((radix_pick_kernel<RS_BITS3, true>), dim3(1), dim3(256), 0, s, state,
-                       hist3, d_threshold_out, d_count_ge_out);
+    const int was_sampled = sampled ? 1 : 0;
+    hipLaunchKernelGGL((radix_hist_kernel<20, RS_BITS1, 1>), dim3(grid), dim3(HIST_BLOCK), 0, s,
+                       d_acc, cand, state, hist1, n, k, cand_cap, was_sampled, d_threshold_out,
+                       d_count_ge_out);
+    hipLaunchKernelGGL((radix_hist_kernel<9, RS_BITS2, 2>), dim3(grid), dim3(HIST_BLOCK), 0, s,
+                       d_acc, cand, state, hist2, n, k, cand_cap, was_sampled, d_threshold_out,
+                       d_count_ge_out);
+    hipLaunchKernelGGL((radix_hist_kernel<0, RS_BITS3, 3>), dim3(grid), dim3(HIST_BLOCK), 0, s,
+                       d_acc, cand, state, hist3, n, k, cand_cap, was_sampled, d_threshold_out,
+                       d_count_ge_out);
     return launch_status();
 }
