@@ -87,6 +87,55 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(
     }
 }
 
+// The same table for launches with few cells (a lone region): one WAVE per cell,
+// 64 evenly spaced probes per step, so a boundary is found in about log64 of the
+// contribution's length dependent round trips instead of log2 - this kernel is
+// nothing but that latency.  (For many regions the extra probes would cost more
+// memory traffic than the latency they save.)
+__global__ __launch_bounds__(256) void reduce_slices_wave_kernel(
+    const uint32_t* __restrict__ idx_cat, const uint64_t* __restrict__ seg_begin,
+    const uint64_t* __restrict__ seg_end, uint32_t seg_stride,
+    const uint32_t* __restrict__ lo_hi, uint32_t lo0, uint32_t hi0, uint32_t P,
+    uint32_t max_width, uint32_t slots, char* ws, uint32_t ws_region_bytes,
+    uint32_t table_offset) {
+    const uint32_t region = blockIdx.y;
+    const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
+    uint32_t* table = (uint32_t*)(ws + (size_t)region * ws_region_bytes + table_offset);
+    uint64_t* scan_state = (uint64_t*)(ws + (size_t)region * ws_region_bytes);
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < table_offset / 8;
+         i += gridDim.x * blockDim.x)
+        scan_state[i] = 0;
+    const uint64_t* begin = seg_begin + (size_t)region * seg_stride;
+    const uint64_t* end = seg_end + (size_t)region * seg_stride;
+    const uint64_t cells = (uint64_t)(r.ntiles + 1) * P;
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
+    const uint64_t waves = (uint64_t)gridDim.x * (blockDim.x / WAVE);
+    for (uint64_t c = (uint64_t)blockIdx.x * (blockDim.x / WAVE) + threadIdx.x / WAVE; c < cells;
+         c += waves) {
+        const uint32_t p = (uint32_t)(c / (r.ntiles + 1)), t = (uint32_t)(c % (r.ntiles + 1));
+        uint64_t bound = (uint64_t)r.lo + (uint64_t)t * slots;
+        if (bound > r.hi) bound = r.hi;
+        const uint32_t x = (uint32_t)bound;                 // bound <= hi < 2^32
+        const uint64_t cb = begin[p];
+        uint64_t lo = cb, hi = end[p] > cb ? end[p] : cb;   // the answer lies in [lo, hi]
+        while (hi - lo > (uint64_t)WAVE) {
+            const uint64_t step = (hi - lo + WAVE - 1) / WAVE;
+            const uint64_t at = lo + lane * step;
+            const bool below = at < hi && idx_cat[at] < x;
+            const uint32_t n_below = (uint32_t)__popcll(__ballot(below));   // lanes 0 .. n_below-1
+            if (n_below == 0) { hi = lo; break; }                           // idx_cat[lo] >= x
+            const uint64_t next = lo + (uint64_t)n_below * step;            // first probe not below x
+            lo = lo + (uint64_t)(n_below - 1) * step + 1;
+            if (next < hi) hi = next;
+        }
+        if (hi > lo) {
+            const bool below = lo + lane < hi && idx_cat[lo + lane] < x;
+            lo += (uint64_t)__popcll(__ballot(below));
+        }
+        if (lane == 0) table[(size_t)t * P + p] = (uint32_t)(lo - cb);
+    }
+}
+
 // Exclusive prefix over the popcounts of `words` bitmap words into s_wprefix;
 // returns the total (to every thread).  Called by the whole workgroup.
 __device__ __forceinline__ uint32_t bitmap_prefix(const uint32_t* s_bits, uint16_t* s_wprefix,
@@ -370,10 +419,17 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
     const uint64_t cells = (tiles + 1) * P;
     uint64_t sblocks = (cells + 255) / 256;
     if (sblocks > 4096) sblocks = 4096;
-    hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)sblocks, B), dim3(256), 0, s,
-                       d_idx_cat, d_seg_begin, d_seg_end, seg_stride, d_lo_hi, lo, hi, P, max_width,
-                       slots, (char*)d_ws,
-                       (uint32_t)region_bytes, table_offset);
+    if (cells * B <= 4096) {
+        // few cells: a wave each
+        hipLaunchKernelGGL(reduce_slices_wave_kernel, dim3((unsigned)((cells + 3) / 4), B),
+                           dim3(256), 0, s, d_idx_cat, d_seg_begin, d_seg_end, seg_stride, d_lo_hi,
+                           lo, hi, P, max_width, slots, (char*)d_ws, (uint32_t)region_bytes,
+                           table_offset);
+    } else {
+        hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)sblocks, B), dim3(256), 0, s,
+                           d_idx_cat, d_seg_begin, d_seg_end, seg_stride, d_lo_hi, lo, hi, P,
+                           max_width, slots, (char*)d_ws, (uint32_t)region_bytes, table_offset);
+    }
     hipLaunchKernelGGL(reduce_tile_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,
                        d_idx_cat, d_val_cat, d_seg_begin, seg_stride, d_lo_hi, lo, hi, P, max_width,
                        slots,
