@@ -67,15 +67,27 @@ __device__ __forceinline__ uint32_t select_round(uint32_t first, const float4& v
     return count + (uint32_t)(__popcll(bx) + __popcll(by) + __popcll(bz) + __popcll(bw));
 }
 
+// Where a walk first ran past a limit on its count: the start of that batch of
+// rounds and the count there (wave-uniform).  `hit` false: it never did.
+struct WalkMark {
+    uint64_t at;
+    uint32_t count;
+    bool hit;
+};
+
 // Walks the wave's piece [start, end) of acc in rounds of 256 elements, U rounds
 // in flight, and feeds every selected element to `sink` in ascending index
-// order.  Returns the number of selected elements.
+// order, ranks counting from `count`.  Returns the count at the end.  If `mark`
+// is given, it records the first batch after which the count exceeds `limit`.
 template <int U, typename Test, typename Sink>
 __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start, uint64_t end,
-                                                Test test, Sink&& sink) {
+                                                Test test, Sink&& sink, uint32_t count = 0,
+                                                WalkMark* mark = nullptr, uint32_t limit = 0) {
     const int lane = lane_id();
-    uint32_t count = 0;
     uint64_t r = start;
+    auto note = [&](uint64_t batch_start, uint32_t before) {
+        if (mark && !mark->hit && count > limit) *mark = WalkMark{batch_start, before, true};
+    };
     // The sink may store to acc.  Loads and stores retire through one in-order
     // counter, so the loads of the next batch are issued before this batch is
     // handed to the sink: they never queue behind its stores.
@@ -87,6 +99,7 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
     };
     if (r + 256 * U <= end) load_batch(v, r);
     for (; r + 256 * U <= end; r += 256 * U) {
+        const uint32_t before = count;
 #pragma unroll
         for (int u = 0; u < U; ++u) w[u] = v[u];
         if (r + 2 * 256 * U <= end) load_batch(v, r + 256 * U);
@@ -94,12 +107,16 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
         for (int u = 0; u < U; ++u)
             count = select_round((uint32_t)r + 256u * u, w[u], test(w[u].x), test(w[u].y),
                                  test(w[u].z), test(w[u].w), count, sink);
+        note(r, before);
     }
     for (; r + 256 <= end; r += 256) {                    // whole rounds short of a batch
+        const uint32_t before = count;
         const float4 x = reinterpret_cast<const float4*>(acc + r)[lane];
         count = select_round((uint32_t)r, x, test(x.x), test(x.y), test(x.z), test(x.w), count, sink);
+        note(r, before);
     }
     for (; r < end; r += 256) {                           // the ragged end of the vector
+        const uint32_t before = count;
         const uint64_t i = r + 4u * (uint32_t)lane;
         float e[4];
         bool s[4];
@@ -111,6 +128,7 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
         }
         count = select_round((uint32_t)r, make_float4(e[0], e[1], e[2], e[3]), s[0], s[1], s[2],
                              s[3], count, sink);
+        note(r, before);
     }
     return count;
 }
@@ -137,17 +155,19 @@ struct CooSource {
 // everything before it from the chained scan, and each wave writes its pairs to
 // their final place.  On entry the wave has seen `count` selected entries in its
 // piece [start, end) and holds the first `stashed` of them (in index order) in
-// its LDS stash, already zeroed in the residual; entries past the stash are
-// untouched.  Entries that do not fit the output are put back.  A wave whose
-// stash did not hold everything puts back what it zeroed and walks its piece a
-// second time, writing directly (dense thresholds only).
+// its LDS stash, already zeroed in the residual (if the source is zeroed at
+// all); entries past the stash are untouched.  Entries that do not fit the
+// output are put back.  A wave whose stash did not hold everything (locally
+// dense selection) writes out the `resume_count` entries that lie before
+// `resume_at`, puts the other stashed ones back, and walks the rest of its piece,
+// from `resume_at`, a second time, writing directly.
 template <int BLOCK, int U, int STASH, typename Test, typename Source>
 __device__ __forceinline__ void select_finish(
     float* __restrict__ acc, Test test, Source source, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t seg,
-    uint64_t start, uint64_t end, uint32_t count, uint32_t stashed, StashEntry* mine,
-    uint32_t* s_count, uint32_t* s_before) {
+    uint64_t start, uint64_t end, uint32_t count, uint32_t stashed, uint64_t resume_at,
+    uint32_t resume_count, StashEntry* mine, uint32_t* s_count, uint32_t* s_before) {
     constexpr int WAVES = BLOCK / WAVE;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
     if (lane == 0) s_count[wave] = count;
@@ -175,30 +195,33 @@ __device__ __forceinline__ void select_finish(
 
     // ---- emit in ascending index order ----
     const uint64_t first = (uint64_t)exclusive + wave_first;
-    if (count == stashed) {
-        for (uint32_t j = lane; j < count; j += WAVE) {
-            const uint64_t pos = first + j;
-            const StashEntry e = mine[j];
-            if (pos < capacity) {
-                idx_out[pos] = source.out_index(e.idx);
-                val_out[pos] = e.val;
-            } else if (Source::zero) {
-                acc[e.idx] = e.val;         // output full: the entry stays in the residual
-            }
+    const bool all_stashed = count == stashed;
+    const uint32_t final_entries = all_stashed ? count : resume_count;   // of the stash
+    for (uint32_t j = lane; j < final_entries; j += WAVE) {
+        const uint64_t pos = first + j;
+        const StashEntry e = mine[j];
+        if (pos < capacity) {
+            idx_out[pos] = source.out_index(e.idx);
+            val_out[pos] = e.val;
+        } else if (Source::zero) {
+            acc[e.idx] = e.val;             // output full: the entry stays in the residual
         }
-    } else {
+    }
+    if (!all_stashed) {
+        (void)start;
         if (Source::zero) {
-            for (uint32_t j = lane; j < stashed; j += WAVE) acc[mine[j].idx] = mine[j].val;
+            for (uint32_t j = resume_count + lane; j < stashed; j += WAVE)
+                acc[mine[j].idx] = mine[j].val;
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // stores land before the re-read
         }
-        select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
+        select_walk<U>(acc, resume_at, end, test, [&](uint32_t rank, uint32_t i, float x) {
             const uint64_t pos = first + rank;
             if (pos < capacity) {
                 idx_out[pos] = source.out_index(i);
                 val_out[pos] = x;
                 if (Source::zero) acc[i] = 0.0f;
             }
-        });
+        }, resume_count);
     }
     if (seg == nseg - 1 && tid == 0) {
         const uint64_t total = (uint64_t)exclusive + aggregate;
@@ -225,17 +248,18 @@ __device__ __forceinline__ void select_body(
     const uint64_t start = ((uint64_t)seg * WAVES + wave) * piece;
     const uint64_t end = start + piece < n ? start + piece : n;       // start >= n: empty
     StashEntry* mine = s_stash[wave];
+    WalkMark over = {start, 0u, false};          // the batch in which the stash ran full
     const uint32_t count =
         select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
             if (rank < (uint32_t)STASH) {
                 mine[rank] = StashEntry{i, x};
                 if (Source::zero) acc[i] = 0.0f;
             }
-        });
+        }, 0u, &over, (uint32_t)STASH);
     select_finish<BLOCK, U, STASH>(acc, test, source, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
                                    group_desc, nseg, seg, start, end, count,
-                                   count < (uint32_t)STASH ? count : (uint32_t)STASH, mine,
-                                   s_count, s_before);
+                                   count < (uint32_t)STASH ? count : (uint32_t)STASH, over.at,
+                                   over.count, mine, s_count, s_before);
 }
 
 // The accumulate and the select in one pass (reuse iterations of Ok-Topk SGD,
@@ -259,11 +283,17 @@ __device__ __forceinline__ void accumulate_select_body(
     const uint64_t end = start + piece < n ? start + piece : n;
     StashEntry* mine = s_stash[wave];
     uint32_t count = 0, stashed = 0;                 // wave-uniform
+    uint64_t resume_at = start;                      // first round that was not stashed
+    bool resumed = false;
 
     // one round of 256 elements whose accumulator values are in `a`; returns the
     // residual to store
     auto round = [&](uint32_t first, float4 a, bool sx, bool sy, bool sz, bool sw) -> float4 {
         const bool room = count <= (uint32_t)(STASH - 256) && count == stashed;
+        if (!room && !resumed) {
+            resumed = true;
+            resume_at = first;
+        }
         const uint32_t now = select_round(first, a, sx, sy, sz, sw, count,
                                           [&](uint32_t rank, uint32_t i, float x) {
                                               if (room) mine[rank] = StashEntry{i, x};
@@ -336,9 +366,10 @@ __device__ __forceinline__ void accumulate_select_body(
         if (inside[2]) res[i + 2] = out.z;
         if (inside[3]) res[i + 3] = out.w;
     }
+    // every stashed entry lies before resume_at: nothing to put back before the second walk
     select_finish<BLOCK, U, STASH>(res, test, DenseSource{}, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
-                                   group_desc, nseg, seg, start, end, count, stashed, mine,
-                                   s_count, s_before);
+                                   group_desc, nseg, seg, start, end, count, stashed, resume_at,
+                                   stashed, mine, s_count, s_before);
 }
 
 #ifndef OKT_SEL_WAVES_PER_EU
