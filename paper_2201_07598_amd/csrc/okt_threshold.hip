@@ -76,15 +76,21 @@ __device__ __forceinline__ void pick_bin(const uint32_t* __restrict__ hist, uint
     __syncthreads();
 }
 
-// Adds a workgroup's count to the global histogram and waits for the answer: an
+// Adds a workgroup's counts to the global histogram and waits for the answers: an
 // atomic that has returned has been carried out where every CU sees it, which a
 // release fence would only achieve by writing the whole L2 back.
-__device__ __forceinline__ void add_count(uint32_t* bin, uint32_t c) {
-    const uint32_t before = atomicAdd(bin, c);
-    asm volatile("" ::"v"(before));
+template <int BINS>
+__device__ __forceinline__ void add_counts(uint32_t* __restrict__ hist, const uint32_t* s_hist) {
+    uint32_t seen = 0;
+#pragma unroll
+    for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) {     // all out first, then one wait
+        const uint32_t c = s_hist[b];
+        if (c) seen |= atomicAdd(&hist[b], c);
+    }
+    asm volatile("" ::"v"(seen));
 }
 // True in exactly one workgroup of the grid: the one that comes last.  Called by
-// every workgroup once its add_count calls have returned; the last one may then
+// every workgroup once add_counts has returned; the last one may then
 // read the complete histogram (with device-scope loads).
 __device__ __forceinline__ bool last_workgroup(uint32_t* counter, uint32_t* s_flag) {
     __syncthreads();
@@ -164,10 +170,7 @@ __global__ __launch_bounds__(HIST_BLOCK) void radix_hist_kernel(
     }
     if (blockIdx.x == 0 && threadIdx.x < (m & 3u)) take(src[(m4 << 2) + threadIdx.x]);
     __syncthreads();
-    for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) {
-        const uint32_t c = s_hist[b];
-        if (c) add_count(&hist[b], c);
-    }
+    add_counts<BINS>(hist, s_hist);
     if (!last_workgroup(&state->done[PASS], &s_flag)) return;
 
     // ---- the complete histogram: pick the digit ----
@@ -229,10 +232,7 @@ __global__ __launch_bounds__(HIST_BLOCK) void sample_hist_kernel(
         }
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < BINS; b += HIST_BLOCK) {
-        const uint32_t c = s_hist[b];
-        if (c) add_count(&hist[b], c);
-    }
+    add_counts<BINS>(hist, s_hist);
     if (!last_workgroup(&state->done[0], &s_flag)) return;
 
     const uint64_t sample = (uint64_t)nblocks_sampled * 1024;
@@ -396,7 +396,11 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
     // check makes them walk the whole vector with the same, smaller grid)
     const uint64_t expect = sampled ? n / 16 : n;
     const uint64_t steps = ((expect >> 2) + HIST_STEP4 - 1) / HIST_STEP4;
-    const unsigned grid = (unsigned)(steps < 2048 ? (steps ? steps : 1) : 2048);
+    // every workgroup ends with up to 2048 returning atomics on the shared histogram:
+    // over the candidates (a few MB) a workgroup per CU is plenty, over a whole
+    // vector the passes want the memory parallelism of many more
+    const uint64_t grid_max = sampled ? 256 : 2048;
+    const unsigned grid = (unsigned)(steps < grid_max ? (steps ? steps : 1) : grid_max);
     const int was_sampled = sampled ? 1 : 0;
     hipLaunchKernelGGL((radix_hist_kernel<20, RS_BITS1, 1>), dim3(grid), dim3(HIST_BLOCK), 0, s,
                        d_acc, cand, state, hist1, n, k, cand_cap, was_sampled, d_threshold_out,
