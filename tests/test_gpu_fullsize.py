@@ -15,22 +15,29 @@ from tests.okt_harness import (DEV, GpuPath, bits_equal, gpu_reduce, reduce_tole
 pytestmark = pytest.mark.gpu
 
 
-def loop(w, iterations):
+def loop(w, iterations, fused=False):
+    """fused: the iterations that reuse the threshold take okt_accumulate_select,
+    as bench.py's step does."""
     gpu = GpuPath(w.n, 4 * w.k)
     res = np.zeros(w.n, dtype=np.float32)
     th = None
     ridx = None
     for it in range(iterations):
         g = wl.gradient(w, it)
-        gpu.accumulate(to_dev(g), w.lr)
         acc = orc.residual_accumulate(g, res, w.lr)
-        del g
-        if w.refresh(it):
-            gpu.threshold(w.k)
-            th, cnt = orc.topk_threshold_exact(acc, w.k, method="partition")
-            assert gpu.th.cpu().numpy().view(np.uint32)[0] == np.float32(th).view(np.uint32), it
-            assert int(u64(gpu.count_ge)[0]) == cnt, it
-        gpu.select()
+        if fused and not w.refresh(it):
+            okt.okt_accumulate_select(to_dev(g), gpu.residual, w.lr, gpu.th, gpu.idx, gpu.val,
+                                      gpu.nnz, gpu.ws, capacity=gpu.capacity)
+            del g
+        else:
+            gpu.accumulate(to_dev(g), w.lr)
+            del g
+            if w.refresh(it):
+                gpu.threshold(w.k)
+                th, cnt = orc.topk_threshold_exact(acc, w.k, method="partition")
+                assert gpu.th.cpu().numpy().view(np.uint32)[0] == np.float32(th).view(np.uint32), it
+                assert int(u64(gpu.count_ge)[0]) == cnt, it
+            gpu.select()
         ridx, rval, res, total = orc.threshold_select(acc, th, capacity=4 * w.k)
         del acc
         idx, val, emitted, gtotal = gpu.selected()
@@ -73,6 +80,14 @@ def test_cfg2_full_size():
     lo, hi = 0, w.n // w.P                      # the region bench.py reduces
     ref = check_reduce(*wl.contributions(w, lo, hi), lo, hi)
     assert ref["idx"].size > 0.9 * w.P * w.m
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("name,iterations", [("cfg2", 3), ("cfg3", 2)])
+def test_full_size_fused_reuse_iterations(name, iterations):
+    # the step bench.py times: iteration 0 in four calls, the others in one fused call;
+    # the bench's vector selects whole layers (the stash-overflow path at full size)
+    loop(wl.WORKLOADS[name], iterations, fused=True)
 
 
 @pytest.mark.timeout(300)
