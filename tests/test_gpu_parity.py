@@ -238,7 +238,7 @@ def test_accumulate_select_degenerate_and_truncated():
     n = 300_007
     g, e = lap(1, n), lap(2, n, 3e-3)
     assert check_fused(g, e, 1.0, np.float32(np.inf), 8) == 0
-    assert check_fused(g, e, 1.0, np.float32(0.0), n) == n          # dense: second walk of every piece
+    assert check_fused(g, e, 1.0, np.float32(0.0), n) == n          # everything selected
     assert check_fused(g, e, 1.0, np.float32(0.0), 1000) == n       # dense and truncated
     total = check_fused(g, e, 0.5, np.float32(2e-3), n)
     assert total > 5000
@@ -249,6 +249,62 @@ def test_accumulate_select_degenerate_and_truncated():
     gg = np.full(5000, 1.0 + 2.0 ** -12, dtype=np.float32)
     ee = np.full(5000, -(1.0 + 2.0 ** -11), dtype=np.float32)
     assert check_fused(gg, ee, 1.0 + 2.0 ** -12, np.float32(1e-30), 5000) == 0
+
+
+# ---------------------------------------------- selection that is dense in places
+def layered(n, seed=5):
+    """A vector whose selection is locally dense, as a real gradient's is: a third
+    far above a threshold of 1 (84 % selected), a third far below (none), a third
+    around it (32 %: some pieces overflow their stash part-way, some do not)."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal(n).astype(np.float32)
+    x[: n // 3] *= 5.0
+    x[n // 3: 2 * (n // 3)] *= 0.1
+    return x
+
+
+@pytest.mark.timeout(300)
+def test_select_where_pieces_overflow_their_stash():
+    # long enough that a wave's piece (about n / 4096) holds more selected entries
+    # than its stash where the selection is dense
+    n = 12_000_003
+    acc = layered(n)
+    one = np.float32(1.0)
+    total = check_select(acc, one, n)
+    assert 0.35 * n < total < 0.45 * n
+    for cap in (1000, total // 5, total // 2 + 3, total - 1):
+        check_select(acc, one, cap)                  # the output fills up at various places
+    assert check_select(acc, np.float32(0.0), n) == n
+    # the same selection without the zeroing, and over a COO of the same length
+    d_acc, d_th = to_dev(acc), to_dev(np.array([1.0], dtype=np.float32))
+    ridx, rval, _, _ = orc.threshold_select(acc, one)
+    idx = torch.full((total,), -1, dtype=torch.int32, device=DEV)
+    val = torch.zeros(total, dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    ws = workspace(okt.okt_workspace_bytes(n, 0))
+    okt.okt_threshold_select_copy(d_acc, d_th, idx, val, nnz, ws)
+    assert tuple(u64(nnz)) == (total, total)
+    assert np.array_equal(u32(idx), ridx) and bits_equal(val.cpu().numpy(), rval)
+    assert bits_equal(d_acc.cpu().numpy(), acc)
+    coo_idx = (np.arange(n, dtype=np.uint64) * 3 + 7).astype(np.uint32)
+    idx.fill_(-1)
+    okt.okt_coo_threshold_select(to_dev(coo_idx), d_acc, to_dev(np.array([n], dtype=np.uint64)), d_th,
+                                 idx, val, nnz, ws)
+    assert tuple(u64(nnz)) == (total, total)
+    assert np.array_equal(u32(idx), coo_idx[ridx]) and bits_equal(val.cpu().numpy(), rval)
+
+
+@pytest.mark.timeout(300)
+def test_accumulate_select_where_pieces_overflow_their_stash():
+    n = 12_000_003
+    acc = layered(n, seed=6)
+    g = lap(7, n, 0.3)
+    e = (acc - g * np.float32(0.5)).astype(np.float32)      # eps + 0.5 g is near `acc`, layered alike
+    total = check_fused(g, e, 0.5, np.float32(1.0), n)
+    assert 0.3 * n < total < 0.5 * n
+    for cap in (1000, total // 3 + 1, total - 1):
+        check_fused(g, e, 0.5, np.float32(1.0), cap)
+    assert check_fused(g, e, 0.5, np.float32(0.0), n) == n
 
 
 # ------------------------------------------------------------------- partition
