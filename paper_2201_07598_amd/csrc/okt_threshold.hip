@@ -8,7 +8,7 @@
 //   2. One streaming pass over the whole vector copies every key at or above
 //      that bound, a little more than k of them, to the workspace (the select
 //      kernel's loop: one compare per element, per-wave LDS stash, one global
-//      atomic per flush).
+//      atomic per workgroup for what the stashes hold at the end).
 //   3. If at least k keys were collected (always, unless the sample misled),
 //      rank k is among them, and an exact MSD radix select, digits of
 //      11 + 11 + 9 bits, runs over the candidates only.  Otherwise, or when the
