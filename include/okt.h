@@ -54,6 +54,20 @@ const char* okt_status_string(int status);
  */
 const char* okt_last_hip_error(void);
 
+/*
+ * Measurement hook.  The next call this thread makes records `start_event` right
+ * before and `stop_event` right after the launch of its main kernel (hipEvent_t
+ * passed as void*; either may be NULL), on the stream of that call - the kernel
+ * that moves the data, not the small launches around it (clearing of scan state,
+ * slice table, histogram bookkeeping): okt_residual_accumulate, the select
+ * family, okt_accumulate_select, okt_region_partition, the tile kernel of the
+ * reduce family, the collect pass of okt_topk_threshold_exact (not recorded when
+ * that call takes its unsampled path), the intersect kernel.  The pair is used
+ * once and forgotten.  For benchmarks: so that an event time can be compared with
+ * a profiler's kernel duration.
+ */
+void okt_time_next_kernel(void* start_event, void* stop_event);
+
 /* Library version, major * 10000 + minor * 100 + patch. */
 int okt_version(void);
 

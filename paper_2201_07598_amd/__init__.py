@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     okt_sparse_reduce_batch_workspace_bytes,
     okt_sparse_reduce_segments,
     okt_status_string,
+    okt_time_next_kernel,
     okt_threshold_select,
     okt_threshold_select_copy,
     okt_topk_threshold_exact,

@@ -20,6 +20,7 @@ c_u32, c_u64, c_sz, c_vp, c_f32, c_int = (ctypes.c_uint32, ctypes.c_uint64, ctyp
 SIGNATURES = {
     "okt_status_string": (ctypes.c_char_p, [c_int]),
     "okt_last_hip_error": (ctypes.c_char_p, []),
+    "okt_time_next_kernel": (None, [c_vp, c_vp]),
     "okt_version": (c_int, []),
     "okt_workspace_bytes": (c_sz, [c_u64, c_u32]),
     "okt_sparse_reduce_batch_workspace_bytes": (c_sz, [c_u32, c_u32, c_u32]),
@@ -86,6 +87,13 @@ def okt_status_string(status: int) -> str:
 
 def okt_last_hip_error() -> str:
     return load_library().okt_last_hip_error().decode()
+
+
+def okt_time_next_kernel(start_event, stop_event) -> None:
+    """torch.cuda.Event objects (already recorded once, so that they exist) or None."""
+    load_library().okt_time_next_kernel(
+        ctypes.c_void_p(start_event.cuda_event if start_event is not None else None),
+        ctypes.c_void_p(stop_event.cuda_event if stop_event is not None else None))
 
 
 def okt_version() -> int:

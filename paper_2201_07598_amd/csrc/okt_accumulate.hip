@@ -71,7 +71,9 @@ extern "C" int okt_residual_accumulate(const float* d_grad, float* d_residual_in
     const uint64_t n4 = n >> 2;
     // the last workgroup also owns the n % 4 scalars, so there is always one
     const uint64_t blocks = n4 / ACC_TILE4 + 1;
+    timing_before((hipStream_t)stream);
     hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)blocks), dim3(ACC_BLOCK), 0,
                        (hipStream_t)stream, d_grad, d_residual_inout, lr, (uint32_t)n);
+    timing_after((hipStream_t)stream);
     return launch_status();
 }

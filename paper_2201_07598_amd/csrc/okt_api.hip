@@ -16,6 +16,17 @@ int launch_status() {
     return e == hipSuccess ? OKT_OK : launch_failed(e);
 }
 
+static thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+
+void timing_before(hipStream_t stream) {
+    if (g_time_start) (void)hipEventRecord(g_time_start, stream);
+    g_time_start = nullptr;
+}
+void timing_after(hipStream_t stream) {
+    if (g_time_stop) (void)hipEventRecord(g_time_stop, stream);
+    g_time_stop = nullptr;
+}
+
 __global__ void zero_words_kernel(uint64_t* p, uint64_t words) {
     uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
@@ -38,6 +49,11 @@ hipError_t launch_zero_words(void* p, uint64_t words, hipStream_t stream) {
 extern "C" {
 
 const char* okt_last_hip_error(void) { return hipGetErrorString(okt::g_last_hip_error); }
+
+void okt_time_next_kernel(void* start_event, void* stop_event) {
+    okt::g_time_start = (hipEvent_t)start_event;
+    okt::g_time_stop = (hipEvent_t)stop_event;
+}
 
 const char* okt_status_string(int status) {
     switch (status) {

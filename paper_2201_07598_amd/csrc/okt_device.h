@@ -165,6 +165,11 @@ hipError_t launch_zero_words(void* p, uint64_t words, hipStream_t stream);
 int launch_status();
 int launch_failed(hipError_t e);
 
+// Measurement hook (okt_time_next_kernel): record the pending pair of events, if
+// any, right before and right after the launch of a call's main kernel.
+void timing_before(hipStream_t stream);
+void timing_after(hipStream_t stream);
+
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 }  // namespace okt

@@ -52,7 +52,9 @@ extern "C" int okt_region_partition(const uint32_t* d_idx, const uint64_t* d_nnz
         !aligned(d_bounds_out, 4)) return OKT_ERR_INVALID_ARG;
     uint64_t blocks = ((uint64_t)R + 1 + 255) / 256;
     if (blocks > 4096) blocks = 4096;
+    timing_before((hipStream_t)stream);
     hipLaunchKernelGGL(partition_kernel, dim3((unsigned)blocks), dim3(256), 0,
                        (hipStream_t)stream, d_idx, d_nnz, n, R, d_bounds_out, d_offsets_out);
+    timing_after((hipStream_t)stream);
     return launch_status();
 }

@@ -430,11 +430,13 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
                            d_idx_cat, d_seg_begin, d_seg_end, seg_stride, d_lo_hi, lo, hi, P,
                            max_width, slots, (char*)d_ws, (uint32_t)region_bytes, table_offset);
     }
+    timing_before(s);
     hipLaunchKernelGGL(reduce_tile_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,
                        d_idx_cat, d_val_cat, d_seg_begin, seg_stride, d_lo_hi, lo, hi, P, max_width,
                        slots,
                        d_idx_out, d_val_out, capacity, d_nnz_out, d_dense, (char*)d_ws,
                        (uint32_t)region_bytes, table_offset);
+    timing_after(s);
     return launch_status();
 }
 

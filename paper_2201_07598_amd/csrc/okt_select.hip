@@ -48,10 +48,12 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
     uint64_t* group_desc = seg_desc + shape.nseg;
     if (launch_zero_words(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
+    timing_before(s);
     hipLaunchKernelGGL((select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET, Source>),
                        dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_acc, (uint32_t)n, d_threshold,
                        d_idx_out, d_val_out, capacity, d_nnz_out, hdr, seg_desc, group_desc,
                        shape.nseg, shape.piece);
+    timing_after(s);
     return launch_status();
 }
 
@@ -101,10 +103,12 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
     uint64_t* group_desc = seg_desc + shape.nseg;
     if (launch_zero_words(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
+    timing_before(s);
     hipLaunchKernelGGL((accumulate_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET>),
                        dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout, lr,
                        (uint32_t)n, d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out, hdr,
                        seg_desc, group_desc, shape.nseg, shape.piece);
+    timing_after(s);
     return launch_status();
 }
 
@@ -135,9 +139,11 @@ extern "C" int okt_coo_threshold_select(const uint32_t* d_idx_in, const float* d
     uint64_t* group_desc = seg_desc + shape.nseg;
     if (launch_zero_words(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
+    timing_before(s);
     hipLaunchKernelGGL((coo_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET>),
                        dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_idx_in, d_val_in, d_nnz_in,
                        (uint32_t)max_nnz, d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out,
                        hdr, seg_desc, group_desc, shape.nseg, shape.piece);
+    timing_after(s);
     return launch_status();
 }

@@ -388,8 +388,10 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
                            hist_sample, state, n, k);
         static_assert(CNT_WAVES == SEL_WAVES, "the collect pass is cut like the select");
         const SelectShape shape = select_shape(n);
+        timing_before(s);
         hipLaunchKernelGGL(collect_kernel, dim3(shape.nseg), dim3(CNT_BLOCK), 0, s, d_acc,
                            (uint32_t)n, shape.piece, state, cand, cand_cap);
+        timing_after(s);
     }
 
     // the radix passes are sized for the candidates when sampling ran (a failed
