@@ -33,6 +33,22 @@ def test_accumulate_bitwise(n, lr):
     assert bits_equal(d_e.cpu().numpy(), orc.residual_accumulate(g, e, lr))
 
 
+def test_time_next_kernel_brackets_one_launch():
+    n = 4_000_000
+    g, e = to_dev(lap(1, n)), to_dev(lap(2, n))
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); b.record()                            # the events exist from here on
+    torch.cuda.synchronize()
+    okt.okt_time_next_kernel(a, b)
+    okt.okt_residual_accumulate(g, e, 0.5)
+    torch.cuda.synchronize()
+    first = a.elapsed_time(b)
+    assert 0.003 < first < 5.0                        # ms: one pass over 48 MB
+    okt.okt_residual_accumulate(g, e, 0.5)            # the pair was used once: not recorded again
+    torch.cuda.synchronize()
+    assert a.elapsed_time(b) == first
+
+
 def test_accumulate_not_fused_and_subnormals():
     lr = 1.0 + 2.0 ** -12
     g = np.array([1.0 + 2.0 ** -12, 1e-40, -1e-45, 3e-39] * 8, dtype=np.float32)
