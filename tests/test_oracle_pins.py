@@ -564,16 +564,21 @@ def test_balance_plan_moves_every_entry_once_and_keeps_the_order():
 def test_balance_plan_extreme_case_and_trigger_rule():
     # Sec. 3.1.2: all global top-k values on one worker; balancing then moves
     # k (P-1)/P entries = 2k (P-1)/P words, one chunk to every other worker
+    gold = read_golden("balance_extreme.txt")
     k, P = 10_000, 8
+    env = {"P": P, "k": k}
     for owner in (0, 3, P - 1):
         sizes = [0] * P
         sizes[owner] = k
         triggered, chunks = orc.balance_plan(sizes)
         assert triggered
         moved = [c for c in chunks if c[0] != c[1]]
-        assert len(moved) == P - 1 and {c[1] for c in moved} == set(range(P)) - {owner}
-        assert sum(c[4] for c in moved) == k * (P - 1) // P
-        assert 2 * sum(c[4] for c in moved) == 2 * k * (P - 1) // P
+        assert len(moved) == eval(gold["extreme_chunks_sent"], env)
+        assert {c[1] for c in moved} == set(range(P)) - {owner}
+        assert 2 * sum(c[4] for c in moved) == eval(gold["extreme_words_moved"], env)
+    factor = int(gold["trigger_factor"])
+    assert orc.balance_plan([factor * 8 + 1, 8, 8, 8, 7, 0, 0, 0])[0] is True      # avg 8
+    assert orc.balance_plan([factor * 8, 8, 8, 8, 8, 0, 0, 0])[0] is False
     # "more than four times the average": exactly four times does not trigger
     assert orc.balance_plan([40, 10, 10, 10, 10, 10, 10, 10, 10, 10, 10, 10, 10])[0] is False   # avg 12.3, 4x = 49.2
     assert orc.balance_plan([16, 0, 0, 0])[0] is False            # P = 4: the max is at most 4 x avg
