@@ -9,9 +9,10 @@
 // Work proportional to the local list (about k entries), far below the dense
 // passes of an iteration.  A workgroup takes a tile of consecutive local entries;
 // because both lists ascend, everything the tile can match lies in one window of
-// the global list, found by two binary searches per tile; each entry is then
-// searched in that window only.  The matched indices are written in ascending
-// order at a position taken from the chained scan over tile counts.
+// the global list, whose ends two waves find with a 64-ary search; the window is
+// staged in LDS (if it fits) and each entry is searched in it.  The matched
+// indices are written in ascending order at a position taken from the chained
+// scan over tile counts.
 #include "okt_device.h"
 #include "okt_sizes.h"
 
