@@ -68,6 +68,22 @@ const char* okt_last_hip_error(void);
  */
 void okt_time_next_kernel(void* start_event, void* stop_event);
 
+/*
+ * Measurement only: two kernels that do none of the method's work and show what
+ * plain streaming reaches on the GPU at hand, to be timed beside the hot path
+ * (okt_time_next_kernel brackets them like the others).
+ *   okt_stream_copy  d_dst[i] = d_src[i], i < n: 4 B read + 4 B written per element.
+ *   okt_stream_sum   reads d_src[0..n) once and writes OKT_STREAM_SUM_PARTIALS
+ *                    partial sums (fp32, summation order unspecified) to
+ *                    d_partials_out: 4 B read per element.
+ * Device pointers, 16-byte aligned (d_partials_out: 4); the buffers must not
+ * overlap; n < 2^32; n == 0 is a no-op for the copy and writes zeros for the sum.
+ * Returns OKT_ERR_INVALID_ARG before any launch otherwise.
+ */
+#define OKT_STREAM_SUM_PARTIALS 2048
+int okt_stream_copy(const float* d_src, float* d_dst, uint64_t n, void* stream);
+int okt_stream_sum(const float* d_src, uint64_t n, float* d_partials_out, void* stream);
+
 /* Library version, major * 10000 + minor * 100 + patch. */
 int okt_version(void);
 

@@ -5,6 +5,7 @@ is no CPU fallback: without the built HIP library every call raises.
 """
 from .binding import (  # noqa: F401
     OktError,
+    STREAM_SUM_PARTIALS,
     library_path,
     load_library,
     okt_accumulate_select,
@@ -20,6 +21,8 @@ from .binding import (  # noqa: F401
     okt_sparse_reduce_batch_workspace_bytes,
     okt_sparse_reduce_segments,
     okt_status_string,
+    okt_stream_copy,
+    okt_stream_sum,
     okt_time_next_kernel,
     okt_threshold_select,
     okt_threshold_select_copy,

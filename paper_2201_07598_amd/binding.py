@@ -22,6 +22,8 @@ SIGNATURES = {
     "okt_last_hip_error": (ctypes.c_char_p, []),
     "okt_time_next_kernel": (None, [c_vp, c_vp]),
     "okt_version": (c_int, []),
+    "okt_stream_copy": (c_int, [c_vp, c_vp, c_u64, c_vp]),
+    "okt_stream_sum": (c_int, [c_vp, c_u64, c_vp, c_vp]),
     "okt_workspace_bytes": (c_sz, [c_u64, c_u32]),
     "okt_sparse_reduce_batch_workspace_bytes": (c_sz, [c_u32, c_u32, c_u32]),
     "okt_residual_accumulate": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp]),
@@ -162,6 +164,29 @@ def okt_residual_accumulate(grad, residual_inout, lr: float, stream=None) -> Non
     _check("okt_residual_accumulate", load_library().okt_residual_accumulate(
         _ptr(grad, torch.float32, "grad"), _ptr(residual_inout, torch.float32, "residual_inout"),
         float(lr), n, _stream(stream)))
+
+
+STREAM_SUM_PARTIALS = 2048     # OKT_STREAM_SUM_PARTIALS
+
+
+def okt_stream_copy(src, dst, stream=None) -> None:
+    """Measurement only: dst[:] = src with the library's plain copy kernel."""
+    torch = _torch()
+    if src.numel() != dst.numel():
+        raise ValueError("src and dst must have the same length")
+    _check("okt_stream_copy", load_library().okt_stream_copy(
+        _ptr(src, torch.float32, "src"), _ptr(dst, torch.float32, "dst"), src.numel(),
+        _stream(stream)))
+
+
+def okt_stream_sum(src, partials_out, stream=None) -> None:
+    """Measurement only: one read of src; STREAM_SUM_PARTIALS fp32 partial sums out."""
+    torch = _torch()
+    if partials_out.numel() < STREAM_SUM_PARTIALS:
+        raise ValueError(f"partials_out needs {STREAM_SUM_PARTIALS} elements")
+    _check("okt_stream_sum", load_library().okt_stream_sum(
+        _ptr(src, torch.float32, "src"), src.numel(),
+        _ptr(partials_out, torch.float32, "partials_out"), _stream(stream)))
 
 
 def okt_topk_threshold_exact(acc, k: int, threshold_out, count_ge_out, ws, stream=None) -> None:

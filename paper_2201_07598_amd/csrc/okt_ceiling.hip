@@ -1,0 +1,97 @@
+// okt_stream_copy, okt_stream_sum: plain streaming kernels that do none of the
+// method's work.  A benchmark times them beside the hot path to know what a
+// kernel that only moves bytes reaches on the chip it runs on: the copy for a
+// step that reads and writes (accumulate, 8 B in + 4 B out per element), the sum
+// for a step that only reads (select at low density, the threshold passes).
+#include "okt_device.h"
+
+namespace okt {
+
+constexpr int CEIL_BLOCK = 256;
+constexpr int CEIL_ITERS = 4;
+constexpr int CEIL_TILE4 = CEIL_BLOCK * CEIL_ITERS;       // float4 per workgroup and trip
+constexpr uint32_t CEIL_SUM_GROUPS = OKT_STREAM_SUM_PARTIALS;
+
+__global__ __launch_bounds__(CEIL_BLOCK) void stream_copy_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, uint32_t n) {
+    const uint32_t n4 = n >> 2;
+    const uint32_t base4 = blockIdx.x * (uint32_t)CEIL_TILE4;
+    const float4* s4 = reinterpret_cast<const float4*>(src);
+    float4* d4 = reinterpret_cast<float4*>(dst);
+    if (base4 + CEIL_TILE4 <= n4) {
+        float4 v[CEIL_ITERS];
+#pragma unroll
+        for (int it = 0; it < CEIL_ITERS; ++it) v[it] = s4[base4 + it * CEIL_BLOCK + threadIdx.x];
+#pragma unroll
+        for (int it = 0; it < CEIL_ITERS; ++it) d4[base4 + it * CEIL_BLOCK + threadIdx.x] = v[it];
+        return;
+    }
+    for (int it = 0; it < CEIL_ITERS; ++it) {
+        const uint32_t i = base4 + it * CEIL_BLOCK + threadIdx.x;
+        if (i < n4) d4[i] = s4[i];
+    }
+    const uint32_t tail = (n4 << 2) + threadIdx.x;
+    if (threadIdx.x < 4 && tail < n) dst[tail] = src[tail];
+}
+
+// Every workgroup strides over the vector, CEIL_ITERS 16-byte loads in flight per
+// thread, and leaves one partial sum; nothing else is written.
+__global__ __launch_bounds__(CEIL_BLOCK) void stream_sum_kernel(
+    const float* __restrict__ src, uint32_t n, float* __restrict__ partials) {
+    __shared__ float s_wave[CEIL_BLOCK / 64];
+    const uint32_t n4 = n >> 2;
+    const float4* s4 = reinterpret_cast<const float4*>(src);
+    float sum = 0.f;
+    const uint32_t stride4 = gridDim.x * (uint32_t)CEIL_TILE4;
+    // trips = ceil(n4 / stride4) for every workgroup: the loop bound is uniform
+    for (uint64_t base4 = (uint64_t)blockIdx.x * CEIL_TILE4; base4 < n4; base4 += stride4) {
+        float4 v[CEIL_ITERS];
+#pragma unroll
+        for (int it = 0; it < CEIL_ITERS; ++it) {
+            const uint64_t i = base4 + (uint64_t)it * CEIL_BLOCK + threadIdx.x;
+            v[it] = i < n4 ? s4[i] : float4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int it = 0; it < CEIL_ITERS; ++it) sum += (v[it].x + v[it].y) + (v[it].z + v[it].w);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 4) {
+        const uint32_t tail = (n4 << 2) + threadIdx.x;
+        if (tail < n) sum += src[tail];
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+    if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < CEIL_BLOCK / 64; ++w) t += s_wave[w];
+        partials[blockIdx.x] = t;
+    }
+}
+
+}  // namespace okt
+
+extern "C" int okt_stream_copy(const float* d_src, float* d_dst, uint64_t n, void* stream) {
+    using namespace okt;
+    if (n == 0) return OKT_OK;
+    if (!d_src || !d_dst || n > 0xffffffffull) return OKT_ERR_INVALID_ARG;
+    if (!aligned(d_src, 16) || !aligned(d_dst, 16)) return OKT_ERR_INVALID_ARG;
+    const uint64_t blocks = (n >> 2) / CEIL_TILE4 + 1;     // the last one owns the ragged end
+    timing_before((hipStream_t)stream);
+    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(CEIL_BLOCK), 0,
+                       (hipStream_t)stream, d_src, d_dst, (uint32_t)n);
+    timing_after((hipStream_t)stream);
+    return launch_status();
+}
+
+extern "C" int okt_stream_sum(const float* d_src, uint64_t n, float* d_partials_out, void* stream) {
+    using namespace okt;
+    if ((!d_src && n) || !d_partials_out || n > 0xffffffffull) return OKT_ERR_INVALID_ARG;
+    if (!aligned(d_src, 16) || !aligned(d_partials_out, 4)) return OKT_ERR_INVALID_ARG;
+    timing_before((hipStream_t)stream);
+    hipLaunchKernelGGL(stream_sum_kernel, dim3(CEIL_SUM_GROUPS), dim3(CEIL_BLOCK), 0,
+                       (hipStream_t)stream, d_src, (uint32_t)n, d_partials_out);
+    timing_after((hipStream_t)stream);
+    return launch_status();
+}

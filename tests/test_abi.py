@@ -88,6 +88,11 @@ def test_argument_errors_are_found_on_the_host():
     assert lib.okt_sparse_reduce_segments(fake, fake, fake, null, 4, 0, 10, fake, fake, 4, fake, null, fake, 1 << 20, null) == INVALID
     assert lib.okt_sparse_reduce_segments(fake, fake, fake, fake, 4, 20, 10, fake, fake, 4, fake, null, fake, 1 << 20, null) == INVALID
     assert lib.okt_sparse_reduce_segments(fake, fake, fake, fake, 4, 0, 1 << 20, fake, fake, 4, fake, null, fake, 64, null) == WORKSPACE
+    assert lib.okt_stream_copy(null, null, 0, null) == 0                                 # n = 0: no-op
+    assert lib.okt_stream_copy(fake, odd, 8, null) == INVALID
+    assert lib.okt_stream_copy(fake, fake, 1 << 32, null) == INVALID
+    assert lib.okt_stream_sum(fake, 8, null, null) == INVALID
+    assert lib.okt_stream_sum(odd, 8, fake, null) == INVALID
     with pytest.raises(TypeError):
         okt.okt_residual_accumulate(None, None, 1.0)
 

@@ -49,6 +49,23 @@ def test_time_next_kernel_brackets_one_launch():
     assert a.elapsed_time(b) == first
 
 
+@pytest.mark.parametrize("n", [0, 1, 3, 1024, 4099, 1 << 20, 4_000_003])
+def test_streaming_ceiling_kernels(n):
+    """The two measurement kernels move what they say: the copy is exact, the
+    partial sums add up to the vector's sum (fp32 partials against an fp64 sum)."""
+    x = lap(7, n)
+    d_x = to_dev(x)
+    d_y = torch.full((n + 8,), 7.0, dtype=torch.float32, device=DEV)
+    okt.okt_stream_copy(d_x, d_y[:n])
+    parts = torch.full((okt.STREAM_SUM_PARTIALS,), 7.0, dtype=torch.float32, device=DEV)
+    okt.okt_stream_sum(d_x, parts)
+    torch.cuda.synchronize()
+    y = d_y.cpu().numpy()
+    assert bits_equal(y[:n], x) and np.all(y[n:] == 7.0)
+    total = float(parts.cpu().numpy().astype(np.float64).sum())
+    assert abs(total - float(x.astype(np.float64).sum())) <= 1e-6 * float(np.abs(x).sum()) + 1e-30
+
+
 def test_accumulate_not_fused_and_subnormals():
     lr = 1.0 + 2.0 ** -12
     g = np.array([1.0 + 2.0 ** -12, 1e-40, -1e-45, 3e-39] * 8, dtype=np.float32)
