@@ -202,7 +202,7 @@ def main():
                 nnz_log.append(int(st.nnz.cpu().numpy().view(np.uint64)[1]))
 
     def summarise(ev, tail=1.0):
-        """name -> (mean, median, count) of the event times in us; `tail` keeps only
+        """name -> (mean, median, count, min) of the event times in us; `tail` keeps only
         the last fraction of each call's samples (the first ones run cold)."""
         per = {}
         for name, a, b in ev:
@@ -210,7 +210,7 @@ def main():
         out = {}
         for name, v in per.items():
             v = v[len(v) - max(1, int(len(v) * tail)):]
-            out[name] = (float(np.mean(v)), float(np.median(v)), len(v))
+            out[name] = (float(np.mean(v)), float(np.median(v)), len(v), float(np.min(v)))
         return out
 
     # ---------------- warmup (instrumented: finds the dominant call) ----------
@@ -274,7 +274,9 @@ def main():
     for c in CALLS:
         if c in table and c in alg_bytes:
             us = table[c][0]
-            kernels[c] = {"us_per_call": round(us, 2), "calls_per_step": calls_per_step[c],
+            kernels[c] = {"us_per_call": round(us, 2), "us_median": round(table[c][1], 2),
+                          "us_min": round(table[c][3], 2), "samples": table[c][2],
+                          "calls_per_step": calls_per_step[c],
                           "algorithmic_bytes": alg_bytes[c],
                           "achieved_GBs": round(alg_bytes[c] / us * 1e-3, 1),
                           "frac_of_hbm_peak": round(alg_bytes[c] / us * 1e-3 / HBM_PEAK_GBS, 4)}
@@ -555,8 +557,15 @@ def cpu_baseline(np, w, grads, contrib, lo, hi, seconds=12.0):
         dt = time.perf_counter() - t0
         if dt >= seconds or steps >= 64:
             break
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as fh:
+            model = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), "")
+    except OSError:
+        pass
     return {"value": steps * ITERS_PER_STEP * w.n / dt, "unit": "elements/s", "cores": 1,
-            "kind": "oracle", "seconds": round(dt, 2),
+            "kind": "oracle", "seconds": round(dt, 2), "host_cpu": model,
+            "host_threads_available": os.cpu_count(),
             "sample": f"{steps} full steps (10 iterations each, n=25,557,032, residual carried) of "
                       "the same workload, numpy oracle, np.partition for the exact threshold"}
 
