@@ -120,3 +120,82 @@ def test_cfg5_full_size():
     idx, val, off = wl.contributions(w, lo, lo + width)
     ref = check_reduce(idx, val, off, lo, lo + width)
     assert ref["hits"].max() > 64               # hot indices collide across most workers
+
+
+@pytest.mark.timeout(600)
+def test_longest_vector_the_interface_allows():
+    """n = 2^32 - 1, the largest length the 32-bit indices address: a vector of
+    zeros with a few thousand planted entries - at both ends, around the
+    boundaries of pieces and tiles, and at random - so that every index the
+    kernels form near 2^32 matters.  Zeros can never be selected (the threshold
+    is positive), so the oracle runs on the planted entries alone, whose order is
+    the order of their positions."""
+    n = (1 << 32) - 1
+    rng = np.random.default_rng(77)
+    special = [0, 1, 2, 3, 4, 255, 256, 257, 1023, 1024, 16383, 16384, 16385,
+               n - 1, n - 2, n - 3, n - 4, n - 5, n - 255, n - 256, n - 257, n - 1024, n - 1025,
+               (1 << 31) - 1, 1 << 31, (1 << 31) + 1]
+    special += [j * 16384 * 16 + d for j in (1, 7, 4095, 16383) for d in (-1, 0, 1)]
+    pos = np.unique(np.concatenate([np.array(special, dtype=np.int64),
+                                    rng.integers(0, n, 3000, dtype=np.int64)]))
+    pos = pos[(pos >= 0) & (pos < n)]
+    m = pos.size
+
+    def planted(seed):
+        r = np.random.default_rng(seed)
+        mag = 1.0 + r.permutation(m).astype(np.float64) / 4096.0       # distinct magnitudes
+        return (mag * r.choice([-1.0, 1.0], m)).astype(np.float32)
+
+    d_pos = torch.from_numpy(pos).to(DEV)
+    gpu = GpuPath(n, 4096)
+    grad = torch.zeros(n, dtype=torch.float32, device=DEV)
+    lr, k = 0.5, 500
+    g_c, e_c = planted(1), (planted(2) * np.float32(0.25)).astype(np.float32)
+    grad[d_pos] = torch.from_numpy(g_c).to(DEV)
+    gpu.residual[d_pos] = torch.from_numpy(e_c).to(DEV)
+
+    # iteration 0: accumulate, exact threshold, select, partition
+    gpu.accumulate(grad, lr)
+    acc_c = orc.residual_accumulate(g_c, e_c, lr)
+    assert np.count_nonzero(acc_c) == m
+    assert bits_equal(gpu.residual[d_pos].cpu().numpy(), acc_c)
+    assert int(torch.count_nonzero(gpu.residual)) == m
+    print("accumulate ok", flush=True)
+    gpu.threshold(k)
+    th, cnt = orc.topk_threshold_exact(acc_c, k)
+    assert gpu.th.cpu().numpy().view(np.uint32)[0] == np.float32(th).view(np.uint32)
+    assert int(u64(gpu.count_ge)[0]) == cnt == k
+    print("threshold ok", flush=True)
+    gpu.select()
+    ridx_c, rval, res_c, total = orc.threshold_select(acc_c, th, capacity=gpu.capacity)
+    idx, val, emitted, gtotal = gpu.selected()
+    assert (emitted, gtotal) == (ridx_c.size, total) == (k, k)
+    assert np.array_equal(idx.astype(np.int64), pos[ridx_c]) and bits_equal(val, rval)
+    assert bits_equal(gpu.residual[d_pos].cpu().numpy(), res_c)
+    assert int(torch.count_nonzero(gpu.residual)) == np.count_nonzero(res_c)
+    print("select ok", flush=True)
+    check_partition(gpu, pos[ridx_c].astype(np.uint32), n, 64)
+
+    # iteration 1: the same threshold, accumulate and select in one pass; then a
+    # threshold below everything planted, which overflows the output
+    g2_c = planted(3)
+    grad[d_pos] = torch.from_numpy(g2_c).to(DEV)
+    okt.okt_accumulate_select(grad, gpu.residual, lr, gpu.th, gpu.idx, gpu.val, gpu.nnz, gpu.ws,
+                              capacity=gpu.capacity)
+    acc_c = orc.residual_accumulate(g2_c, res_c, lr)
+    ridx_c, rval, res_c, total = orc.threshold_select(acc_c, th, capacity=gpu.capacity)
+    idx, val, emitted, gtotal = gpu.selected()
+    assert (emitted, gtotal) == (ridx_c.size, total)
+    assert np.array_equal(idx.astype(np.int64), pos[ridx_c]) and bits_equal(val, rval)
+    assert bits_equal(gpu.residual[d_pos].cpu().numpy(), res_c)
+    assert int(torch.count_nonzero(gpu.residual)) == np.count_nonzero(res_c)
+    print("accumulate+select ok", flush=True)
+    low = np.float32(1e-3)
+    gpu.th.fill_(float(low))
+    okt.okt_threshold_select_copy(gpu.residual, gpu.th, gpu.idx, gpu.val, gpu.nnz, gpu.ws,
+                                  capacity=1000)
+    ridx_c, rval, _, total = orc.threshold_select(res_c, low, capacity=1000)
+    idx, val, emitted, gtotal = gpu.selected()
+    assert (emitted, gtotal) == (1000, total) and total > 1000
+    assert np.array_equal(idx.astype(np.int64), pos[ridx_c]) and bits_equal(val, rval)
+    assert bits_equal(gpu.residual[d_pos].cpu().numpy(), res_c)          # left untouched

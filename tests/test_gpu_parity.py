@@ -297,6 +297,48 @@ def layered(n, seed=5):
 
 
 @pytest.mark.timeout(300)
+def test_two_streams_each_with_its_own_workspace():
+    """Calls enqueued on two streams, each with its own workspace and outputs, run
+    side by side without a synchronisation between them: the library keeps no
+    state of its own between calls, so neither disturbs the other."""
+    n, lr, rounds = 3_000_017, 0.75, 4
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    lanes = []
+    for j, st in enumerate(streams):
+        g = [lap(100 + 10 * j + r, n) for r in range(rounds)]
+        th = np.float32(4e-3 + 1e-3 * j)
+        lanes.append({
+            "g": g, "th": th, "d_g": [to_dev(x) for x in g],
+            "res": torch.zeros(n, dtype=torch.float32, device=DEV),
+            "d_th": to_dev(np.array([th], dtype=np.float32)),
+            "idx": [torch.full((n // 8,), -1, dtype=torch.int32, device=DEV) for _ in range(rounds)],
+            "val": [torch.zeros(n // 8, dtype=torch.float32, device=DEV) for _ in range(rounds)],
+            "nnz": [torch.zeros(2, dtype=torch.int64, device=DEV) for _ in range(rounds)],
+            "ws": workspace(okt.okt_workspace_bytes(n, 0))})
+    torch.cuda.synchronize()
+    for r in range(rounds):
+        for j, st in enumerate(streams):
+            L = lanes[j]
+            if (r + j) % 2:         # one stream takes the fused call while the other takes two
+                okt.okt_accumulate_select(L["d_g"][r], L["res"], lr, L["d_th"], L["idx"][r],
+                                          L["val"][r], L["nnz"][r], L["ws"], stream=st)
+            else:
+                okt.okt_residual_accumulate(L["d_g"][r], L["res"], lr, stream=st)
+                okt.okt_threshold_select(L["res"], L["d_th"], L["idx"][r], L["val"][r],
+                                         L["nnz"][r], L["ws"], stream=st)
+    torch.cuda.synchronize()
+    for j, L in enumerate(lanes):
+        res = np.zeros(n, dtype=np.float32)
+        for r in range(rounds):
+            acc = orc.residual_accumulate(L["g"][r], res, lr)
+            ridx, rval, res, total = orc.threshold_select(acc, L["th"], capacity=n // 8)
+            c = u64(L["nnz"][r])
+            assert (int(c[0]), int(c[1])) == (ridx.size, total), (j, r)
+            assert np.array_equal(u32(L["idx"][r][:total]), ridx), (j, r)
+            assert bits_equal(L["val"][r][:total].cpu().numpy(), rval), (j, r)
+        assert bits_equal(L["res"].cpu().numpy(), res), j
+
+
 def test_select_where_pieces_overflow_their_stash():
     # long enough that a wave's piece (about n / 4096) holds more selected entries
     # than its stash where the selection is dense
@@ -400,6 +442,8 @@ REDUCE_CASES = [
     ("cfg3", 3_437_500, 3_437_500 + 120_007, 1_200, 32),
     ("cfg4", 100, 100 + 400_003, 400, 64),
     ("cfg5", 55_000_064, 55_000_064 + 30_001, 300, 256),
+    # the top of the 32-bit index space: hi = 2^32 - 1, overlapping draws
+    ("cfg3", (1 << 32) - 1 - 300_001, (1 << 32) - 1, 2_000, 8),
 ]
 
 
