@@ -297,6 +297,61 @@ def layered(n, seed=5):
 
 
 @pytest.mark.timeout(300)
+def test_calls_captured_in_a_hip_graph_replay_like_eager():
+    """The entry points enqueue kernels only (the scan state is cleared by a small
+    kernel, not a memset), so a sequence of them can be captured once and
+    replayed.  Every replay - with eager work and synchronisations in between - is
+    checked against the oracle, which follows the carried residual."""
+    n, lr, R, rounds = 1_000_003, 0.5, 8, 4
+    th = np.float32(3e-3)
+    grads = [lap(300 + r, n) for r in range(rounds)]
+    d_g = to_dev(grads[0])
+    res = torch.zeros(n, dtype=torch.float32, device=DEV)
+    d_th = to_dev(np.array([th], dtype=np.float32))
+    cap = n // 4
+    idx = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
+    val = torch.zeros(cap, dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    b = torch.zeros(R + 1, dtype=torch.int32, device=DEV)
+    off = torch.zeros(R + 1, dtype=torch.int64, device=DEV)
+    lo, hi = 100_000, 400_000
+    cidx, cval, coff = wl.contributions(wl.WORKLOADS["cfg3"], lo, hi, m=3_000, P=8)
+    d_ci, d_cv, d_co = to_dev(cidx), to_dev(cval), to_dev(coff)
+    out_idx = torch.full((cidx.size,), -1, dtype=torch.int32, device=DEV)
+    out_val = torch.zeros(cidx.size, dtype=torch.float32, device=DEV)
+    out_nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    ws = workspace(okt.okt_workspace_bytes(n, 8))
+    ws2 = workspace(okt.okt_workspace_bytes(hi - lo, 8))
+    okt.load_library()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        okt.okt_accumulate_select(d_g, res, lr, d_th, idx, val, nnz, ws, capacity=cap)
+        okt.okt_region_partition(idx, nnz, n, R, b, off)
+        okt.okt_sparse_reduce(d_ci, d_cv, d_co, lo, hi, out_idx, out_val, out_nnz, ws2)
+    res.zero_()                                    # capture does not run anything; start clean anyway
+    ref_red = orc.sparse_reduce(cidx, cval, coff, lo, hi)
+    host_res = np.zeros(n, dtype=np.float32)
+    for r in range(rounds):
+        d_g.copy_(torch.from_numpy(grads[r]))      # eager work between the replays
+        out_val.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        acc = orc.residual_accumulate(grads[r], host_res, lr)
+        ridx, rval, host_res, total = orc.threshold_select(acc, th, capacity=cap)
+        c = u64(nnz)
+        assert (int(c[0]), int(c[1])) == (ridx.size, total), r
+        assert np.array_equal(u32(idx[:total]), ridx) and bits_equal(val[:total].cpu().numpy(), rval), r
+        assert bits_equal(res.cpu().numpy(), host_res), r
+        rb, roff = orc.region_partition(ridx, n, R)
+        assert np.array_equal(u32(b), rb) and np.array_equal(u64(off), roff), r
+        U = ref_red["idx"].size
+        assert int(u64(out_nnz)[1]) == U and np.array_equal(u32(out_idx[:U]), ref_red["idx"]), r
+        err = np.abs(out_val[:U].cpu().numpy().astype(np.float64) - ref_red["val"].astype(np.float64))
+        assert np.all(err <= reduce_tolerance(ref_red)), r
+
+
 def test_two_streams_each_with_its_own_workspace():
     """Calls enqueued on two streams, each with its own workspace and outputs, run
     side by side without a synchronisation between them: the library keeps no
