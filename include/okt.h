@@ -64,8 +64,8 @@ const char* okt_last_hip_error(void);
  * reduce family, the collect pass of okt_topk_threshold_exact (not recorded when
  * that call takes its unsampled path), the intersect kernel.  The pair is used
  * once and forgotten; a call that launches no such kernel (an argument error, an
- * empty input) leaves it armed for the next one.  For benchmarks: so that an event time can be compared with
- * a profiler's kernel duration.
+ * empty input) leaves it armed for the next one.  For benchmarks: so that an
+ * event time can be compared with a profiler's kernel duration.
  */
 void okt_time_next_kernel(void* start_event, void* stop_event);
 
