@@ -27,6 +27,13 @@
  *     on the host before anything is launched; then no output is touched.
  *     OKT_ERR_HIP means the HIP runtime refused a launch; okt_last_hip_error
  *     gives its reason.
+ *   - The kernels that place their output through a scan across workgroups
+ *     (the select family, the reduce family, the index intersection) wait for
+ *     one another through device memory.  Every such wait ends by construction
+ *     and is bounded all the same; should one run out, the kernel still exits
+ *     normally, every count the call writes (d_nnz_out, d_count_out) is set to
+ *     UINT64_MAX and the other outputs are unspecified (all stores stay inside
+ *     the buffers).
  */
 #ifndef OKT_H
 #define OKT_H
@@ -53,6 +60,14 @@ const char* okt_status_string(int status);
  * OKT_ERR_HIP ("no error" if there was none); never NULL; static storage.
  */
 const char* okt_last_hip_error(void);
+
+/*
+ * Test hook: the number of polls a wait between workgroups may take before it
+ * gives up, for every call made after this one, process-wide (0 = the built-in
+ * limit, about 2^24).  With a limit of 1 a call either completes as usual or
+ * reports UINT64_MAX counts as described above; it never hangs or faults.
+ */
+void okt_debug_spin_limit(uint32_t polls);
 
 /*
  * Measurement hook.  The next call this thread makes records `start_event` right

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     okt_accumulate_select,
     okt_balance_plan,
     okt_coo_threshold_select,
+    okt_debug_spin_limit,
     okt_index_intersect_restore,
     okt_index_intersect_zero,
     okt_last_hip_error,

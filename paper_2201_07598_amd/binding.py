@@ -21,6 +21,7 @@ SIGNATURES = {
     "okt_status_string": (ctypes.c_char_p, [c_int]),
     "okt_last_hip_error": (ctypes.c_char_p, []),
     "okt_time_next_kernel": (None, [c_vp, c_vp]),
+    "okt_debug_spin_limit": (None, [c_u32]),
     "okt_version": (c_int, []),
     "okt_stream_copy": (c_int, [c_vp, c_vp, c_u64, c_vp]),
     "okt_stream_sum": (c_int, [c_vp, c_u64, c_vp, c_vp]),
@@ -96,6 +97,11 @@ def okt_time_next_kernel(start_event, stop_event) -> None:
     load_library().okt_time_next_kernel(
         ctypes.c_void_p(start_event.cuda_event if start_event is not None else None),
         ctypes.c_void_p(stop_event.cuda_event if stop_event is not None else None))
+
+
+def okt_debug_spin_limit(polls: int) -> None:
+    """Test hook: polls a wait between workgroups may take (0 = built-in limit)."""
+    load_library().okt_debug_spin_limit(int(polls))
 
 
 def okt_version() -> int:

@@ -2,6 +2,8 @@
 #include "okt_device.h"
 #include "okt_sizes.h"
 
+#include <atomic>
+
 namespace okt {
 
 static thread_local hipError_t g_last_hip_error = hipSuccess;
@@ -27,18 +29,21 @@ void timing_after(hipStream_t stream) {
     g_time_stop = nullptr;
 }
 
-__global__ void zero_words_kernel(uint64_t* p, uint64_t words) {
+static std::atomic<uint32_t> g_spin_limit{0};
+uint32_t spin_limit_setting() { return g_spin_limit.load(std::memory_order_relaxed); }
+
+__global__ void clear_scan_state_kernel(uint64_t* p, uint64_t words, uint32_t spin_limit) {
     uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (; i < words; i += stride) p[i] = 0;
+    for (; i < words; i += stride) p[i] = i == SCAN_SPIN_WORD ? (uint64_t)spin_limit : 0ull;
 }
 
-hipError_t launch_zero_words(void* p, uint64_t words, hipStream_t stream) {
+hipError_t launch_clear_scan_state(void* p, uint64_t words, hipStream_t stream) {
     if (words == 0) return hipSuccess;
     uint64_t blocks = (words + 255) / 256;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       (uint64_t*)p, words);
+    hipLaunchKernelGGL(clear_scan_state_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       (uint64_t*)p, words, spin_limit_setting());
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) launch_failed(e);
     return e;
@@ -49,6 +54,10 @@ hipError_t launch_zero_words(void* p, uint64_t words, hipStream_t stream) {
 extern "C" {
 
 const char* okt_last_hip_error(void) { return hipGetErrorString(okt::g_last_hip_error); }
+
+void okt_debug_spin_limit(uint32_t polls) {
+    okt::g_spin_limit.store(polls, std::memory_order_relaxed);
+}
 
 void okt_time_next_kernel(void* start_event, void* stop_event) {
     okt::g_time_start = (hipEvent_t)start_event;

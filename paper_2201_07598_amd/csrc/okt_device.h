@@ -67,8 +67,10 @@ constexpr uint32_t SPIN_LIMIT = 1u << 24;         // polls before a wait gives u
 struct ScanHeader {           // first 64 bytes of the workspace
     uint32_t ticket;
     uint32_t error;           // nonzero: a bounded wait ran out
-    uint32_t pad[14];
+    uint32_t spin_limit;      // polls a wait may take; 0 = SPIN_LIMIT (set when the state is cleared)
+    uint32_t pad[13];
 };
+constexpr int SCAN_SPIN_WORD = 1;     // the 64-bit word of the header whose low half is spin_limit
 
 __device__ __forceinline__ uint64_t desc_load(const uint64_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -79,9 +81,13 @@ __device__ __forceinline__ void desc_store(uint64_t* p, uint64_t v) {
 // Poll until the descriptor is valid (status != 0).
 __device__ __forceinline__ uint64_t desc_wait(const uint64_t* p, ScanHeader* hdr) {
     uint64_t d = desc_load(p);
-    uint32_t polls = 0;
+    uint32_t polls = 0, limit = 0;
     while ((d >> 62) == 0) {
-        if (++polls > SPIN_LIMIT) {
+        if (limit == 0) {               // only a wait that has to poll reads the setting
+            limit = __hip_atomic_load(&hdr->spin_limit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (limit == 0) limit = SPIN_LIMIT;
+        }
+        if (++polls > limit) {
             __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return DESC_INCLUSIVE;      // give up: count 0, stops the walk
         }
@@ -154,11 +160,16 @@ inline size_t scan_ws_bytes(uint64_t tiles) {
     return SCAN_HEADER_BYTES + 8 * (size_t)(tiles + scan_groups(tiles));
 }
 
-// Zero `words` 64-bit words (a fill kernel rather than a memset node, so that a
+// Clear the `words` 64-bit words of a scan state (header and descriptors) and set
+// the header's spin limit (a fill kernel rather than a memset node, so that a
 // caller may capture the calls into a HIP graph).
-__global__ void zero_words_kernel(uint64_t* p, uint64_t words);
+__global__ void clear_scan_state_kernel(uint64_t* p, uint64_t words, uint32_t spin_limit);
 
-hipError_t launch_zero_words(void* p, uint64_t words, hipStream_t stream);
+hipError_t launch_clear_scan_state(void* p, uint64_t words, hipStream_t stream);
+
+// Polls a bounded wait may take before it gives up, as set by
+// okt_debug_spin_limit (0 = SPIN_LIMIT).
+uint32_t spin_limit_setting();
 
 // Status of the launches an entry point has just made: OKT_OK, or OKT_ERR_HIP
 // with the runtime's error kept for okt_last_hip_error.

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(
     const uint64_t* __restrict__ seg_end, uint32_t seg_stride,
     const uint32_t* __restrict__ lo_hi, uint32_t lo0, uint32_t hi0, uint32_t P,
     uint32_t max_width, uint32_t slots, char* ws, uint32_t ws_region_bytes,
-    uint32_t table_offset) {
+    uint32_t table_offset, uint32_t spin_limit) {
     const uint32_t region = blockIdx.y;
     const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
     uint32_t* table = (uint32_t*)(ws + (size_t)region * ws_region_bytes + table_offset);
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(
     uint64_t* scan_state = (uint64_t*)(ws + (size_t)region * ws_region_bytes);
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < table_offset / 8;
          i += gridDim.x * blockDim.x)
-        scan_state[i] = 0;
+        scan_state[i] = i == SCAN_SPIN_WORD ? (uint64_t)spin_limit : 0ull;
     const uint64_t* begin = seg_begin + (size_t)region * seg_stride;
     const uint64_t* end = seg_end + (size_t)region * seg_stride;
     const uint64_t cells = (uint64_t)(r.ntiles + 1) * P;
@@ -97,14 +97,14 @@ __global__ __launch_bounds__(256) void reduce_slices_wave_kernel(
     const uint64_t* __restrict__ seg_end, uint32_t seg_stride,
     const uint32_t* __restrict__ lo_hi, uint32_t lo0, uint32_t hi0, uint32_t P,
     uint32_t max_width, uint32_t slots, char* ws, uint32_t ws_region_bytes,
-    uint32_t table_offset) {
+    uint32_t table_offset, uint32_t spin_limit) {
     const uint32_t region = blockIdx.y;
     const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
     uint32_t* table = (uint32_t*)(ws + (size_t)region * ws_region_bytes + table_offset);
     uint64_t* scan_state = (uint64_t*)(ws + (size_t)region * ws_region_bytes);
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < table_offset / 8;
          i += gridDim.x * blockDim.x)
-        scan_state[i] = 0;
+        scan_state[i] = i == SCAN_SPIN_WORD ? (uint64_t)spin_limit : 0ull;
     const uint64_t* begin = seg_begin + (size_t)region * seg_stride;
     const uint64_t* end = seg_end + (size_t)region * seg_stride;
     const uint64_t cells = (uint64_t)(r.ntiles + 1) * P;
@@ -424,11 +424,12 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
         hipLaunchKernelGGL(reduce_slices_wave_kernel, dim3((unsigned)((cells + 3) / 4), B),
                            dim3(256), 0, s, d_idx_cat, d_seg_begin, d_seg_end, seg_stride, d_lo_hi,
                            lo, hi, P, max_width, slots, (char*)d_ws, (uint32_t)region_bytes,
-                           table_offset);
+                           table_offset, spin_limit_setting());
     } else {
         hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)sblocks, B), dim3(256), 0, s,
                            d_idx_cat, d_seg_begin, d_seg_end, seg_stride, d_lo_hi, lo, hi, P,
-                           max_width, slots, (char*)d_ws, (uint32_t)region_bytes, table_offset);
+                           max_width, slots, (char*)d_ws, (uint32_t)region_bytes, table_offset,
+                           spin_limit_setting());
     }
     timing_before(s);
     hipLaunchKernelGGL(reduce_tile_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,

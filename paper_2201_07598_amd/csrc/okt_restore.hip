@@ -224,7 +224,7 @@ static int launch_intersect(float* d_vec, uint64_t n, const uint32_t* d_local_id
     ScanHeader* hdr = (ScanHeader*)d_ws;
     uint64_t* tile_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
     uint64_t* group_desc = tile_desc + ntiles;
-    if (launch_zero_words(d_ws, scan_ws_bytes(ntiles) / 8, s) != hipSuccess) return OKT_ERR_HIP;
+    if (launch_clear_scan_state(d_ws, scan_ws_bytes(ntiles) / 8, s) != hipSuccess) return OKT_ERR_HIP;
     timing_before(s);
     hipLaunchKernelGGL(intersect_kernel<ZERO_MEMBERS>, dim3(ntiles), dim3(RST_BLOCK), 0, s, d_vec,
                        (uint32_t)n, d_local_idx, d_local_val, d_local_nnz, (uint32_t)max_local,

@@ -46,7 +46,7 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
     ScanHeader* hdr = (ScanHeader*)d_ws;
     uint64_t* seg_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
     uint64_t* group_desc = seg_desc + shape.nseg;
-    if (launch_zero_words(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
+    if (launch_clear_scan_state(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
     timing_before(s);
     hipLaunchKernelGGL((select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET, Source>),
@@ -101,7 +101,7 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
     ScanHeader* hdr = (ScanHeader*)d_ws;
     uint64_t* seg_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
     uint64_t* group_desc = seg_desc + shape.nseg;
-    if (launch_zero_words(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
+    if (launch_clear_scan_state(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
     timing_before(s);
     hipLaunchKernelGGL((accumulate_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET>),
@@ -137,7 +137,7 @@ extern "C" int okt_coo_threshold_select(const uint32_t* d_idx_in, const float* d
     ScanHeader* hdr = (ScanHeader*)d_ws;
     uint64_t* seg_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
     uint64_t* group_desc = seg_desc + shape.nseg;
-    if (launch_zero_words(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
+    if (launch_clear_scan_state(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
     timing_before(s);
     hipLaunchKernelGGL((coo_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET>),

@@ -82,7 +82,8 @@ def gpu_reduce(idx_cat, val_cat, chunk_off, lo, hi, capacity=None, dense=True):
     torch.cuda.synchronize()
     c = u64(nnz)
     e = int(c[0])
-    return {"idx": u32(out_idx[:e]), "val": out_val[:e].cpu().numpy(),
+    w = min(e, cap)               # e is UINT64_MAX when the call reports a failed wait
+    return {"idx": u32(out_idx[:w]), "val": out_val[:w].cpu().numpy(),
             "emitted": e, "total": int(c[1]),
             "dense": d_dense[:hi - lo].cpu().numpy() if dense else None}
 

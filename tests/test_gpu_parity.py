@@ -179,7 +179,8 @@ def gpu_select(acc, th, capacity):
     okt.okt_threshold_select(d, d_th, idx, val, nnz, ws, capacity=capacity)
     c = u64(nnz)
     e = int(c[0])
-    return u32(idx[:e]), val[:e].cpu().numpy(), d.cpu().numpy(), e, int(c[1])
+    w = min(e, capacity)          # e is UINT64_MAX when a call reports a failed wait
+    return u32(idx[:w]), val[:w].cpu().numpy(), d.cpu().numpy(), e, int(c[1])
 
 
 def check_select(acc, th, capacity):
@@ -350,6 +351,48 @@ def test_calls_captured_in_a_hip_graph_replay_like_eager():
         assert int(u64(out_nnz)[1]) == U and np.array_equal(u32(out_idx[:U]), ref_red["idx"]), r
         err = np.abs(out_val[:U].cpu().numpy().astype(np.float64) - ref_red["val"].astype(np.float64))
         assert np.all(err <= reduce_tolerance(ref_red)), r
+
+
+def test_a_wait_that_gives_up_is_reported():
+    """Failure handling of the scan across workgroups, forced from the host: with
+    the test hook's limit of one poll, a workgroup that finds a predecessor's
+    count not yet published gives up at once.  Every kernel still runs to its
+    end; a call either completes as usual or reports UINT64_MAX counts - never a
+    wrong result with valid counts - and the next call with the built-in limit
+    is right again."""
+    n = 30_000_011
+    acc = lap(500, n)
+    th = np.float32(5e-3)
+    ridx, rval, rres, total = orc.threshold_select(acc, th, capacity=n // 8)
+    lo, hi = 0, 2_000_000
+    cidx, cval, coff = wl.contributions(wl.WORKLOADS["cfg2"], lo, hi, m=20_000, P=16)
+    ref = orc.sparse_reduce(cidx, cval, coff, lo, hi)
+    bad = np.uint64(0xFFFFFFFFFFFFFFFF)
+    outcomes = []
+    try:
+        okt.okt_debug_spin_limit(1)
+        for rep in range(3):
+            idx, val, res, e, t = gpu_select(acc, th, n // 8)
+            if t == int(bad):
+                outcomes.append("select gave up")
+                assert e == int(bad)
+            else:
+                outcomes.append("select completed")
+                assert (e, t) == (ridx.size, total) and np.array_equal(idx, ridx)
+                assert bits_equal(val, rval) and bits_equal(res, rres)
+            got = gpu_reduce(cidx, cval, coff, lo, hi, dense=False)
+            if got["total"] == int(bad):
+                outcomes.append("reduce gave up")
+            else:
+                outcomes.append("reduce completed")
+                assert got["total"] == ref["idx"].size and np.array_equal(got["idx"], ref["idx"])
+    finally:
+        okt.okt_debug_spin_limit(0)
+    print(outcomes, flush=True)
+    idx, val, res, e, t = gpu_select(acc, th, n // 8)
+    assert (e, t) == (ridx.size, total) and np.array_equal(idx, ridx) and bits_equal(res, rres)
+    got = gpu_reduce(cidx, cval, coff, lo, hi, dense=False)
+    assert got["total"] == ref["idx"].size and np.array_equal(got["idx"], ref["idx"])
 
 
 def test_two_streams_each_with_its_own_workspace():
