@@ -129,7 +129,6 @@ def region_partition(idx: np.ndarray, n: int, R: int):
             b[r] = int(idx[(r * nnz) // R])
         else:
             b[r] = (r * n) // R
-        b[r] = max(b[r], b[r - 1])
     off = np.zeros(R + 1, dtype=np.uint64)
     idx64 = idx.astype(np.uint64)
     for r in range(R):

@@ -241,6 +241,22 @@ def test_partition_counts_balanced():
             assert inside == [int(i) for i in idx[int(off[r]):int(off[r + 1])]]
 
 
+def test_partition_worked_by_hand():
+    # the reading written out on lists short enough to do by hand: boundary r is
+    # the entry at list position floor(r * nnz / R); region r takes the entries
+    # from there up to the next boundary
+    idx = np.array([10, 20, 30, 40, 50], dtype=np.uint32)             # nnz = 5
+    b, off = orc.region_partition(idx, 100, 2)                         # floor(5/2) = 2 -> idx[2]
+    assert b.tolist() == [0, 30, 100] and off.tolist() == [0, 2, 5]
+    b, off = orc.region_partition(idx, 100, 3)                         # floor(5/3) = 1, floor(10/3) = 3
+    assert b.tolist() == [0, 20, 40, 100] and off.tolist() == [0, 1, 3, 5]
+    b, off = orc.region_partition(idx, 100, 4)                         # positions 1, 2, 3
+    assert b.tolist() == [0, 20, 30, 40, 100] and off.tolist() == [0, 1, 2, 3, 5]
+    idx = np.array([7, 8], dtype=np.uint32)                            # fewer entries than regions
+    b, off = orc.region_partition(idx, 64, 4)                          # positions 0, 1, 1
+    assert b.tolist() == [0, 7, 8, 8, 64] and off.tolist() == [0, 0, 1, 1, 2]
+
+
 def test_partition_extreme_case_from_the_paper():
     gold = read_golden("split_extreme.txt")
     P, k, n = 8, 4000, 1 << 20
@@ -559,6 +575,26 @@ def test_balance_plan_moves_every_entry_once_and_keeps_the_order():
             # balanced: floor or ceil of T / P each
             assert all(len(b) in (T // P, -(-T // P)) for b in new)
             assert len(chunks) <= 2 * P - 1
+
+
+def test_balance_plan_worked_by_hand():
+    # T = 11 entries, all on worker 0 of P = 5 (11 > 4 x 2.2): balanced, worker j
+    # holds list positions [floor(11 j / 5), floor(11 (j+1) / 5)) = [0,2) [2,4) [4,6) [6,8) [8,11)
+    triggered, chunks = orc.balance_plan([11, 0, 0, 0, 0])
+    assert triggered
+    assert chunks == [(0, 0, 0, 0, 2), (0, 1, 2, 0, 2), (0, 2, 4, 0, 2), (0, 3, 6, 0, 2),
+                      (0, 4, 8, 0, 3)]
+    # T = 13 over P = 6, [1, 0, 12, 0, 0, 0] (12 > 4 x 13/6): the list is the one
+    # entry of worker 0, then the twelve of worker 2; targets [0,2) [2,4) [4,6) [6,8) [8,10) [10,13)
+    triggered, chunks = orc.balance_plan([1, 0, 12, 0, 0, 0])
+    assert triggered
+    assert chunks == [(0, 0, 0, 0, 1),          # list position 0 stays
+                      (2, 0, 0, 1, 1),          # position 1: first of worker 2 -> second slot of worker 0
+                      (2, 1, 1, 0, 2),          # positions 2-3
+                      (2, 2, 3, 0, 2),          # positions 4-5: stay on worker 2
+                      (2, 3, 5, 0, 2),          # positions 6-7
+                      (2, 4, 7, 0, 2),          # positions 8-9
+                      (2, 5, 9, 0, 3)]          # positions 10-12
 
 
 def test_balance_plan_extreme_case_and_trigger_rule():
