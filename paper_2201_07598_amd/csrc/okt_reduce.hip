@@ -9,9 +9,9 @@
 //     of a call run side by side, so their latency is paid once.
 //  2. reduce_tile_kernel: a workgroup owns one tile.  Its slice of every
 //     contribution is known from the table, so all its entries are addressed up
-//     front: the slices are flattened into one list and every thread takes each
-//     256th entry, whatever the slice lengths.  Entries are summed with LDS fp64
-//     atomic adds.  Where the region is densely hit the accumulator of a slot is
+//     front: the slices go round-robin to the waves, a wave reads a slice 64
+//     consecutive entries at a time and keeps several such blocks, across its
+//     slices, in flight.  Entries are summed with LDS fp64 atomic adds.  Where the region is densely hit the accumulator of a slot is
 //     the slot itself.  Where it is sparsely hit the tile is wider than the
 //     accumulator array: a first sweep marks the hit slots in a bitmap, the
 //     popcount prefix of the bitmap ranks them, and the second sweep sums into
