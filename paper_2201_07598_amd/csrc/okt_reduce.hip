@@ -234,6 +234,12 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
         constexpr bool VALUES = decltype(with_values)::value;
         for (uint32_t p0 = 0; p0 < P; p0 += RED_CHUNKS) {
             const uint32_t np = (P - p0) < (uint32_t)RED_CHUNKS ? (P - p0) : (uint32_t)RED_CHUNKS;
+            // Every thread must take the same branch here.  The note of what is
+            // loaded is therefore written between the two barriers: each thread has
+            // read it (before the first) when it changes, and sees the new value
+            // (after the second) when it next looks.  Written after the second
+            // barrier instead, a wave that ran ahead could still read the value an
+            // earlier sweep left for this very chunk and skip the reload alone.
             if (p0 != s_loaded_p0) {            // slice table of this sweep not in LDS yet
                 __syncthreads();
                 for (uint32_t q = tid; q < np; q += RED_BLOCK) {
@@ -241,8 +247,8 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
                     s_start[q] = off[p0 + q] + b;
                     s_len[q] = e > b ? e - b : 0u;      // e < b only for unsorted input
                 }
-                __syncthreads();
                 if (tid == 0) s_loaded_p0 = p0;
+                __syncthreads();
             }
             uint32_t q = (uint32_t)__builtin_amdgcn_readfirstlane(wave), o = 0;   // next block: slice q, entries o .. o+63
             while (q < np) {

@@ -612,6 +612,36 @@ def test_reduce_tile_modes():
     assert got["total"] == cl.size
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_reduce_more_contributions_than_one_sweep_over_ranked_tiles(seed):
+    """300 contributions (more than the 256 a sweep takes at a time) over a
+    region wide enough for ranked tiles, most slices of a tile empty: every
+    pass over the entries reloads the slice table twice, and a wave with nothing
+    to do in the first part runs far ahead of the others."""
+    rng = np.random.default_rng(1000 + seed)
+    width, P = 700_000, 300
+    lo = int(rng.integers(0, (1 << 32) - 1 - width))
+    parts = []
+    for p in range(P):
+        m = int(rng.integers(0, 4001))
+        mode = p % 3
+        if m == 0:
+            loc = np.zeros(0, np.int64)
+        elif mode == 0:
+            loc = np.sort(rng.choice(width, m, replace=False))
+        elif mode == 1:                                   # clustered: empty slices elsewhere
+            a = int(rng.integers(0, width - 2 * m))
+            loc = np.sort(rng.choice(2 * m, m, replace=False)) + a
+        else:                                             # shared support: collisions
+            loc = np.sort(np.random.default_rng(7).choice(width, m, replace=False))
+        parts.append((loc + lo).astype(np.uint32))
+    cat_i = np.concatenate(parts)
+    cat_v = lap(600 + seed, cat_i.size)
+    off = np.concatenate([[0], np.cumsum([x.size for x in parts])]).astype(np.uint64)
+    got, ref = check_reduce(cat_i, cat_v, off, lo, lo + width)
+    assert ref["hits"].max() > 8 and got["total"] > 300_000
+
+
 def test_reduce_paper_shaped_regions():
     """The shapes of the paper's runs (16 .. 64 contributions hitting 6 .. 30 % of a
     region) and what can go wrong around them, steered by the density estimate
