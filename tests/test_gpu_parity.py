@@ -201,6 +201,29 @@ def test_select_matches_oracle(n):
     assert check_select(acc, th, 4 * k) == cnt
 
 
+@pytest.mark.parametrize("n", [70_001, 5_000_003])
+def test_threshold_and_select_with_nan_and_inf_elements(n):
+    """Not a case the method meets (gradients are finite), but the order of the
+    magnitude keys is defined for every bit pattern - Inf above finite, NaN above
+    Inf - and both sides must follow it: NaNs of either sign and any payload are
+    the largest elements, copied bit for bit; the k-th largest may itself be an
+    Inf or a NaN (then the select compares keys, not floats).  n covers the
+    three-pass and the sample-then-count path of the threshold."""
+    rng = np.random.default_rng(n)
+    acc = lap(n + 1, n)
+    bits = acc.view(np.uint32)
+    where = rng.choice(n, 160, replace=False)
+    bits[where[:100]] = (np.uint32(0x7F800001) + rng.integers(0, 0x7FFFFE, 100).astype(np.uint32)) \
+        | (rng.integers(0, 2, 100).astype(np.uint32) << np.uint32(31))          # NaNs
+    bits[where[100:]] = np.where(rng.integers(0, 2, 60) == 1, 0xFF800000, 0x7F800000).astype(np.uint32)  # +-Inf
+    assert np.isnan(acc).sum() == 100 and np.isinf(acc).sum() == 60
+    for k in (1, 37, 100, 101, 160, 161, 5000):
+        th, cnt = gpu_threshold(acc, k)
+        rth, rcnt = orc.topk_threshold_exact(acc, k, method="partition")
+        assert np.float32(th).view(np.uint32) == np.float32(rth).view(np.uint32) and cnt == rcnt, k
+        assert check_select(acc, rth, cnt + 3) == cnt
+
+
 def test_select_degenerate_thresholds():
     acc = lap(99, 50_001)
     assert check_select(acc, np.float32(np.inf), 16) == 0
