@@ -237,3 +237,44 @@ def test_random_shapes_of_the_reduce_family(seed):
                                          max_local=li.size, max_global=gli.size)
             assert int(u64(count)[0]) == want.size, f"{where} intersect zero"
             assert bits_equal(d_vec.cpu().numpy(), eps), f"{where} intersect zero"
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_random_vectors_through_the_sampled_threshold(seed):
+    """Vectors long enough for the sample-then-count path of the exact threshold,
+    of kinds on which a sample says much, little or the wrong thing, at ranks
+    from 1 to n and with workspaces from the smallest to the full one."""
+    rng = np.random.default_rng(9200 + seed)
+    for case in range(5):
+        n = int(rng.integers(4_194_304 - 5, 16_000_000))
+        kind = int(rng.integers(0, 7))
+        x = rng.standard_normal(n, dtype=np.float32) * np.float32(1e-3)
+        if kind == 1:                                # layers of different scale
+            cuts = np.sort(rng.integers(0, n, 8))
+            for a, b in zip(cuts[:-1], cuts[1:]):
+                x[a:b] *= np.float32(10.0 ** rng.integers(-4, 4))
+        if kind == 2:                                # the large values sit in a few short blocks
+            x *= np.float32(1e-3)
+            for _ in range(int(rng.integers(1, 6))):
+                a = int(rng.integers(0, n))
+                b = min(n, a + int(rng.integers(1, 3000)))
+                x[a:b] = rng.standard_normal(b - a).astype(np.float32)
+        if kind == 3:                                # five distinct values
+            x = rng.choice(np.array([0.0, 1e-3, -1e-3, 2e-3, 5e-4], dtype=np.float32), n)
+        if kind == 4:                                # nearly all zero
+            x[rng.random(n) < 0.999] = 0.0
+        if kind == 5:                                # all equal
+            x[:] = np.float32(rng.choice([0.0, 1.5, -2.0, 1e-40]))
+        if kind == 6:                                # one exponent: the first digit says little
+            x = np.abs(x) + np.float32(1.0)
+        d = to_dev(x)
+        full = workspace(okt.okt_workspace_bytes(n, 0))
+        for k in (1, n, int(rng.integers(1, n + 1)), max(1, n // 1000), max(1, n // 100), max(1, n // 7)):
+            ws = full if rng.random() < 0.6 else workspace(int(rng.choice([70_000, 300_000, 4_000_000])))
+            th = torch.zeros(1, device=DEV)
+            cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+            okt.okt_topk_threshold_exact(d, k, th, cnt, ws)
+            rth, rcnt = orc.topk_threshold_exact(x, k, method="partition")
+            where = f"seed {seed} case {case}: n={n} kind={kind} k={k} ws={ws.numel()}"
+            assert th.cpu().numpy().view(np.uint32)[0] == np.float32(rth).view(np.uint32), where
+            assert int(u64(cnt)[0]) == rcnt, where
