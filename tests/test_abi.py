@@ -97,6 +97,29 @@ def test_argument_errors_are_found_on_the_host():
         okt.okt_residual_accumulate(None, None, 1.0)
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/okt.h is a C header: it compiles as C99 and as C++ without a warning,
+    and a C program can name every declared function."""
+    import shutil
+    import subprocess
+    names = declared_functions()
+    src = tmp_path / "use_okt.c"
+    body = "\n".join(f"    p[{i}] = (fn)&{name};" for i, name in enumerate(names))
+    src.write_text('#include "okt.h"\ntypedef void (*fn)(void);\nint main(void) {\n'
+                   f'    fn p[{len(names)}];\n{body}\n'
+                   '    okt_chunk c = {0, 0, 0, 0, 0};\n'
+                   f'    return p[{len(names) - 1}] == 0 || c.count != 0 || OKT_ERR_HIP == 0;\n'
+                   '}\n')
+    inc = os.path.join(ROOT, "include")
+    for compiler, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        if shutil.which(compiler) is None:
+            pytest.skip(f"{compiler} not installed")
+        cmd = [compiler, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc,
+               "-x", "c" if compiler == "gcc" else "c++", str(src)]
+        done = subprocess.run(cmd, capture_output=True, text=True)
+        assert done.returncode == 0, done.stderr
+
+
 def test_balance_plan_library_matches_the_oracle():
     # host logic of the library (no GPU involved) against the oracle
     rng = np.random.default_rng(92)
