@@ -26,6 +26,10 @@ HIPCC_FLAGS = [
 ]
 
 
+CABI_SMOKE_SRC = os.path.join(ROOT, "tests", "cabi", "cabi_smoke.cpp")
+CABI_SMOKE_BIN = os.path.join(ROOT, "tests", "cabi", "cabi_smoke.bin")
+
+
 def build(verbose: bool = True) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     sources = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
@@ -34,7 +38,21 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    build_cabi_smoke(verbose)
     return LIB
+
+
+def build_cabi_smoke(verbose: bool = True, out: str = CABI_SMOKE_BIN) -> str:
+    """The host program of tests/cabi: a plain C++ caller of the C ABI (hipMalloc,
+    default stream, no Python), linked against the library next to this file."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O2", "-std=c++17", "--offload-arch=gfx950", "-I", os.path.join(ROOT, "include"),
+           CABI_SMOKE_SRC, "-L", HERE, "-lokt", "-Wl,-rpath," + HERE,
+           "-Wl,-rpath,$ORIGIN/../../paper_2201_07598_amd", "-o", out]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return out
 
 
 if __name__ == "__main__":

@@ -120,6 +120,16 @@ def test_header_is_plain_c(tmp_path):
         assert done.returncode == 0, done.stderr
 
 
+def test_cabi_host_program_builds_and_links(tmp_path):
+    """tests/cabi/cabi_smoke.cpp, the torch-free caller of the C ABI, compiles for
+    gfx950 and links against the built library (it runs on the GPU machine, from smoke())."""
+    import subprocess
+    from paper_2201_07598_amd import build as okt_build
+    out = okt_build.build_cabi_smoke(verbose=False, out=str(tmp_path / "cabi_smoke.bin"))
+    listing = subprocess.run(["ldd", out], capture_output=True, text=True).stdout
+    assert "libokt.so" in listing and "not found" not in listing.split("libokt.so")[1].splitlines()[0]
+
+
 def test_balance_plan_library_matches_the_oracle():
     # host logic of the library (no GPU involved) against the oracle
     rng = np.random.default_rng(92)
