@@ -376,6 +376,56 @@ def test_calls_captured_in_a_hip_graph_replay_like_eager():
         assert np.all(err <= reduce_tolerance(ref_red)), r
 
 
+def test_two_host_threads_call_the_library_at_once():
+    """The entry points keep no shared mutable state (the measurement hook and the
+    last HIP error are per thread), so host threads with their own streams,
+    buffers and workspaces may call them at the same time."""
+    import threading
+    n, lr, rounds = 1_500_011, 0.5, 6
+    results, errors = {}, []
+
+    def worker(j):
+        try:
+            st = torch.cuda.Stream()
+            g = [lap(700 + 10 * j + r, n) for r in range(rounds)]
+            th = np.float32(3e-3 + 1e-3 * j)
+            with torch.cuda.stream(st):
+                d_g = [to_dev(x) for x in g]
+                res = torch.zeros(n, dtype=torch.float32, device=DEV)
+                d_th = to_dev(np.array([th], dtype=np.float32))
+                idx = [torch.full((n // 8,), -1, dtype=torch.int32, device=DEV) for _ in range(rounds)]
+                val = [torch.zeros(n // 8, dtype=torch.float32, device=DEV) for _ in range(rounds)]
+                nnz = [torch.zeros(2, dtype=torch.int64, device=DEV) for _ in range(rounds)]
+                ws = workspace(okt.okt_workspace_bytes(n, 0))
+                for r in range(rounds):
+                    if (r + j) % 2:
+                        okt.okt_accumulate_select(d_g[r], res, lr, d_th, idx[r], val[r], nnz[r], ws)
+                    else:
+                        okt.okt_residual_accumulate(d_g[r], res, lr)
+                        okt.okt_threshold_select(res, d_th, idx[r], val[r], nnz[r], ws)
+            st.synchronize()
+            results[j] = (g, th, res.cpu().numpy(), [u32(t) for t in idx],
+                          [t.cpu().numpy() for t in val], [u64(t) for t in nnz])
+        except Exception as e:          # surfaces in the main thread below
+            errors.append((j, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(j,)) for j in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for j in range(2):
+        g, th, res_gpu, idx, val, nnz = results[j]
+        res = np.zeros(n, dtype=np.float32)
+        for r in range(rounds):
+            acc = orc.residual_accumulate(g[r], res, lr)
+            ridx, rval, res, total = orc.threshold_select(acc, th, capacity=n // 8)
+            assert (int(nnz[r][0]), int(nnz[r][1])) == (ridx.size, total), (j, r)
+            assert np.array_equal(idx[r][:total], ridx) and bits_equal(val[r][:total], rval), (j, r)
+        assert bits_equal(res_gpu, res), j
+
+
 def test_a_wait_that_gives_up_is_reported():
     """Failure handling of the scan across workgroups, forced from the host: with
     the test hook's limit of one poll, a workgroup that finds a predecessor's
