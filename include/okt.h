@@ -27,6 +27,10 @@
  *     on the host before anything is launched; then no output is touched.
  *     OKT_ERR_HIP means the HIP runtime refused a launch; okt_last_hip_error
  *     gives its reason.
+ *   - Host threads may call the library at the same time as long as the calls
+ *     share no workspace and no output buffer; the library keeps no state
+ *     between calls.  okt_time_next_kernel and okt_last_hip_error act per
+ *     thread, okt_debug_spin_limit on the whole process.
  *   - The kernels that place their output through a scan across workgroups
  *     (the select family, the reduce family, the index intersection) wait for
  *     one another through device memory.  Every such wait ends by construction
