@@ -233,7 +233,10 @@ int okt_region_partition(const uint32_t* d_idx, const uint64_t* d_nnz, uint64_t 
  *                         accumulated in fp64 and rounded once to fp32; the order
  *                         of the fp64 additions is not fixed.
  *   capacity              entries the output can hold; the union is truncated to
- *                         its first `capacity` members
+ *                         its first `capacity` members.  It is also taken as the
+ *                         estimate of the union's size from which the kernel's
+ *                         tile width is chosen: a capacity far from the real size
+ *                         costs speed, never correctness
  *   d_nnz_out             out uint64[2] {emitted, size of the union}
  *   d_dense_out_or_null   out fp32[hi-lo] the region densified (absent = +0.0f),
  *                         or NULL
@@ -275,7 +278,7 @@ int okt_sparse_reduce_segments(const uint32_t* d_idx_cat, const float* d_val_cat
  * d_dense_out_or_null is given, its densified region at element j * max_width.
  * Every region must be at most max_width wide (wider is an invalid argument the
  * kernel reports by setting both counts of that region to UINT64_MAX).
- * Workspace: okt_sparse_reduce_batch_workspace_bytes(B, P, max_width).
+ * 1 <= B <= 65535.  Workspace: okt_sparse_reduce_batch_workspace_bytes(B, P, max_width).
  */
 size_t okt_sparse_reduce_batch_workspace_bytes(uint32_t B, uint32_t P, uint32_t max_width);
 
