@@ -28,7 +28,6 @@
 namespace okt {
 
 constexpr int RED_WAVES = RED_BLOCK / WAVE;
-constexpr uint32_t RED_WORDS_MAX = RED_S_MAX / 32;
 
 __device__ __forceinline__ uint64_t lower_bound_idx(const uint32_t* __restrict__ a, uint64_t lo,
                                                     uint64_t hi, uint32_t x) {
@@ -138,9 +137,11 @@ __global__ __launch_bounds__(256) void reduce_slices_wave_kernel(
 
 // Exclusive prefix over the popcounts of `words` bitmap words into s_wprefix;
 // returns the total (to every thread).  Called by the whole workgroup.
+template <uint32_t WORDS_MAX>
 __device__ __forceinline__ uint32_t bitmap_prefix(const uint32_t* s_bits, uint16_t* s_wprefix,
                                                   uint32_t words, uint32_t* s_wave) {
-    constexpr uint32_t PER = RED_WORDS_MAX / RED_BLOCK;        // words per thread (4)
+    static_assert(WORDS_MAX % RED_BLOCK == 0, "every thread owns the same number of bitmap words");
+    constexpr uint32_t PER = WORDS_MAX / RED_BLOCK;            // words per thread (2 or 3)
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
     uint32_t c[PER], sum = 0;
 #pragma unroll
@@ -161,7 +162,7 @@ __device__ __forceinline__ uint32_t bitmap_prefix(const uint32_t* s_bits, uint16
 #pragma unroll
     for (uint32_t j = 0; j < PER; ++j) {
         const uint32_t w = tid * PER + j;
-        if (w < words) s_wprefix[w] = (uint16_t)before;       // < RED_S_MAX <= 65536
+        if (w < words) s_wprefix[w] = (uint16_t)before;       // < 32 * WORDS_MAX <= 65536
         before += c[j];
     }
     __syncthreads();
@@ -171,6 +172,9 @@ __device__ __forceinline__ uint32_t bitmap_prefix(const uint32_t* s_bits, uint16
 // grid = (tiles of the widest region, B).  Region j: chunk offsets at
 // seg_begin / seg_end + j * seg_stride; bounds from lo_hi[2j..] if lo_hi != NULL else
 // (lo0, hi0).
+// C accumulators, a bitmap of S_MAX slots: (RED_C, RED_S_MAX), or (RED_C_SPARSE,
+// RED_S_SPARSE) for very sparsely hit regions.
+template <uint32_t C, uint32_t S_MAX>
 __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     const uint32_t* __restrict__ idx_cat, const float* __restrict__ val_cat,
     const uint64_t* __restrict__ seg_begin, uint32_t seg_stride,
@@ -178,10 +182,12 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     uint32_t hi0, uint32_t P, uint32_t max_width, uint32_t slots, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     float* __restrict__ dense_out, char* ws, uint32_t ws_region_bytes, uint32_t table_offset) {
-    __shared__ double s_sum[RED_C];
-    __shared__ uint32_t s_bits[RED_WORDS_MAX];
-    __shared__ uint16_t s_wprefix[RED_WORDS_MAX];
-    __shared__ uint16_t s_slot[RED_C];            // ranked tiles: slot of accumulator [rank]
+    constexpr uint32_t WORDS_MAX = S_MAX / 32;
+    static_assert(S_MAX <= 65536, "slots and ranks are kept in 16 bits");
+    __shared__ double s_sum[C];
+    __shared__ uint32_t s_bits[WORDS_MAX];
+    __shared__ uint16_t s_wprefix[WORDS_MAX];
+    __shared__ uint16_t s_slot[C];                // ranked tiles: slot of accumulator [rank]
     __shared__ uint64_t s_start[RED_CHUNKS];      // slice starts of the current sweep
     __shared__ uint32_t s_len[RED_CHUNKS];        // slice lengths
     __shared__ uint32_t s_loaded_p0;              // which sweep they belong to
@@ -202,7 +208,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
 
     const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
     uint64_t* nnz = nnz_out + 2 * (size_t)region;
-    const bool ranked = slots > RED_C;           // accumulators indexed by rank, not by slot
+    const bool ranked = slots > C;               // accumulators indexed by rank, not by slot
     const uint32_t words_all = slots / 32;       // slots is a multiple of 32
     for (uint32_t w = tid; w < words_all; w += RED_BLOCK) s_bits[w] = 0;
     __syncthreads();
@@ -309,7 +315,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
 
     if (!ranked) {
         // ---- densely hit region: accumulator = slot, one sweep ----
-        for (uint32_t s = tid; s < RED_C; s += RED_BLOCK) s_sum[s] = 0.0;
+        for (uint32_t s = tid; s < C; s += RED_BLOCK) s_sum[s] = 0.0;
         __syncthreads();
         for_each_entry(Yes{}, [&](uint32_t index, float x) {
             const uint32_t slot = index - a;
@@ -320,7 +326,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
                                   __HIP_MEMORY_SCOPE_WORKGROUP);
         });
         __syncthreads();
-        distinct = bitmap_prefix(s_bits, s_wprefix, words, s_wave);
+        distinct = bitmap_prefix<WORDS_MAX>(s_bits, s_wprefix, words, s_wave);
         exclusive = place_tile(distinct);
         for (uint32_t w = tid; w < words; w += RED_BLOCK) {
             uint32_t bits = s_bits[w];
@@ -347,26 +353,26 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
                                       __HIP_MEMORY_SCOPE_WORKGROUP);
         });
         __syncthreads();
-        distinct = bitmap_prefix(s_bits, s_wprefix, words, s_wave);
+        distinct = bitmap_prefix<WORDS_MAX>(s_bits, s_wprefix, words, s_wave);
         // the count is known before the sums: publish it now, wait for the others later
         if (tid == 0) scan_publish_early(tile_desc, tile, distinct);
         exclusive = 0;
-        const uint32_t rounds = (distinct + RED_C - 1) / RED_C;     // 1, unless the estimate was off
+        const uint32_t rounds = (distinct + C - 1) / C;             // 1, unless the estimate was off
         if (dense) {
             for (uint32_t s = tid; s < tslots; s += RED_BLOCK) dense[s] = 0.0f;
             __syncthreads();                     // zeros land before the values below
         }
         for (uint32_t round = 0; round < rounds; ++round) {
-            const uint32_t r0 = round * RED_C;                       // first rank of this round
+            const uint32_t r0 = round * C;                           // first rank of this round
             if (round) __syncthreads();                              // previous round fully read
-            for (uint32_t s = tid; s < RED_C; s += RED_BLOCK) s_sum[s] = 0.0;
+            for (uint32_t s = tid; s < C; s += RED_BLOCK) s_sum[s] = 0.0;
             __syncthreads();
             auto add = [&](uint32_t index, float x) {
                 const uint32_t slot = index - a;
                 if (slot >= tslots) return;
                 const uint32_t below = s_bits[slot >> 5] & ((1u << (slot & 31)) - 1u);
                 const uint32_t rank = (uint32_t)s_wprefix[slot >> 5] + (uint32_t)__popc(below) - r0;
-                if (rank < RED_C) {
+                if (rank < C) {
                     __hip_atomic_fetch_add(&s_sum[rank], (double)x, __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
                     s_slot[rank] = (uint16_t)slot;       // every hit of the slot writes the same
@@ -376,7 +382,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
             __syncthreads();
             if (round == 0) exclusive = place_tile(distinct);
             // accumulators and their slots are already in output order
-            const uint32_t in_round = distinct - r0 < RED_C ? distinct - r0 : RED_C;
+            const uint32_t in_round = distinct - r0 < C ? distinct - r0 : C;
             for (uint32_t k = tid; k < in_round; k += RED_BLOCK) {
                 const uint64_t pos = (uint64_t)exclusive + r0 + k;
                 const uint32_t slot = s_slot[k];
@@ -415,7 +421,8 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
         !aligned(d_dense, 4) || !aligned(d_lo_hi, 4))
         return OKT_ERR_INVALID_ARG;
     // the caller's bound on the size of the union doubles as the density estimate
-    const uint32_t slots = reduce_tile_slots(max_width, capacity);
+    const ReduceShape shape = reduce_tile_shape(max_width, capacity);
+    const uint32_t slots = shape.slots;
     const size_t region_bytes = reduce_ws_bytes_region(max_width, P, slots);
     if (region_bytes > 0xffffffffull) return OKT_ERR_INVALID_ARG;
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < region_bytes * B) return OKT_ERR_WORKSPACE;
@@ -438,7 +445,9 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
                            spin_limit_setting());
     }
     timing_before(s);
-    hipLaunchKernelGGL(reduce_tile_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,
+    auto* tile_kernel = shape.sparse ? reduce_tile_kernel<RED_C_SPARSE, RED_S_SPARSE>
+                                     : reduce_tile_kernel<RED_C, RED_S_MAX>;
+    hipLaunchKernelGGL(tile_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,
                        d_idx_cat, d_val_cat, d_seg_begin, seg_stride, d_lo_hi, lo, hi, P, max_width,
                        slots,
                        d_idx_out, d_val_out, capacity, d_nnz_out, d_dense, (char*)d_ws,

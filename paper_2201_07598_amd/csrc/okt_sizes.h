@@ -120,19 +120,45 @@ constexpr uint32_t RED_S_MAX = OKT_RED_S_MAX;   // widest tile (bits in the bitm
 #endif
 constexpr int RED_CHUNKS = OKT_RED_CHUNKS;      // contributions handled per sweep
 
-// Tile width for a region `width` wide whose union is expected to hold at most
+// Very sparsely hit regions get a second shape of the same kernel: a wider
+// bitmap paid for with fewer accumulators (the same LDS), so that a tile is not
+// cut short by the bitmap with half of its accumulators unused.
+#ifndef OKT_RED_C_SPARSE
+#define OKT_RED_C_SPARSE 3840
+#endif
+#ifndef OKT_RED_S_SPARSE
+#define OKT_RED_S_SPARSE 49152
+#endif
+constexpr uint32_t RED_C_SPARSE = OKT_RED_C_SPARSE;
+constexpr uint32_t RED_S_SPARSE = OKT_RED_S_SPARSE;
+
+// Tile shape for a region `width` wide whose union is expected to hold at most
 // `expected` entries: RED_C slots where the region is densely hit (accumulator =
-// slot), else as wide - any multiple of 32 slots up to RED_S_MAX - as keeps the
-// expected number of hit slots per tile at OKT_RED_FILL of the accumulators.
+// slot), else as wide - any multiple of 32 slots - as keeps the expected number
+// of hit slots per tile at OKT_RED_FILL of the accumulators; up to RED_S_MAX
+// slots with RED_C accumulators, beyond that the sparse shape, up to RED_S_SPARSE
+// slots with RED_C_SPARSE accumulators.
 #ifndef OKT_RED_FILL
 #define OKT_RED_FILL 0.9
 #endif
-inline uint32_t reduce_tile_slots(uint64_t width, uint64_t expected) {
-    if (width == 0 || expected == 0) return expected == 0 && width > RED_C ? RED_S_MAX : RED_C;
-    const double want = OKT_RED_FILL * RED_C * (double)width / (double)expected;
-    if (want >= RED_S_MAX) return RED_S_MAX;
+struct ReduceShape {
+    uint32_t slots;
+    bool sparse;
+};
+inline ReduceShape reduce_tile_shape(uint64_t width, uint64_t expected) {
+    if (width == 0 || expected == 0)
+        return expected == 0 && width > RED_C ? ReduceShape{RED_S_SPARSE, true} : ReduceShape{RED_C, false};
+    const double per_acc = OKT_RED_FILL * (double)width / (double)expected;   // slots per accumulator
+    const double want = per_acc * RED_C;
+    if (want > RED_S_MAX) {
+        const double wide = per_acc * RED_C_SPARSE;
+        if (wide >= RED_S_SPARSE) return ReduceShape{RED_S_SPARSE, true};
+        const uint32_t slots = (uint32_t)wide / 32 * 32;
+        // narrower than the other shape's widest tile: that one holds more per tile
+        return slots > RED_S_MAX ? ReduceShape{slots, true} : ReduceShape{RED_S_MAX, false};
+    }
     const uint32_t slots = (uint32_t)want / 32 * 32;
-    return slots < RED_C ? RED_C : slots;
+    return ReduceShape{slots < RED_C ? RED_C : slots, false};
 }
 inline uint64_t reduce_tiles(uint64_t width, uint32_t slots) { return (width + slots - 1) / slots; }
 // per region: a 64-byte header, one descriptor per tile and one per 64 tiles,

@@ -715,6 +715,24 @@ def test_reduce_more_contributions_than_one_sweep_over_ranked_tiles(seed):
     assert ref["hits"].max() > 8 and got["total"] > 300_000
 
 
+@pytest.mark.parametrize("want", [30_000, 32_768, 33_000, 34_900, 35_100, 40_000, 49_000, 49_152, 60_000, 400_000])
+def test_reduce_tile_shapes_around_the_switch_to_the_sparse_shape(want):
+    """The capacity steers the tile width (about `want` slots here): up to 32,768
+    slots with 4,096 accumulators, beyond that the sparse shape of the kernel, up
+    to 49,152 slots with 3,840 accumulators.  Same result from every shape."""
+    width, P = 1_000_003, 8
+    cap = int(0.9 * 4096 * width / want)
+    rng = np.random.default_rng(want)
+    m = max(cap // P - 3, 1)
+    parts = [np.sort(rng.choice(width, m, replace=False)).astype(np.uint32) + np.uint32(1234) for _ in range(P)]
+    parts[3] = parts[0]                                   # one support twice: collisions
+    cat_i = np.concatenate(parts)
+    cat_v = lap(want, cat_i.size)
+    off = np.arange(P + 1, dtype=np.uint64) * m
+    got, ref = check_reduce(cat_i, cat_v, off, 1234, 1234 + width, capacity=cap)
+    assert got["total"] == ref["idx"].size <= cap
+
+
 def test_reduce_paper_shaped_regions():
     """The shapes of the paper's runs (16 .. 64 contributions hitting 6 .. 30 % of a
     region) and what can go wrong around them, steered by the density estimate
