@@ -140,8 +140,9 @@ __global__ __launch_bounds__(256) void reduce_slices_wave_kernel(
 template <uint32_t WORDS_MAX>
 __device__ __forceinline__ uint32_t bitmap_prefix(const uint32_t* s_bits, uint16_t* s_wprefix,
                                                   uint32_t words, uint32_t* s_wave) {
-    static_assert(WORDS_MAX % RED_BLOCK == 0, "every thread owns the same number of bitmap words");
-    constexpr uint32_t PER = WORDS_MAX / RED_BLOCK;            // words per thread (2 or 3)
+    static_assert(WORDS_MAX % RED_BLOCK == 0 || WORDS_MAX < RED_BLOCK,
+                  "every thread owns the same number of bitmap words");
+    constexpr uint32_t PER = (WORDS_MAX + RED_BLOCK - 1) / RED_BLOCK;   // words per thread (1 to 3)
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
     uint32_t c[PER], sum = 0;
 #pragma unroll
@@ -172,8 +173,9 @@ __device__ __forceinline__ uint32_t bitmap_prefix(const uint32_t* s_bits, uint16
 // grid = (tiles of the widest region, B).  Region j: chunk offsets at
 // seg_begin / seg_end + j * seg_stride; bounds from lo_hi[2j..] if lo_hi != NULL else
 // (lo0, hi0).
-// C accumulators, a bitmap of S_MAX slots: (RED_C, RED_S_MAX), or (RED_C_SPARSE,
-// RED_S_SPARSE) for very sparsely hit regions.
+// C accumulators, a bitmap of S_MAX slots: (RED_C, RED_S_MAX); (RED_C_SPARSE,
+// RED_S_SPARSE) for very sparsely hit regions; (RED_C_DENSE, RED_C_DENSE) for
+// densely hit ones, where the accumulator of a slot is the slot itself.
 template <uint32_t C, uint32_t S_MAX>
 __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     const uint32_t* __restrict__ idx_cat, const float* __restrict__ val_cat,
@@ -187,7 +189,8 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     __shared__ double s_sum[C];
     __shared__ uint32_t s_bits[WORDS_MAX];
     __shared__ uint16_t s_wprefix[WORDS_MAX];
-    __shared__ uint16_t s_slot[C];                // ranked tiles: slot of accumulator [rank]
+    constexpr bool CAN_RANK = S_MAX > C;          // else: accumulator = slot, always
+    __shared__ uint16_t s_slot[CAN_RANK ? C : 1]; // ranked tiles: slot of accumulator [rank]
     __shared__ uint64_t s_start[RED_CHUNKS];      // slice starts of the current sweep
     __shared__ uint32_t s_len[RED_CHUNKS];        // slice lengths
     __shared__ uint32_t s_loaded_p0;              // which sweep they belong to
@@ -208,7 +211,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
 
     const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
     uint64_t* nnz = nnz_out + 2 * (size_t)region;
-    const bool ranked = slots > C;               // accumulators indexed by rank, not by slot
+    const bool ranked = CAN_RANK && slots > C;   // accumulators indexed by rank, not by slot
     const uint32_t words_all = slots / 32;       // slots is a multiple of 32
     for (uint32_t w = tid; w < words_all; w += RED_BLOCK) s_bits[w] = 0;
     __syncthreads();
@@ -344,7 +347,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
         }
         if (dense)
             for (uint32_t s = tid; s < tslots; s += RED_BLOCK) dense[s] = (float)s_sum[s];
-    } else {
+    } else if constexpr (CAN_RANK) {
         // ---- sparsely hit region: mark, rank, then sum into accumulator [rank] ----
         for_each_entry(No{}, [&](uint32_t index, float) {
             const uint32_t slot = index - a;
@@ -421,7 +424,12 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
         !aligned(d_dense, 4) || !aligned(d_lo_hi, 4))
         return OKT_ERR_INVALID_ARG;
     // the caller's bound on the size of the union doubles as the density estimate
-    const ReduceShape shape = reduce_tile_shape(max_width, capacity);
+    ReduceShape shape = reduce_tile_shape(max_width, capacity);
+    // The wide dense tile is for throughput.  A launch that cannot fill the chip
+    // anyway is nothing but the latency of its tiles: it takes the narrower dense
+    // tile of the ranked shape (more, shorter tiles).
+    if (shape.kind == RED_DENSE && (uint64_t)B * reduce_tiles(max_width, RED_C) <= 3 * 256)
+        shape = ReduceShape{RED_C, RED_RANKED};
     const uint32_t slots = shape.slots;
     const size_t region_bytes = reduce_ws_bytes_region(max_width, P, slots);
     if (region_bytes > 0xffffffffull) return OKT_ERR_INVALID_ARG;
@@ -445,8 +453,9 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
                            spin_limit_setting());
     }
     timing_before(s);
-    auto* tile_kernel = shape.sparse ? reduce_tile_kernel<RED_C_SPARSE, RED_S_SPARSE>
-                                     : reduce_tile_kernel<RED_C, RED_S_MAX>;
+    auto* tile_kernel = shape.kind == RED_SPARSE  ? reduce_tile_kernel<RED_C_SPARSE, RED_S_SPARSE>
+                        : shape.kind == RED_DENSE ? reduce_tile_kernel<RED_C_DENSE, RED_C_DENSE>
+                                                  : reduce_tile_kernel<RED_C, RED_S_MAX>;
     hipLaunchKernelGGL(tile_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,
                        d_idx_cat, d_val_cat, d_seg_begin, seg_stride, d_lo_hi, lo, hi, P, max_width,
                        slots,

@@ -120,45 +120,54 @@ constexpr uint32_t RED_S_MAX = OKT_RED_S_MAX;   // widest tile (bits in the bitm
 #endif
 constexpr int RED_CHUNKS = OKT_RED_CHUNKS;      // contributions handled per sweep
 
-// Very sparsely hit regions get a second shape of the same kernel: a wider
-// bitmap paid for with fewer accumulators (the same LDS), so that a tile is not
-// cut short by the bitmap with half of its accumulators unused.
+// Two more shapes of the same kernel spend the same LDS differently.  Very
+// sparsely hit regions: a wider bitmap paid for with fewer accumulators, so that
+// a tile is not cut short by the bitmap with half of its accumulators unused.
+// Densely hit regions (accumulator = slot): no rank-to-slot array and a bitmap
+// only as wide as the accumulators, which leaves room for more of them.
 #ifndef OKT_RED_C_SPARSE
 #define OKT_RED_C_SPARSE 3840
 #endif
 #ifndef OKT_RED_S_SPARSE
 #define OKT_RED_S_SPARSE 49152
 #endif
+#ifndef OKT_RED_C_DENSE
+#define OKT_RED_C_DENSE 5888
+#endif
 constexpr uint32_t RED_C_SPARSE = OKT_RED_C_SPARSE;
 constexpr uint32_t RED_S_SPARSE = OKT_RED_S_SPARSE;
+constexpr uint32_t RED_C_DENSE = OKT_RED_C_DENSE;      // a multiple of 32
 
 // Tile shape for a region `width` wide whose union is expected to hold at most
-// `expected` entries: RED_C slots where the region is densely hit (accumulator =
-// slot), else as wide - any multiple of 32 slots - as keeps the expected number
-// of hit slots per tile at OKT_RED_FILL of the accumulators; up to RED_S_MAX
-// slots with RED_C accumulators, beyond that the sparse shape, up to RED_S_SPARSE
-// slots with RED_C_SPARSE accumulators.
+// `expected` entries.  Densely hit (at most RED_C_DENSE / RED_C slots per expected
+// entry and accumulator): RED_C_DENSE slots, accumulator = slot, one sweep.  Else
+// ranked tiles as wide - any multiple of 32 slots - as keeps the expected number
+// of hit slots per tile at OKT_RED_FILL of the accumulators: up to RED_S_MAX
+// slots with RED_C accumulators, beyond that up to RED_S_SPARSE slots with
+// RED_C_SPARSE accumulators.
 #ifndef OKT_RED_FILL
 #define OKT_RED_FILL 0.9
 #endif
+enum ReduceKind { RED_DENSE = 0, RED_RANKED = 1, RED_SPARSE = 2 };
 struct ReduceShape {
     uint32_t slots;
-    bool sparse;
+    ReduceKind kind;
 };
 inline ReduceShape reduce_tile_shape(uint64_t width, uint64_t expected) {
     if (width == 0 || expected == 0)
-        return expected == 0 && width > RED_C ? ReduceShape{RED_S_SPARSE, true} : ReduceShape{RED_C, false};
+        return expected == 0 && width > RED_C_DENSE ? ReduceShape{RED_S_SPARSE, RED_SPARSE}
+                                                    : ReduceShape{RED_C_DENSE, RED_DENSE};
     const double per_acc = OKT_RED_FILL * (double)width / (double)expected;   // slots per accumulator
     const double want = per_acc * RED_C;
+    if (want <= RED_C_DENSE) return ReduceShape{RED_C_DENSE, RED_DENSE};
     if (want > RED_S_MAX) {
         const double wide = per_acc * RED_C_SPARSE;
-        if (wide >= RED_S_SPARSE) return ReduceShape{RED_S_SPARSE, true};
+        if (wide >= RED_S_SPARSE) return ReduceShape{RED_S_SPARSE, RED_SPARSE};
         const uint32_t slots = (uint32_t)wide / 32 * 32;
         // narrower than the other shape's widest tile: that one holds more per tile
-        return slots > RED_S_MAX ? ReduceShape{slots, true} : ReduceShape{RED_S_MAX, false};
+        return slots > RED_S_MAX ? ReduceShape{slots, RED_SPARSE} : ReduceShape{RED_S_MAX, RED_RANKED};
     }
-    const uint32_t slots = (uint32_t)want / 32 * 32;
-    return ReduceShape{slots < RED_C ? RED_C : slots, false};
+    return ReduceShape{(uint32_t)want / 32 * 32, RED_RANKED};
 }
 inline uint64_t reduce_tiles(uint64_t width, uint32_t slots) { return (width + slots - 1) / slots; }
 // per region: a 64-byte header, one descriptor per tile and one per 64 tiles,
@@ -170,7 +179,7 @@ inline size_t reduce_ws_bytes_region(uint64_t max_width, uint32_t P, uint32_t sl
     return (bytes + 63) & ~(size_t)63;
 }
 inline size_t reduce_ws_bytes(uint64_t B, uint64_t max_width, uint32_t P) {
-    return (size_t)B * reduce_ws_bytes_region(max_width, P, RED_C);     // narrowest tile: largest
+    return (size_t)B * reduce_ws_bytes_region(max_width, P, RED_C);     // no tile is narrower: largest
 }
 
 }  // namespace okt
