@@ -23,6 +23,10 @@
 #include "okt_device.h"
 #include "okt_sizes.h"
 
+#ifndef OKT_RED_EMIT_BITS
+#define OKT_RED_EMIT_BITS 4      // bits of a bitmap word one thread writes out (dense tiles)
+#endif
+
 #include <type_traits>
 
 namespace okt {
@@ -331,13 +335,19 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
         __syncthreads();
         distinct = bitmap_prefix<WORDS_MAX>(s_bits, s_wprefix, words, s_wave);
         exclusive = place_tile(distinct);
-        for (uint32_t w = tid; w < words; w += RED_BLOCK) {
-            uint32_t bits = s_bits[w];
-            uint64_t pos = (uint64_t)exclusive + s_wprefix[w];
+        // a thread writes out the hit slots of one EMIT_BITS-wide piece of a bitmap
+        // word: a tile has fewer words than the workgroup has threads, a word up
+        // to 32 hits, and the slowest thread sets the pace
+        constexpr uint32_t EMIT_BITS = OKT_RED_EMIT_BITS, EMIT_PER = 32 / EMIT_BITS;
+        for (uint32_t u = tid; u < words * EMIT_PER; u += RED_BLOCK) {
+            const uint32_t w = u / EMIT_PER, shift = (u % EMIT_PER) * EMIT_BITS;
+            const uint32_t word = s_bits[w];
+            uint32_t bits = (word >> shift) & ((1u << EMIT_BITS) - 1u);
+            uint64_t pos = (uint64_t)exclusive + s_wprefix[w] + (uint32_t)__popc(word & ((1u << shift) - 1u));
             while (bits) {
                 const int bit = __ffs(bits) - 1;
                 bits &= bits - 1;
-                const uint32_t slot = w * 32u + bit;
+                const uint32_t slot = w * 32u + shift + bit;
                 if (pos < capacity) {
                     idx_out[pos] = a + slot;
                     val_out[pos] = (float)s_sum[slot];

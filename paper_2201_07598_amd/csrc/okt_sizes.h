@@ -132,7 +132,7 @@ constexpr int RED_CHUNKS = OKT_RED_CHUNKS;      // contributions handled per swe
 #define OKT_RED_S_SPARSE 49152
 #endif
 #ifndef OKT_RED_C_DENSE
-#define OKT_RED_C_DENSE 5888
+#define OKT_RED_C_DENSE 6016
 #endif
 constexpr uint32_t RED_C_SPARSE = OKT_RED_C_SPARSE;
 constexpr uint32_t RED_S_SPARSE = OKT_RED_S_SPARSE;
