@@ -106,7 +106,7 @@ inline size_t threshold_ws_bytes(uint64_t n) {
 #define OKT_RED_BLOCK 512
 #endif
 #ifndef OKT_RED_UNROLL
-#define OKT_RED_UNROLL 8
+#define OKT_RED_UNROLL 10
 #endif
 constexpr int RED_BLOCK = OKT_RED_BLOCK;
 constexpr int RED_UNROLL = OKT_RED_UNROLL;      // entries a thread keeps in flight
