@@ -217,7 +217,9 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     uint64_t* nnz = nnz_out + 2 * (size_t)region;
     const bool ranked = CAN_RANK && slots > C;   // accumulators indexed by rank, not by slot
     const uint32_t words_all = slots / 32;       // slots is a multiple of 32
+    // the bitmap and the accumulators are cleared while the ticket is under way
     for (uint32_t w = tid; w < words_all; w += RED_BLOCK) s_bits[w] = 0;
+    for (uint32_t s = tid; s < C; s += RED_BLOCK) s_sum[s] = 0.0;
     __syncthreads();
     const uint32_t tile = s_tile;
     if (r.ntiles == 0) {
@@ -322,8 +324,6 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
 
     if (!ranked) {
         // ---- densely hit region: accumulator = slot, one sweep ----
-        for (uint32_t s = tid; s < C; s += RED_BLOCK) s_sum[s] = 0.0;
-        __syncthreads();
         for_each_entry(Yes{}, [&](uint32_t index, float x) {
             const uint32_t slot = index - a;
             if (slot >= tslots) return;          // only reachable with unsorted input
@@ -377,9 +377,11 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
         }
         for (uint32_t round = 0; round < rounds; ++round) {
             const uint32_t r0 = round * C;                           // first rank of this round
-            if (round) __syncthreads();                              // previous round fully read
-            for (uint32_t s = tid; s < C; s += RED_BLOCK) s_sum[s] = 0.0;
-            __syncthreads();
+            if (round) {                                             // the first round starts cleared
+                __syncthreads();                                     // previous round fully read
+                for (uint32_t s = tid; s < C; s += RED_BLOCK) s_sum[s] = 0.0;
+                __syncthreads();
+            }
             auto add = [&](uint32_t index, float x) {
                 const uint32_t slot = index - a;
                 if (slot >= tslots) return;
