@@ -26,7 +26,31 @@ struct TestKey {
     __device__ __forceinline__ bool operator()(float x) const { return magnitude_key(x) >= th_key; }
 };
 
-struct StashEntry { uint32_t idx; float val; };     // 8 bytes: one LDS store per entry
+// A wave's stash in LDS: the selected entries of its piece, in index order, as
+// the value (4 bytes) and the position inside the piece (2 bytes: a piece is at
+// most SEL_PIECE_MAX = 16,384 elements long).  Six bytes an entry instead of eight
+// is a third more entries in the same LDS.
+struct StashEntry { uint32_t idx; float val; };
+struct WaveStash {
+    float* val;
+    uint16_t* off;
+    uint32_t base;                                   // index of the piece's first element
+    __device__ __forceinline__ void put(uint32_t rank, uint32_t i, float x) const {
+        val[rank] = x;
+        off[rank] = (uint16_t)(i - base);
+    }
+    __device__ __forceinline__ StashEntry operator[](uint32_t j) const {
+        return StashEntry{base + (uint32_t)off[j], val[j]};
+    }
+};
+template <int WAVES, int STASH>
+struct StashMemory {                                 // the stashes of a workgroup
+    float val[WAVES][STASH];
+    uint16_t off[WAVES][STASH];
+    __device__ __forceinline__ WaveStash of(int wave, uint64_t piece_start) {
+        return WaveStash{val[wave], off[wave], (uint32_t)piece_start};
+    }
+};
 
 // One round of a wave: 64 lanes x float4 = 256 consecutive elements starting at
 // `first` (lane l holds first + 4l .. first + 4l + 3); sx..sw say which of the
@@ -167,7 +191,7 @@ __device__ __forceinline__ void select_finish(
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t seg,
     uint64_t start, uint64_t end, uint32_t count, uint32_t stashed, uint64_t resume_at,
-    uint32_t resume_count, StashEntry* mine, uint32_t* s_count, uint32_t* s_before) {
+    uint32_t resume_count, WaveStash mine, uint32_t* s_count, uint32_t* s_before) {
     constexpr int WAVES = BLOCK / WAVE;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
     if (lane == 0) s_count[wave] = count;
@@ -210,8 +234,10 @@ __device__ __forceinline__ void select_finish(
     if (!all_stashed) {
         (void)start;
         if (Source::zero) {
-            for (uint32_t j = resume_count + lane; j < stashed; j += WAVE)
-                acc[mine[j].idx] = mine[j].val;
+            for (uint32_t j = resume_count + lane; j < stashed; j += WAVE) {
+                const StashEntry e = mine[j];
+                acc[e.idx] = e.val;
+            }
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // stores land before the re-read
         }
         select_walk<U>(acc, resume_at, end, test, [&](uint32_t rank, uint32_t i, float x) {
@@ -242,17 +268,17 @@ __device__ __forceinline__ void select_body(
     float* __restrict__ acc, uint32_t n, Test test, Source source, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece,
-    uint32_t seg, StashEntry (*s_stash)[STASH], uint32_t* s_count, uint32_t* s_before) {
+    uint32_t seg, StashMemory<BLOCK / WAVE, STASH>& s_stash, uint32_t* s_count, uint32_t* s_before) {
     constexpr int WAVES = BLOCK / WAVE;
     const int wave = threadIdx.x >> 6;
     const uint64_t start = ((uint64_t)seg * WAVES + wave) * piece;
     const uint64_t end = start + piece < n ? start + piece : n;       // start >= n: empty
-    StashEntry* mine = s_stash[wave];
+    const WaveStash mine = s_stash.of(wave, start);
     WalkMark over = {start, 0u, false};          // the batch in which the stash ran full
     const uint32_t count =
         select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
             if (rank < (uint32_t)STASH) {
-                mine[rank] = StashEntry{i, x};
+                mine.put(rank, i, x);
                 if (Source::zero) acc[i] = 0.0f;
             }
         }, 0u, &over, (uint32_t)STASH);
@@ -275,13 +301,13 @@ __device__ __forceinline__ void accumulate_select_body(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, Test test,
     uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
     uint64_t* __restrict__ nnz_out, ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc,
-    uint32_t nseg, uint32_t piece, uint32_t seg, StashEntry (*s_stash)[STASH], uint32_t* s_count,
+    uint32_t nseg, uint32_t piece, uint32_t seg, StashMemory<BLOCK / WAVE, STASH>& s_stash, uint32_t* s_count,
     uint32_t* s_before) {
     constexpr int WAVES = BLOCK / WAVE;
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
     const uint64_t start = ((uint64_t)seg * WAVES + wave) * piece;
     const uint64_t end = start + piece < n ? start + piece : n;
-    StashEntry* mine = s_stash[wave];
+    const WaveStash mine = s_stash.of(wave, start);
     uint32_t count = 0, stashed = 0;                 // wave-uniform
     uint64_t resume_at = start;                      // first round that was not stashed
     bool resumed = false;
@@ -289,14 +315,17 @@ __device__ __forceinline__ void accumulate_select_body(
     // one round of 256 elements whose accumulator values are in `a`; returns the
     // residual to store
     auto round = [&](uint32_t first, float4 a, bool sx, bool sy, bool sz, bool sw) -> float4 {
-        const bool room = count <= (uint32_t)(STASH - 256) && count == stashed;
+        // the round goes to the stash if all of it fits (and nothing was left out before)
+        const uint32_t add = (uint32_t)(__popcll(__ballot(sx)) + __popcll(__ballot(sy)) +
+                                        __popcll(__ballot(sz)) + __popcll(__ballot(sw)));
+        const bool room = count == stashed && count + add <= (uint32_t)STASH;
         if (!room && !resumed) {
             resumed = true;
             resume_at = first;
         }
         const uint32_t now = select_round(first, a, sx, sy, sz, sw, count,
                                           [&](uint32_t rank, uint32_t i, float x) {
-                                              if (room) mine[rank] = StashEntry{i, x};
+                                              if (room) mine.put(rank, i, x);
                                           });
         if (room) {
             stashed = now;
@@ -385,7 +414,7 @@ __global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void select_kernel(
     uint32_t nseg, uint32_t piece) {
     static_assert(BLOCK % WAVE == 0 && BLOCK >= 2 * WAVE, "needs two waves for the scan");
     constexpr int WAVES = BLOCK / WAVE;
-    __shared__ StashEntry s_stash[WAVES][STASH];
+    __shared__ StashMemory<WAVES, STASH> s_stash;
     __shared__ uint32_t s_count[WAVES];
     __shared__ uint32_t s_seg;
     __shared__ uint32_t s_before[2];           // within the group, across groups
@@ -419,7 +448,7 @@ __global__ __launch_bounds__(BLOCK) void coo_select_kernel(
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece) {
     constexpr int WAVES = BLOCK / WAVE;
-    __shared__ StashEntry s_stash[WAVES][STASH];
+    __shared__ StashMemory<WAVES, STASH> s_stash;
     __shared__ uint32_t s_count[WAVES];
     __shared__ uint32_t s_seg;
     __shared__ uint32_t s_before[2];
@@ -452,7 +481,7 @@ __global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void accumulate_select_kernel(
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
     ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece) {
     constexpr int WAVES = BLOCK / WAVE;
-    __shared__ StashEntry s_stash[WAVES][STASH];
+    __shared__ StashMemory<WAVES, STASH> s_stash;
     __shared__ uint32_t s_count[WAVES];
     __shared__ uint32_t s_seg;
     __shared__ uint32_t s_before[2];

@@ -12,7 +12,7 @@ namespace okt {
 // vector, one per wave; a wave streams its piece in rounds of 256 elements,
 // SEL_U rounds in flight.  The piece length (select_shape below) is never above
 // SEL_PIECE_MAX, which keeps the selected entries of a piece inside the wave's
-// LDS stash up to a local density of SEL_STASH / SEL_PIECE_MAX = 7.3 %.
+// LDS stash up to a local density of SEL_STASH / SEL_PIECE_MAX = 9.8 %.
 #ifndef OKT_SEL_U
 #define OKT_SEL_U 4
 #endif
@@ -26,12 +26,12 @@ constexpr int SEL_BLOCK = OKT_SEL_BLOCK;
 constexpr int SEL_WAVES = SEL_BLOCK / 64;
 constexpr int SEL_U = OKT_SEL_U;
 // The kernels need more than 64 registers, so a CU holds one workgroup at a time
-// anyway: its stash takes nearly the whole LDS (16 waves x 1200 entries x 8 bytes
+// anyway: its stash takes nearly the whole LDS (16 waves x 1600 entries x 6 bytes
 // = 150 KB of 160).  Gradients select unevenly - whole layers above the
 // threshold next to layers with nothing - and a piece that overflows its stash
 // is partly walked twice.
 #ifndef OKT_SEL_STASH
-#define OKT_SEL_STASH 1200
+#define OKT_SEL_STASH 1600
 #endif
 constexpr int SEL_STASH = OKT_SEL_STASH;       // entries per wave
 constexpr bool SEL_TICKET = OKT_SEL_TICKET;    // false: measurement builds only
