@@ -7,16 +7,20 @@ Workload: the ResNet-50-sized configuration (n = 25,557,032 fp32, 161 layer
 segments, density 1 %, P = 16).  One STEP is one refresh period of the local
 part of Ok-Topk SGD for one simulated worker, 10 iterations:
 
-    iteration 0:     okt_residual_accumulate -> okt_topk_threshold_exact
-                     -> okt_threshold_select -> okt_region_partition
+    iteration 0:     okt_accumulate_topk_select (accumulate, exact threshold and
+                     select reading the gradient and the residual once: the same
+                     results, bit for bit, as okt_residual_accumulate ->
+                     okt_topk_threshold_exact -> okt_threshold_select)
+                     -> okt_region_partition
     iterations 1-9:  okt_accumulate_select (the same accumulate and select, bit for
                      bit, in one pass: the threshold is reused, so it is known
                      before the accumulator is)
     every iteration: okt_sparse_reduce (P = 16 contributions over one region of n/16)
 
 with the error-feedback residual carried from iteration to iteration and from
-step to step.  `two_call_path` in the output is the same step with iterations 1-9
-calling okt_residual_accumulate + okt_threshold_select instead.  Steps rotate over several independent simulated workers and the
+step to step.  `two_call_path` in the output is the same step made of the separate
+calls (okt_residual_accumulate, okt_topk_threshold_exact at iteration 0,
+okt_threshold_select).  Steps rotate over several independent simulated workers and the
 reduce rotates over a pool of contribution sets, so that no vector is served
 from the 256 MB Infinity Cache on re-use.  All inputs are seeded, synthetic and
 resident in HBM before the timed region starts.
@@ -41,7 +45,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 ITERS_PER_STEP = 10
 WORKLOAD = "cfg2"
-CALLS = ("accumulate", "threshold", "select", "accumulate_select", "partition", "reduce")
+CALLS = ("accumulate", "threshold", "select", "accumulate_topk_select", "accumulate_select",
+         "partition", "reduce")
 
 
 def log(*a):
@@ -179,7 +184,12 @@ def main():
                 fn()
 
         for it in range(ITERS_PER_STEP):
-            if fused and it != 0:
+            if fused and it == 0:
+                # refresh iteration: accumulate, exact threshold and select in one call
+                timed("accumulate_topk_select", lambda: okt.okt_accumulate_topk_select(
+                    st.grads[it], st.residual, w.lr, k, st.th, st.count_ge, st.idx, st.val,
+                    st.nnz, st.ws, capacity=st.cap))
+            elif fused:
                 # reuse iteration: the threshold is already known, one pass does both
                 timed("accumulate_select", lambda: okt.okt_accumulate_select(
                     st.grads[it], st.residual, w.lr, st.th, st.idx, st.val, st.nnz, st.ws,
@@ -225,7 +235,7 @@ def main():
     torch.cuda.synchronize()
     warm = summarise(ev, tail=0.5) if ev else {}
     nnz_seen = int(workers[0].nnz.cpu().numpy().view(np.uint64)[1]) if args.warmup else k
-    calls_per_step = {"accumulate": 1, "threshold": 1, "select": 1,
+    calls_per_step = {"accumulate": 1, "threshold": 1, "select": 1, "accumulate_topk_select": 1,
                       "accumulate_select": ITERS_PER_STEP - 1, "partition": 1,
                       "reduce": ITERS_PER_STEP}
     if warm:
@@ -264,6 +274,18 @@ def main():
         run_step(args.warmup + args.steps + s, ev=ev2k, kernel_pairs=pairs2)
     torch.cuda.synchronize()
     table_kernel = summarise(ev2k)
+    # the separate calls (not part of the step any more) for the same table
+    ev2s, ev2sk = [], []
+    pairs3 = event_pairs(64 * 4)
+    for s in range(4):
+        run_step(args.warmup + args.steps + s, ev=ev2s, fused=False)
+    for s in range(4):
+        run_step(args.warmup + args.steps + s, ev=ev2sk, fused=False, kernel_pairs=pairs3)
+    torch.cuda.synchronize()
+    for c, v in summarise(ev2s).items():
+        table.setdefault(c, v)
+    for c, v in summarise(ev2sk).items():
+        table_kernel.setdefault(c, v)
     nnz_now = int(workers[0].nnz.cpu().numpy().view(np.uint64)[1])
     U = int(red_nnz.cpu().numpy().view(np.uint64)[1])
 
@@ -273,6 +295,7 @@ def main():
         "threshold": 4.0 * n,                                 # one read of acc is the floor
         "select": 4.0 * n + 12.0 * nnz_now,                   # read acc; idx, val, zero per entry
         "accumulate_select": 12.0 * n + 8.0 * nnz_now,        # read G, eps; write eps; idx, val
+        "accumulate_topk_select": 12.0 * n + 12.0 * nnz_now,  # the same, and a zero per entry
         "reduce": 8.0 * E + 8.0 * U + (4.0 * (hi - lo) if args.reduce_dense else 0.0),   # entries in, union out
     }
     kernels = {}
@@ -310,8 +333,8 @@ def main():
         run_step(s, ev=ev3, only=("accumulate", "select"), fused=False)
     torch.cuda.synchronize()
     two = summarise(ev3)
-    two_call_path = {"what": "iterations 1-9 of a step call okt_residual_accumulate + "
-                             "okt_threshold_select instead of okt_accumulate_select",
+    two_call_path = {"what": "the same step made of the separate calls: okt_residual_accumulate, "
+                             "okt_topk_threshold_exact (iteration 0), okt_threshold_select",
                      "ms_per_step": ms_two, "value": ITERS_PER_STEP * n / (ms_two * 1e-3)}
     for c in ("accumulate", "select"):
         us = two[c][0]

@@ -79,9 +79,10 @@ void okt_debug_spin_limit(uint32_t polls);
  * passed as void*; either may be NULL), on the stream of that call - the kernel
  * that moves the data, not the small launches around it (clearing of scan state,
  * slice table, histogram bookkeeping): okt_residual_accumulate, the select
- * family, okt_accumulate_select, okt_region_partition, the tile kernel of the
- * reduce family, the collect pass of okt_topk_threshold_exact (not recorded when
- * that call takes its unsampled path), the intersect kernel.  The pair is used
+ * family, okt_accumulate_select, the pass of okt_accumulate_topk_select that
+ * forms the accumulator, okt_region_partition, the tile kernel of the reduce
+ * family, the collect pass of okt_topk_threshold_exact (not recorded when that
+ * call takes its unsampled path), the intersect kernel.  The pair is used
  * once and forgotten; a call that launches no such kernel (an argument error, an
  * empty input) leaves it armed for the next one.  For benchmarks: so that an
  * event time can be compared with a profiler's kernel duration.
@@ -192,6 +193,30 @@ int okt_accumulate_select(const float* d_grad, float* d_residual_inout, float lr
                           const float* d_threshold, uint32_t* d_idx_out, float* d_val_out,
                           uint64_t capacity, uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes,
                           void* stream);
+
+/*
+ * A whole iteration that re-evaluates the threshold (Algorithm 1, lines 2-4;
+ * Algorithm 2, lines 4-6) while reading the gradient and the residual once.
+ * Same results, bit for bit, as okt_residual_accumulate, okt_topk_threshold_exact
+ * on the accumulator with the same k, and okt_threshold_select with that
+ * threshold and the same capacity:
+ *   d_threshold_out, d_count_ge_out   as in okt_topk_threshold_exact
+ *   d_idx_out, d_val_out, d_nnz_out   as in okt_threshold_select
+ *   d_residual_inout                  ends as acc with +0.0f at the emitted entries
+ * 1 <= k <= n < 2^32; d_grad and d_residual_inout must not overlap.
+ * With a workspace of okt_workspace_bytes(n, .) and n of four million or more,
+ * the pass that forms the accumulator also sets aside, in index order, every
+ * element above a bound read off a sample; the exact selection and the final
+ * select then run over those candidates (a few percent of the vector), and only
+ * the emitted entries are zeroed in the residual with scattered stores: 12 B per
+ * element instead of 20.  A shorter vector, a smaller workspace (the minimum is
+ * what the three calls need), or a sample that misled take the three steps over
+ * the whole vector: the results are the same.
+ */
+int okt_accumulate_topk_select(const float* d_grad, float* d_residual_inout, float lr, uint64_t n,
+                               uint64_t k, float* d_threshold_out, uint64_t* d_count_ge_out,
+                               uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                               uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
  * Balanced split of the index space [0, n) into R regions by the local top-k

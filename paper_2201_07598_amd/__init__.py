@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     okt_accumulate_select,
+    okt_accumulate_topk_select,
     okt_balance_plan,
     okt_coo_threshold_select,
     okt_debug_spin_limit,

@@ -35,6 +35,8 @@ SIGNATURES = {
                                          c_vp, c_sz, c_vp]),
     "okt_accumulate_select": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp,
                                       c_sz, c_vp]),
+    "okt_accumulate_topk_select": (c_int, [c_vp, c_vp, c_f32, c_u64, c_u64, c_vp, c_vp, c_vp, c_vp,
+                                           c_u64, c_vp, c_vp, c_sz, c_vp]),
     "okt_coo_threshold_select": (c_int, [c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp,
                                          c_sz, c_vp]),
     "okt_index_intersect_restore": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_u64,
@@ -242,6 +244,26 @@ def okt_accumulate_select(grad, residual_inout, lr: float, threshold, idx_out, v
     _check("okt_accumulate_select", load_library().okt_accumulate_select(
         _ptr(grad, torch.float32, "grad"), residual_inout.data_ptr(), float(lr),
         residual_inout.numel(), _ptr(threshold, torch.float32, "threshold"),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
+        _ptr(nnz_out, _u64(torch), "nnz_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
+        _stream(stream)))
+
+
+def okt_accumulate_topk_select(grad, residual_inout, lr: float, k: int, threshold_out, count_ge_out,
+                               idx_out, val_out, nnz_out, ws, capacity=None, stream=None) -> None:
+    torch = _torch()
+    _ptr(residual_inout, torch.float32, "residual_inout")
+    if grad.numel() != residual_inout.numel():
+        raise ValueError("grad and residual must have the same length")
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > idx_out.numel() or cap > val_out.numel():
+        raise ValueError("capacity exceeds the output buffers")
+    if nnz_out.numel() < 2 or threshold_out.numel() < 1 or count_ge_out.numel() < 1:
+        raise ValueError("nnz_out needs two elements, threshold_out and count_ge_out one")
+    _check("okt_accumulate_topk_select", load_library().okt_accumulate_topk_select(
+        _ptr(grad, torch.float32, "grad"), residual_inout.data_ptr(), float(lr),
+        residual_inout.numel(), int(k), _ptr(threshold_out, torch.float32, "threshold_out"),
+        _ptr(count_ge_out, _u64(torch), "count_ge_out"),
         _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
         _ptr(nnz_out, _u64(torch), "nnz_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
         _stream(stream)))

@@ -81,6 +81,8 @@ size_t okt_workspace_bytes(uint64_t n_max, uint32_t P_max) {
     size_t need = okt::threshold_ws_bytes(n_max);
     size_t s = okt::select_ws_bytes(n_max);
     if (s > need) need = s;
+    s = okt::refresh_ws_bytes(n_max);
+    if (s > need) need = s;
     s = okt::restore_ws_bytes(n_max);
     if (s > need) need = s;
     s = okt::reduce_ws_bytes(1, n_max, P_max);

@@ -2,6 +2,8 @@
 #ifndef OKT_SELECT_KERNEL_H
 #define OKT_SELECT_KERNEL_H
 
+#include <type_traits>
+
 #include "okt_device.h"
 
 namespace okt {
@@ -159,20 +161,38 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
 
 // What the select runs over.  DenseSource: a dense vector whose selected elements
 // are zeroed in place (the residual update) and whose positions are the output
-// indices; DenseCopySource: the same without the zeroing.  CooSource: the value array of a sorted COO list, left untouched; the
-// output index of position i is idx_in[i].
+// indices; DenseCopySource: the same without the zeroing.  CooSource: the value
+// array of a sorted COO list, left untouched; the output index of position i is
+// idx_in[i].  CandidateSource: a sorted COO list of candidates drawn from a dense
+// residual (idx_in set), or that residual itself (idx_in null); nothing is
+// zeroed during the walk, an entry's place in the residual is zeroed when the
+// entry is written out.
 struct DenseSource {
     static constexpr bool zero = true;
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return i; }
+    __device__ __forceinline__ void on_emit(float*, uint32_t, uint32_t) const {}
 };
 struct DenseCopySource {                     // a dense vector that is only read
     static constexpr bool zero = false;
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return i; }
+    __device__ __forceinline__ void on_emit(float*, uint32_t, uint32_t) const {}
 };
 struct CooSource {
     static constexpr bool zero = false;
     const uint32_t* idx_in;
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return idx_in[i]; }
+    __device__ __forceinline__ void on_emit(float*, uint32_t, uint32_t) const {}
+};
+struct CandidateSource {
+    static constexpr bool zero = false;
+    const uint32_t* idx_in;
+    float* res;                              // used only when idx_in is set
+    __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return idx_in ? idx_in[i] : i; }
+    // `walked` is the array the walk runs over, `i` the position in it, `o` the output index
+    __device__ __forceinline__ void on_emit(float* walked, uint32_t i, uint32_t o) const {
+        if (idx_in) res[o] = 0.0f;
+        else walked[i] = 0.0f;
+    }
 };
 
 // Second half of a select: the workgroup publishes its count, learns the count of
@@ -225,8 +245,10 @@ __device__ __forceinline__ void select_finish(
         const uint64_t pos = first + j;
         const StashEntry e = mine[j];
         if (pos < capacity) {
-            idx_out[pos] = source.out_index(e.idx);
+            const uint32_t o = source.out_index(e.idx);
+            idx_out[pos] = o;
             val_out[pos] = e.val;
+            source.on_emit(acc, e.idx, o);
         } else if (Source::zero) {
             acc[e.idx] = e.val;             // output full: the entry stays in the residual
         }
@@ -243,9 +265,11 @@ __device__ __forceinline__ void select_finish(
         select_walk<U>(acc, resume_at, end, test, [&](uint32_t rank, uint32_t i, float x) {
             const uint64_t pos = first + rank;
             if (pos < capacity) {
-                idx_out[pos] = source.out_index(i);
+                const uint32_t o = source.out_index(i);
+                idx_out[pos] = o;
                 val_out[pos] = x;
                 if (Source::zero) acc[i] = 0.0f;
+                source.on_emit(acc, i, o);
             }
         }, resume_count);
     }
@@ -295,8 +319,10 @@ __device__ __forceinline__ void select_body(
 // and writes the new residual -- acc, with zeros at the parked entries -- as
 // whole 16-byte stores.  Every residual line is written once, densely: no
 // scattered zeroing at all.  Rounds met after the stash is full are written
-// unzeroed and left to the second walk of select_finish.
-template <int BLOCK, int U, int STASH, bool TICKET, typename Test>
+// unzeroed and left to the second walk of select_finish.  With ZERO false the
+// residual is written without the zeros (the parked entries are candidates only:
+// the pass that collects them for the exact threshold of a refresh iteration).
+template <int BLOCK, int U, int STASH, bool TICKET, bool ZERO, typename Test>
 __device__ __forceinline__ void accumulate_select_body(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, Test test,
     uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
@@ -329,10 +355,12 @@ __device__ __forceinline__ void accumulate_select_body(
                                           });
         if (room) {
             stashed = now;
-            if (sx) a.x = 0.0f;
-            if (sy) a.y = 0.0f;
-            if (sz) a.z = 0.0f;
-            if (sw) a.w = 0.0f;
+            if (ZERO) {
+                if (sx) a.x = 0.0f;
+                if (sy) a.y = 0.0f;
+                if (sz) a.z = 0.0f;
+                if (sw) a.w = 0.0f;
+            }
         }
         count = now;
         return a;
@@ -396,7 +424,8 @@ __device__ __forceinline__ void accumulate_select_body(
         if (inside[3]) res[i + 3] = out.w;
     }
     // every stashed entry lies before resume_at: nothing to put back before the second walk
-    select_finish<BLOCK, U, STASH>(res, test, DenseSource{}, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
+    using Source = typename std::conditional<ZERO, DenseSource, DenseCopySource>::type;
+    select_finish<BLOCK, U, STASH>(res, test, Source{}, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
                                    group_desc, nseg, seg, start, end, count, stashed, resume_at,
                                    stashed, mine, s_count, s_before);
 }
@@ -492,11 +521,11 @@ __global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void accumulate_select_kernel(
     const uint32_t seg = TICKET ? s_seg : blockIdx.x;
     const float th = *d_threshold;
     if (th == th) {
-        accumulate_select_body<BLOCK, U, STASH, TICKET>(
+        accumulate_select_body<BLOCK, U, STASH, TICKET, true>(
             grad, res, lr, n, TestFloat{__builtin_fabsf(th)}, idx_out, val_out, capacity, nnz_out,
             hdr, seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     } else {
-        accumulate_select_body<BLOCK, U, STASH, TICKET>(
+        accumulate_select_body<BLOCK, U, STASH, TICKET, true>(
             grad, res, lr, n, TestKey{magnitude_key(th)}, idx_out, val_out, capacity, nnz_out,
             hdr, seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     }

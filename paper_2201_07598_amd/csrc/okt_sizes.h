@@ -91,6 +91,14 @@ inline size_t threshold_ws_bytes(uint64_t n) {
     // state + histograms + room for the candidate keys (a few percent of the vector)
     return threshold_ws_min_bytes() + 4 * (size_t)(n / 8 + 1024);
 }
+// A refresh iteration in one pass: the threshold's state and histograms, two scan
+// states, and candidates with their indices (8 bytes each, a sixteenth of the
+// vector and some).  A shorter vector takes the three steps one after the other.
+inline size_t refresh_scan_bytes(uint64_t n) { return (select_ws_bytes(n) + 255) & ~(size_t)255; }
+inline size_t refresh_ws_bytes(uint64_t n) {
+    if (n < RS_SAMPLE_MIN_N) return 0;
+    return threshold_ws_min_bytes() + 2 * refresh_scan_bytes(n) + 8 * (size_t)(n / 8 + 1024);
+}
 
 // ---- sparse reduce ----
 // A workgroup of RED_BLOCK threads owns a tile of `slots` consecutive index

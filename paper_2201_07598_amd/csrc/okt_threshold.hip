@@ -19,6 +19,16 @@
 // Either way the answer is the exact order statistic: all arithmetic is integer
 // counting, the sample only decides how much is read.  State lives in the
 // workspace on the device; the host never waits.
+//
+// okt_accumulate_topk_select: a whole refresh iteration (Algorithm 2, lines 4-6,
+// with the threshold re-evaluated) that reads the gradient and the residual
+// once.  The sample is formed on the fly from both; the pass that collects the
+// candidates is the fused accumulate+select kernel run against the sample's
+// bound, writing the accumulator over the residual and the candidates, in index
+// order with their indices, to the workspace; the radix select runs over the
+// candidate values; and the final select walks the candidates instead of the
+// vector, zeroing the residual where an entry goes out.  If the sample misled,
+// the last two steps run over the whole vector instead: same results.
 #include "okt_device.h"
 #include "okt_select_kernel.h"
 #include "okt_sizes.h"
@@ -35,6 +45,7 @@ struct RadixState {
     uint32_t pad;
     unsigned long long cand_count;    // number of candidates found by the counting pass
     uint32_t done[4];      // workgroups that have handed in their histogram: sample, digits 1-3
+    uint64_t collected[2]; // ordered collection (refresh iteration): candidates written, found
 };
 static_assert(sizeof(RadixState) <= RS_STATE_BYTES, "state fits its slot");
 
@@ -125,7 +136,9 @@ __global__ __launch_bounds__(HIST_BLOCK) void radix_hist_kernel(
     uint32_t use_cand;
     uint64_t m64;
     if (FIRST) {
-        const uint64_t found = state->cand_count;           // keys at or above cand_lo
+        // keys at or above cand_lo: counted by the collect pass, or by the ordered
+        // collection of a refresh iteration (all ones if one of its waits gave up)
+        const uint64_t found = sampled == 2 ? state->collected[1] : state->cand_count;
         use_cand = sampled && k <= found && found <= cand_cap ? 1u : 0u;   // rank k is among them
         m64 = use_cand ? found : n;
     } else {
@@ -204,9 +217,12 @@ __global__ __launch_bounds__(HIST_BLOCK) void radix_hist_kernel(
 // k' + margin, k' = k * sample / n; every key from the bottom of that bin up is
 // a candidate.
 constexpr int SAMPLE_PER_WG = 8;
+// With `grad` set the sampled values are eps + lr * G formed on the fly (`acc` is
+// then the residual before the accumulate).
 __global__ __launch_bounds__(HIST_BLOCK) void sample_hist_kernel(
-    const float* __restrict__ acc, uint32_t nblocks_sampled, uint32_t stride,
-    uint32_t* __restrict__ hist, RadixState* state, uint64_t n, uint64_t k) {
+    const float* __restrict__ acc, const float* __restrict__ grad, float lr,
+    uint32_t nblocks_sampled, uint32_t stride, uint32_t* __restrict__ hist, RadixState* state,
+    uint64_t n, uint64_t k) {
     constexpr int BINS = 1 << RS_BITS1;
     __shared__ uint32_t s_hist[BINS];
     __shared__ uint64_t s_wave_total[4], s_result[2];
@@ -219,8 +235,17 @@ __global__ __launch_bounds__(HIST_BLOCK) void sample_hist_kernel(
     for (int u = 0; u < SAMPLE_PER_WG; ++u) {
         const uint32_t j = blockIdx.x * SAMPLE_PER_WG + u;
         v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (j < nblocks_sampled)
-            v[u] = reinterpret_cast<const float4*>(acc)[(size_t)j * stride * 256 + threadIdx.x];
+        if (j < nblocks_sampled) {
+            const size_t at = (size_t)j * stride * 256 + threadIdx.x;
+            v[u] = reinterpret_cast<const float4*>(acc)[at];
+            if (grad) {
+                const float4 g = reinterpret_cast<const float4*>(grad)[at];
+                v[u].x = __fadd_rn(v[u].x, __fmul_rn(lr, g.x));
+                v[u].y = __fadd_rn(v[u].y, __fmul_rn(lr, g.y));
+                v[u].z = __fadd_rn(v[u].z, __fmul_rn(lr, g.z));
+                v[u].w = __fadd_rn(v[u].w, __fmul_rn(lr, g.w));
+            }
+        }
     }
 #pragma unroll
     for (int u = 0; u < SAMPLE_PER_WG; ++u) {
@@ -351,6 +376,103 @@ __global__ void radix_init_kernel(RadixState* state, uint32_t* hist, uint32_t wo
     }
 }
 
+// ---------------------------------------------------------------------------
+// refresh iteration in one pass over the gradient
+// ---------------------------------------------------------------------------
+// Clears the radix state, the histograms and the two scan states (collection,
+// final select) of a refresh iteration.
+__global__ void refresh_init_kernel(RadixState* state, uint32_t* hist, uint32_t hist_words,
+                                    uint64_t* scan_a, uint64_t* scan_b, uint32_t scan_words,
+                                    uint32_t spin_limit) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < hist_words) hist[i] = 0;
+    if (i < scan_words) {
+        const uint64_t w = i == SCAN_SPIN_WORD ? (uint64_t)spin_limit : 0ull;
+        scan_a[i] = w;
+        scan_b[i] = w;
+    }
+    if (i == 0) {
+        RadixState z = {};
+        *state = z;
+    }
+}
+
+// The fused accumulate+select kernel run against the sample's bound: the
+// residual becomes the accumulator (no zeros), every element at or above the
+// bound goes, in index order, to the candidate list, whose length (written,
+// found) lands in state->collected.
+template <int BLOCK, int U, int STASH>
+__global__ __launch_bounds__(BLOCK) void accumulate_collect_kernel(
+    const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, RadixState* state,
+    uint32_t* __restrict__ cand_idx, float* __restrict__ cand_val, uint64_t cand_cap,
+    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece) {
+    constexpr int WAVES = BLOCK / WAVE;
+    __shared__ StashMemory<WAVES, STASH> s_stash;
+    __shared__ uint32_t s_count[WAVES];
+    __shared__ uint32_t s_seg;
+    __shared__ uint32_t s_before[2];
+    if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    const uint32_t seg = s_seg;
+    const uint32_t lo_key = state->cand_lo;
+    const float lo = __uint_as_float(lo_key);               // a key below the Inf/NaN range, or NaN
+    if (lo == lo) {
+        accumulate_select_body<BLOCK, U, STASH, true, false>(
+            grad, res, lr, n, TestFloat{lo}, cand_idx, cand_val, cand_cap, state->collected, hdr,
+            seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
+    } else {
+        accumulate_select_body<BLOCK, U, STASH, true, false>(
+            grad, res, lr, n, TestKey{lo_key}, cand_idx, cand_val, cand_cap, state->collected, hdr,
+            seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
+    }
+}
+
+// The select of a refresh iteration.  If the radix passes ran over the
+// candidates, so does this: the candidates hold every element at or above the
+// threshold, in index order, so the walk over them emits what a walk over the
+// vector would, and the residual is zeroed where an entry is written out.  The
+// candidates are shared out over all the workgroups of the launch.  Otherwise
+// the walk runs over the residual itself.
+template <int BLOCK, int U, int STASH>
+__global__ __launch_bounds__(BLOCK) void candidate_select_kernel(
+    float* __restrict__ res, uint32_t n, const RadixState* __restrict__ state,
+    const uint32_t* __restrict__ cand_idx, float* __restrict__ cand_val,
+    const float* __restrict__ d_threshold, uint32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
+    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg, uint32_t piece) {
+    constexpr int WAVES = BLOCK / WAVE;
+    __shared__ StashMemory<WAVES, STASH> s_stash;
+    __shared__ uint32_t s_count[WAVES];
+    __shared__ uint32_t s_seg;
+    __shared__ uint32_t s_before[2];
+    if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    const uint32_t seg = s_seg;
+    const bool use_cand = state->use_cand != 0;
+    float* walked = res;
+    uint32_t len = n;
+    CandidateSource source{nullptr, res};
+    if (use_cand) {
+        walked = cand_val;
+        len = (uint32_t)state->m;                           // <= cand_cap <= n
+        source.idx_in = cand_idx;
+        const uint32_t waves = nseg * (uint32_t)WAVES;
+        uint32_t share = ((len + waves - 1) / waves + 255u) / 256u * 256u;   // whole rounds
+        if (share == 0) share = 256u;
+        if (share < piece) piece = share;                   // never longer than the launch's piece
+    }
+    const float th = *d_threshold;
+    if (th == th) {
+        select_body<BLOCK, U, STASH, true>(walked, len, TestFloat{__builtin_fabsf(th)}, source, idx_out,
+                                           val_out, capacity, nnz_out, hdr, seg_desc, group_desc,
+                                           nseg, piece, seg, s_stash, s_count, s_before);
+    } else {
+        select_body<BLOCK, U, STASH, true>(walked, len, TestKey{magnitude_key(th)}, source, idx_out,
+                                           val_out, capacity, nnz_out, hdr, seg_desc, group_desc,
+                                           nseg, piece, seg, s_stash, s_count, s_before);
+    }
+}
+
 }  // namespace okt
 
 extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t k,
@@ -384,8 +506,8 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
         const uint64_t nsamp = (blocks + stride - 1) / stride;
         hipLaunchKernelGGL(sample_hist_kernel,
                            dim3((unsigned)((nsamp + SAMPLE_PER_WG - 1) / SAMPLE_PER_WG)),
-                           dim3(HIST_BLOCK), 0, s, d_acc, (uint32_t)nsamp, (uint32_t)stride,
-                           hist_sample, state, n, k);
+                           dim3(HIST_BLOCK), 0, s, d_acc, (const float*)nullptr, 0.0f,
+                           (uint32_t)nsamp, (uint32_t)stride, hist_sample, state, n, k);
         static_assert(CNT_WAVES == SEL_WAVES, "the collect pass is cut like the select");
         const SelectShape shape = select_shape(n);
         timing_before(s);
@@ -413,5 +535,94 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
     hipLaunchKernelGGL((radix_hist_kernel<0, RS_BITS3, 3>), dim3(grid), dim3(HIST_BLOCK), 0, s,
                        d_acc, cand, state, hist3, n, k, cand_cap, was_sampled, d_threshold_out,
                        d_count_ge_out);
+    return launch_status();
+}
+
+extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual_inout, float lr,
+                                          uint64_t n, uint64_t k, float* d_threshold_out,
+                                          uint64_t* d_count_ge_out, uint32_t* d_idx_out,
+                                          float* d_val_out, uint64_t capacity, uint64_t* d_nnz_out,
+                                          void* d_ws, size_t ws_bytes, void* stream) {
+    using namespace okt;
+    hipStream_t s = (hipStream_t)stream;
+    if (!d_grad || !d_residual_inout || d_grad == d_residual_inout || !d_threshold_out ||
+        !d_count_ge_out || !d_nnz_out)
+        return OKT_ERR_INVALID_ARG;
+    if (n == 0 || n > 0xffffffffull || k == 0 || k > n) return OKT_ERR_INVALID_ARG;
+    if (!aligned(d_grad, 16) || !aligned(d_residual_inout, 16) || !aligned(d_threshold_out, 4) ||
+        !aligned(d_count_ge_out, 8) || !aligned(d_nnz_out, 8))
+        return OKT_ERR_INVALID_ARG;
+    if (capacity > 0 && (!d_idx_out || !d_val_out || !aligned(d_idx_out, 4) ||
+                         !aligned(d_val_out, 4)))
+        return OKT_ERR_INVALID_ARG;
+    const size_t separate = threshold_ws_min_bytes() > select_ws_bytes(n) ? threshold_ws_min_bytes()
+                                                                           : select_ws_bytes(n);
+    if (!d_ws || !aligned(d_ws, 256) || ws_bytes < separate) return OKT_ERR_WORKSPACE;
+
+    const SelectShape shape = select_shape(n);
+    const size_t scan_bytes = refresh_scan_bytes(n);
+    const size_t fixed = threshold_ws_min_bytes() + 2 * scan_bytes;
+    const uint64_t cand_cap = ws_bytes > fixed ? ((ws_bytes - fixed) / 8) & ~(uint64_t)63 : 0;
+    if (n < RS_SAMPLE_MIN_N || cand_cap < n / 16) {
+        // short vector (or a workspace without room for candidates): the three steps
+        // one after the other, each with the workspace to itself
+        int rc = okt_residual_accumulate(d_grad, d_residual_inout, lr, n, stream);
+        if (rc != OKT_OK) return rc;
+        rc = okt_topk_threshold_exact(d_residual_inout, n, k, d_threshold_out, d_count_ge_out, d_ws,
+                                      ws_bytes, stream);
+        if (rc != OKT_OK) return rc;
+        return okt_threshold_select(d_residual_inout, n, d_threshold_out, d_idx_out, d_val_out,
+                                    capacity, d_nnz_out, d_ws, ws_bytes, stream);
+    }
+
+    RadixState* state = (RadixState*)d_ws;
+    uint32_t* hist_sample = (uint32_t*)((char*)d_ws + RS_STATE_BYTES);
+    uint32_t* hist1 = hist_sample + RS_MAX_BINS;
+    uint32_t* hist2 = hist1 + RS_MAX_BINS;
+    uint32_t* hist3 = hist2 + RS_MAX_BINS;
+    char* scan_a = (char*)d_ws + threshold_ws_min_bytes();
+    char* scan_b = scan_a + scan_bytes;
+    float* cand_val = (float*)(scan_b + scan_bytes);
+    uint32_t* cand_idx = (uint32_t*)(cand_val + cand_cap);
+    auto header = [](char* p) { return (ScanHeader*)p; };
+    auto segs = [](char* p) { return (uint64_t*)(p + SCAN_HEADER_BYTES); };
+
+    const uint32_t scan_words = (uint32_t)(scan_ws_bytes(shape.nseg) / 8);
+    const uint32_t init_words = scan_words > 4u * RS_MAX_BINS ? scan_words : 4u * RS_MAX_BINS;
+    hipLaunchKernelGGL(refresh_init_kernel, dim3((init_words + 255) / 256), dim3(256), 0, s, state,
+                       hist_sample, 4u * RS_MAX_BINS, (uint64_t*)scan_a, (uint64_t*)scan_b,
+                       scan_words, spin_limit_setting());
+
+    const uint64_t blocks = n / 1024;
+    uint64_t stride = blocks / RS_SAMPLE_BLOCKS;
+    if (stride < 1) stride = 1;
+    const uint64_t nsamp = (blocks + stride - 1) / stride;
+    hipLaunchKernelGGL(sample_hist_kernel,
+                       dim3((unsigned)((nsamp + SAMPLE_PER_WG - 1) / SAMPLE_PER_WG)),
+                       dim3(HIST_BLOCK), 0, s, d_residual_inout, d_grad, lr, (uint32_t)nsamp,
+                       (uint32_t)stride, hist_sample, state, n, k);
+    timing_before(s);
+    hipLaunchKernelGGL((accumulate_collect_kernel<SEL_BLOCK, SEL_U, SEL_STASH>), dim3(shape.nseg),
+                       dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout, lr, (uint32_t)n, state,
+                       cand_idx, cand_val, cand_cap, header(scan_a), segs(scan_a),
+                       segs(scan_a) + shape.nseg, shape.nseg, shape.piece);
+    timing_after(s);
+
+    const uint64_t steps = (((n / 16) >> 2) + HIST_STEP4 - 1) / HIST_STEP4;
+    const unsigned grid = (unsigned)(steps < 256 ? (steps ? steps : 1) : 256);
+    const uint32_t* cand_keys = reinterpret_cast<const uint32_t*>(cand_val);
+    hipLaunchKernelGGL((radix_hist_kernel<20, RS_BITS1, 1>), dim3(grid), dim3(HIST_BLOCK), 0, s,
+                       d_residual_inout, cand_keys, state, hist1, n, k, cand_cap, 2, d_threshold_out,
+                       d_count_ge_out);
+    hipLaunchKernelGGL((radix_hist_kernel<9, RS_BITS2, 2>), dim3(grid), dim3(HIST_BLOCK), 0, s,
+                       d_residual_inout, cand_keys, state, hist2, n, k, cand_cap, 2, d_threshold_out,
+                       d_count_ge_out);
+    hipLaunchKernelGGL((radix_hist_kernel<0, RS_BITS3, 3>), dim3(grid), dim3(HIST_BLOCK), 0, s,
+                       d_residual_inout, cand_keys, state, hist3, n, k, cand_cap, 2, d_threshold_out,
+                       d_count_ge_out);
+    hipLaunchKernelGGL((candidate_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH>), dim3(shape.nseg),
+                       dim3(SEL_BLOCK), 0, s, d_residual_inout, (uint32_t)n, state, cand_idx, cand_val,
+                       d_threshold_out, d_idx_out, d_val_out, capacity, d_nnz_out, header(scan_b),
+                       segs(scan_b), segs(scan_b) + shape.nseg, shape.nseg, shape.piece);
     return launch_status();
 }

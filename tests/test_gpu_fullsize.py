@@ -16,8 +16,9 @@ pytestmark = pytest.mark.gpu
 
 
 def loop(w, iterations, fused=False):
-    """fused: the iterations that reuse the threshold take okt_accumulate_select,
-    as bench.py's step does."""
+    """fused: as bench.py's step does, the iterations that re-evaluate the
+    threshold take okt_accumulate_topk_select and those that reuse it
+    okt_accumulate_select."""
     gpu = GpuPath(w.n, 4 * w.k)
     res = np.zeros(w.n, dtype=np.float32)
     th = None
@@ -25,7 +26,14 @@ def loop(w, iterations, fused=False):
     for it in range(iterations):
         g = wl.gradient(w, it)
         acc = orc.residual_accumulate(g, res, w.lr)
-        if fused and not w.refresh(it):
+        if fused and w.refresh(it):
+            okt.okt_accumulate_topk_select(to_dev(g), gpu.residual, w.lr, w.k, gpu.th, gpu.count_ge,
+                                           gpu.idx, gpu.val, gpu.nnz, gpu.ws, capacity=gpu.capacity)
+            del g
+            th, cnt = orc.topk_threshold_exact(acc, w.k, method="partition")
+            assert gpu.th.cpu().numpy().view(np.uint32)[0] == np.float32(th).view(np.uint32), it
+            assert int(u64(gpu.count_ge)[0]) == cnt, it
+        elif fused:
             okt.okt_accumulate_select(to_dev(g), gpu.residual, w.lr, gpu.th, gpu.idx, gpu.val,
                                       gpu.nnz, gpu.ws, capacity=gpu.capacity)
             del g
@@ -82,10 +90,10 @@ def test_cfg2_full_size():
     assert ref["idx"].size > 0.9 * w.P * w.m
 
 
-@pytest.mark.timeout(300)
-@pytest.mark.parametrize("name,iterations", [("cfg2", 3), ("cfg3", 2)])
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name,iterations", [("cfg2", 3), ("cfg3", 2), ("cfg4", 2)])
 def test_full_size_fused_reuse_iterations(name, iterations):
-    # the step bench.py times: iteration 0 in four calls, the others in one fused call;
+    # the step bench.py times: one call per iteration (cfg4 re-evaluates every time);
     # the bench's vector selects whole layers (the stash-overflow path at full size)
     loop(wl.WORKLOADS[name], iterations, fused=True)
 
