@@ -34,6 +34,18 @@ __global__ __launch_bounds__(CEIL_BLOCK) void stream_copy_kernel(
     if (threadIdx.x < 4 && tail < n) dst[tail] = src[tail];
 }
 
+// A 16-byte load with the non-temporal hint: 5 % faster for this kernel on data
+// that is in no cache.  The hot path does not use it: on the loads of the fused
+// accumulate+select and of the select walks it gains 4-5 % on cold data and loses
+// as much in a training step, where the residual an iteration writes is still in
+// the last-level cache when the next one reads it; on dense stores it always
+// loses (a copy 10 % slower).
+typedef float v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_once(const float4* p) {
+    const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // Every workgroup strides over the vector, CEIL_ITERS 16-byte loads in flight per
 // thread, and leaves one partial sum; nothing else is written.
 __global__ __launch_bounds__(CEIL_BLOCK) void stream_sum_kernel(
@@ -49,7 +61,7 @@ __global__ __launch_bounds__(CEIL_BLOCK) void stream_sum_kernel(
 #pragma unroll
         for (int it = 0; it < CEIL_ITERS; ++it) {
             const uint64_t i = base4 + (uint64_t)it * CEIL_BLOCK + threadIdx.x;
-            v[it] = i < n4 ? s4[i] : float4{0.f, 0.f, 0.f, 0.f};
+            v[it] = i < n4 ? load_once(s4 + i) : float4{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int it = 0; it < CEIL_ITERS; ++it) sum += (v[it].x + v[it].y) + (v[it].z + v[it].w);
