@@ -278,3 +278,55 @@ def test_random_vectors_through_the_sampled_threshold(seed):
             where = f"seed {seed} case {case}: n={n} kind={kind} k={k} ws={ws.numel()}"
             assert th.cpu().numpy().view(np.uint32)[0] == np.float32(rth).view(np.uint32), where
             assert int(u64(cnt)[0]) == rcnt, where
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("seed", range(3))
+def test_random_refresh_iterations_in_one_call(seed):
+    """okt_accumulate_topk_select on long vectors of the same kinds, with a
+    residual of a random scale, ranks from 1 to n, outputs that fill up, and
+    workspaces from the smallest to the full one, against the oracle's accumulate,
+    exact threshold and select applied in turn."""
+    rng = np.random.default_rng(9300 + seed)
+    for case in range(4):
+        n = int(rng.integers(4_194_304 - 5, 12_000_000))
+        kind = int(rng.integers(0, 6))
+        g = rng.standard_normal(n, dtype=np.float32) * np.float32(1e-3)
+        if kind == 1:                                # layers of different scale
+            cuts = np.sort(rng.integers(0, n, 8))
+            for a, b in zip(cuts[:-1], cuts[1:]):
+                g[a:b] *= np.float32(10.0 ** rng.integers(-4, 4))
+        if kind == 2:                                # the large values sit in a few short blocks
+            g *= np.float32(1e-3)
+            for _ in range(int(rng.integers(1, 6))):
+                a = int(rng.integers(0, n))
+                b = min(n, a + int(rng.integers(1, 3000)))
+                g[a:b] = rng.standard_normal(b - a).astype(np.float32)
+        if kind == 3:                                # five distinct values
+            g = rng.choice(np.array([0.0, 1e-3, -1e-3, 2e-3, 5e-4], dtype=np.float32), n)
+        if kind == 4:                                # nearly all zero
+            g[rng.random(n) < 0.999] = 0.0
+        if kind == 5:                                # one exponent: the first digit says little
+            g = np.abs(g) + np.float32(1.0)
+        e = rng.standard_normal(n, dtype=np.float32) * np.float32(rng.choice([0.0, 1e-4, 1e-2]))
+        lr = float(rng.choice([1.0, 0.5, -0.25]))
+        acc = orc.residual_accumulate(g, e, lr)
+        d_g = to_dev(g)
+        full = okt.okt_workspace_bytes(n, 0)
+        for k in (int(rng.integers(1, n + 1)), max(1, n // 1000), max(1, n // 100)):
+            ws = workspace(full if rng.random() < 0.7 else int(rng.choice([70_000, 300_000, 4_000_000])))
+            rth, rcnt = orc.topk_threshold_exact(acc, k, method="partition")
+            cap = int(rng.choice([rcnt, rcnt + 5, rcnt // 2, 0]))
+            ridx, rval, rres, total = orc.threshold_select(acc, rth, capacity=cap)
+            d_e = to_dev(e)
+            th = torch.zeros(1, device=DEV)
+            cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+            idx = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=DEV)
+            val = torch.zeros(max(cap, 1), dtype=torch.float32, device=DEV)
+            nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+            okt.okt_accumulate_topk_select(d_g, d_e, lr, k, th, cnt, idx, val, nnz, ws, capacity=cap)
+            where = f"seed {seed} case {case}: n={n} kind={kind} k={k} cap={cap} ws={ws.numel()}"
+            assert th.cpu().numpy().view(np.uint32)[0] == np.float32(rth).view(np.uint32), where
+            assert int(u64(cnt)[0]) == rcnt == total, where
+            assert selected_matches(idx, val, nnz, ridx, rval, total), where
+            assert bits_equal(d_e.cpu().numpy(), rres), where

@@ -155,3 +155,43 @@ def test_argument_errors_are_caught_on_the_host():
     okt.okt_accumulate_topk_select(g, e, 1.0, 5, th, cnt, idx, val, nnz, ws)
     torch.cuda.synchronize()
     assert int(u64(nnz)[1]) >= 5
+
+
+def test_bounded_waits_that_give_up_are_reported():
+    """With the waits between workgroups limited to one poll (a test hook) the call
+    never hangs: if the collection of the candidates gives up, the whole-vector
+    path takes over, so the threshold and its count stay exact; if the final
+    select gives up, its counts read UINT64_MAX, as okt_threshold_select's do."""
+    n, k = 6_000_011, 60_000
+    g, e = lap(21, n), lap(22, n, 2e-3)
+    acc = orc.residual_accumulate(g, e, 0.5)
+    rth, rcnt = orc.topk_threshold_exact(acc, k, method="partition")
+    ridx, rval, rres, total = orc.threshold_select(acc, rth, capacity=2 * k)
+    bad = 0xFFFFFFFFFFFFFFFF
+    outcomes = []
+    try:
+        okt.okt_debug_spin_limit(1)
+        for rep in range(3):
+            d_g, d_e = to_dev(g), to_dev(e)
+            th = torch.zeros(1, dtype=torch.float32, device=DEV)
+            cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+            idx = torch.full((2 * k,), -1, dtype=torch.int32, device=DEV)
+            val = torch.zeros(2 * k, dtype=torch.float32, device=DEV)
+            nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+            ws = workspace(okt.okt_workspace_bytes(n, 0))
+            okt.okt_accumulate_topk_select(d_g, d_e, 0.5, k, th, cnt, idx, val, nnz, ws)
+            torch.cuda.synchronize()
+            assert th.cpu().numpy().view(np.uint32)[0] == np.float32(rth).view(np.uint32)
+            assert int(u64(cnt)[0]) == rcnt
+            c = u64(nnz)
+            if int(c[1]) == bad:
+                outcomes.append("gave up")
+                assert int(c[0]) == bad
+            else:
+                outcomes.append("completed")
+                assert (int(c[0]), int(c[1])) == (ridx.size, total)
+                assert np.array_equal(u32(idx[:total]), ridx) and bits_equal(d_e.cpu().numpy(), rres)
+    finally:
+        okt.okt_debug_spin_limit(0)
+    print(outcomes, flush=True)
+    check_refresh(g, e, 0.5, k, 2 * k)               # the limit restored: exact again
