@@ -207,3 +207,34 @@ def test_longest_vector_the_interface_allows():
     assert (emitted, gtotal) == (1000, total) and total > 1000
     assert np.array_equal(idx.astype(np.int64), pos[ridx_c]) and bits_equal(val, rval)
     assert bits_equal(gpu.residual[d_pos].cpu().numpy(), res_c)          # left untouched
+    print("select without zeroing ok", flush=True)
+
+    # a refresh iteration in one call from a fresh residual.  Some small entries are
+    # planted where the threshold's sample looks (every 4095th block of 1024 elements
+    # at this length), so that its bound is a positive value below the others and the
+    # call's one-pass path - candidates collected, selection over them - runs at this n
+    del grad
+    blocks = rng.choice(1024, 300, replace=False).astype(np.int64)
+    pos_s = blocks * ((n // 1024) // 1024) * 1024 + rng.integers(0, 1024, 300)
+    pos_s = np.setdiff1d(pos_s, pos)
+    pos2 = np.concatenate([pos, pos_s])
+    order = np.argsort(pos2, kind="stable")
+    g3_c = np.concatenate([planted(4), (0.25 + rng.random(pos_s.size) / 16).astype(np.float32)])
+    pos2, g3_c = pos2[order], g3_c[order]
+    d_pos2 = torch.from_numpy(pos2).to(DEV)
+    gpu.residual.zero_()
+    grad = torch.zeros(n, dtype=torch.float32, device=DEV)
+    grad[d_pos2] = torch.from_numpy(g3_c).to(DEV)
+    okt.okt_accumulate_topk_select(grad, gpu.residual, lr, k, gpu.th, gpu.count_ge, gpu.idx, gpu.val,
+                                   gpu.nnz, gpu.ws, capacity=gpu.capacity)
+    acc_c = orc.residual_accumulate(g3_c, np.zeros_like(g3_c), lr)
+    th, cnt = orc.topk_threshold_exact(acc_c, k)
+    assert gpu.th.cpu().numpy().view(np.uint32)[0] == np.float32(th).view(np.uint32)
+    assert int(u64(gpu.count_ge)[0]) == cnt == k
+    ridx_c, rval, res_c, total = orc.threshold_select(acc_c, th, capacity=gpu.capacity)
+    idx, val, emitted, gtotal = gpu.selected()
+    assert (emitted, gtotal) == (ridx_c.size, total) == (k, k)
+    assert np.array_equal(idx.astype(np.int64), pos2[ridx_c]) and bits_equal(val, rval)
+    assert bits_equal(gpu.residual[d_pos2].cpu().numpy(), res_c)
+    assert int(torch.count_nonzero(gpu.residual)) == np.count_nonzero(res_c)
+    print("refresh iteration in one call ok", flush=True)
