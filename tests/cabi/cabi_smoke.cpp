@@ -4,8 +4,9 @@
 // whose expected results follow from the definitions by plain host code: the
 // k-th largest magnitude by std::nth_element, the selection by a filter, the
 // quantile boundaries by indexing, and a reduce of the selection with itself
-// (every value doubled, exactly).  Prints "cabi smoke ok" and exits 0, or says
-// what differs and exits 1.
+// (every value doubled, exactly); then the first three calls again as the one
+// call okt_accumulate_topk_select, which must give the same bits.  Prints
+// "cabi smoke ok" and exits 0, or says what differs and exits 1.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -48,7 +49,7 @@ static int upload(T** d, const std::vector<T>& h) {
 }
 
 int main() {
-    const uint64_t n = 1000003, k = 5000;
+    const uint64_t n = 4500003, k = 20000;     // long enough for the one-pass refresh iteration
     const uint32_t R = 4;
     std::vector<float> g(n), zero(n, 0.0f);
     uint32_t state = 12345u;
@@ -170,6 +171,35 @@ int main() {
             std::printf("reduce differs at %llu\n", (unsigned long long)j);
             return 1;
         }
+    }
+    // ---- the iteration again in one call: the same threshold, selection and residual ----
+    uint32_t* d_idx2 = nullptr;
+    float* d_val2 = nullptr;
+    HIP_OK(hipMalloc((void**)&d_idx2, cap * 4));
+    HIP_OK(hipMalloc((void**)&d_val2, cap * 4));
+    HIP_OK(hipMemset(d_res, 0, n * 4));
+    HIP_OK(hipMemset(d_ws, 0x5A, ws_bytes));
+    OKT_OK_(okt_accumulate_topk_select(d_g, d_res, 1.0f, n, k, d_th, d_cnt, d_idx2, d_val2, cap, d_nnz,
+                                       d_ws, ws_bytes, nullptr));
+    HIP_OK(hipDeviceSynchronize());
+    float th2;
+    uint64_t cnt2, nnz2[2];
+    HIP_OK(hipMemcpy(&th2, d_th, 4, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(&cnt2, d_cnt, 8, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(nnz2, d_nnz, 16, hipMemcpyDeviceToHost));
+    std::vector<uint32_t> idx2(idx.size());
+    std::vector<float> val2(idx.size()), res2(n);
+    if (std::memcmp(&th2, &th, 4) != 0 || cnt2 != cnt || nnz2[0] != nnz[0] || nnz2[1] != nnz[1]) {
+        std::printf("one-call iteration: threshold or counts differ\n");
+        return 1;
+    }
+    HIP_OK(hipMemcpy(idx2.data(), d_idx2, idx2.size() * 4, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(val2.data(), d_val2, val2.size() * 4, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(res2.data(), d_res, n * 4, hipMemcpyDeviceToHost));
+    if (idx2 != idx || std::memcmp(val2.data(), val.data(), val.size() * 4) != 0 ||
+        std::memcmp(res2.data(), res.data(), n * 4) != 0) {
+        std::printf("one-call iteration: selection or residual differs\n");
+        return 1;
     }
     std::printf("cabi smoke ok: n=%llu k=%llu selected=%zu region=[%u,%u) reduced=%llu version=%d\n",
                 (unsigned long long)n, (unsigned long long)k, idx.size(), lo, hi,
