@@ -100,6 +100,11 @@ def test_sample_that_misleads_and_ties():
     # every value equal: the candidates are the whole vector and do not fit
     same = np.full(4_500_000, 0.25, dtype=np.float32)
     assert check_refresh(same, np.zeros_like(same), 1.0, 45_000, 4_500_000) == 4_500_000
+    # the same with pieces longer than a wave's stash (the whole-vector select then
+    # walks part of every piece twice), once with room for everything, once cut short
+    same = np.full(9_000_000, -0.25, dtype=np.float32)
+    assert check_refresh(same, np.zeros_like(same), 1.0, 90_000, 9_000_000) == 9_000_000
+    assert check_refresh(same, np.zeros_like(same), 1.0, 90_000, 5_000_001) == 9_000_000
     # heavy ties around rank k: all of them are selected
     tied = lap(8, n)
     tied[100_000:400_000] = np.float32(3e-3)
