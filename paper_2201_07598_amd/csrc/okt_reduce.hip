@@ -187,7 +187,8 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     const uint32_t* __restrict__ lo_hi, uint32_t lo0,
     uint32_t hi0, uint32_t P, uint32_t max_width, uint32_t slots, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
-    float* __restrict__ dense_out, char* ws, uint32_t ws_region_bytes, uint32_t table_offset) {
+    float* __restrict__ dense_out, char* ws, uint32_t ws_region_bytes, uint32_t table_offset,
+    uint32_t span_blocks) {
     constexpr uint32_t WORDS_MAX = S_MAX / 32;
     static_assert(S_MAX <= 65536, "slots and ranks are kept in 16 bits");
     __shared__ double s_sum[C];
@@ -241,12 +242,16 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
 
     // Hands every entry of the tile to body(index, value).  Contributions are
     // taken RED_CHUNKS at a time; slice q of a sweep belongs to wave q mod WAVES,
-    // whose lanes read it 64 consecutive entries at a time (coalesced).  A wave
-    // first names up to RED_UNROLL such blocks, across its slices, then issues all
-    // their loads, then consumes them: enough loads in flight to cover the memory
-    // latency, no per-entry search, and only wave-uniform bookkeeping.
-    auto for_each_entry = [&](auto with_values, auto&& body) {
+    // whose lanes read it in spans of G x 64 consecutive entries (G coalesced loads
+    // that share one address and one piece of bookkeeping).  A wave first names up
+    // to UNITS such spans, across its slices, then issues all their loads, then
+    // consumes them: enough loads in flight to cover the memory latency, no
+    // per-entry search, and only wave-uniform bookkeeping.  Long slices (few
+    // contributions) take G = 4 or 2; short ones G = 1, where a longer span would
+    // be mostly empty (the host picks from the expected slice length).
+    auto for_each_entry_in = [&](auto with_values, auto span, auto units, auto&& body) {
         constexpr bool VALUES = decltype(with_values)::value;
+        constexpr int G = decltype(span)::value, UNITS = decltype(units)::value;
         for (uint32_t p0 = 0; p0 < P; p0 += RED_CHUNKS) {
             const uint32_t np = (P - p0) < (uint32_t)RED_CHUNKS ? (P - p0) : (uint32_t)RED_CHUNKS;
             // Every thread must take the same branch here.  The note of what is
@@ -265,38 +270,56 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
                 if (tid == 0) s_loaded_p0 = p0;
                 __syncthreads();
             }
-            uint32_t q = (uint32_t)__builtin_amdgcn_readfirstlane(wave), o = 0;   // next block: slice q, entries o .. o+63
+            uint32_t q = (uint32_t)__builtin_amdgcn_readfirstlane(wave), o = 0;   // next span: slice q, from entry o
             while (q < np) {
-                uint64_t pos[RED_UNROLL];
-                bool live[RED_UNROLL];
+                uint64_t pos[UNITS];
+                uint32_t left[UNITS];            // entries of the slice from the span's start on (wave-uniform)
 #pragma unroll
-                for (int k = 0; k < RED_UNROLL; ++k) {
+                for (int u = 0; u < UNITS; ++u) {
                     // skip empty slices
                     while (q < np && s_len[q] == 0) q += RED_WAVES;
                     const bool have = q < np;
                     const uint32_t len =
                         have ? (uint32_t)__builtin_amdgcn_readfirstlane(s_len[q]) : 0u;
-                    live[k] = have && o + lane < len;
-                    pos[k] = have ? s_start[q] + o + lane : 0;
+                    left[u] = have ? len - o : 0u;
+                    pos[u] = have ? s_start[q] + o + lane : 0;
                     if (have) {
-                        o += WAVE;
+                        o += G * WAVE;
                         if (o >= len) { q += RED_WAVES; o = 0; }
                     }
                 }
-                uint32_t index[RED_UNROLL];
-                float value[RED_UNROLL];
+                uint32_t index[UNITS][G];
+                float value[UNITS][G];
 #pragma unroll
-                for (int k = 0; k < RED_UNROLL; ++k) {
-                    if (live[k]) {
-                        index[k] = idx_cat[pos[k]];
-                        if (VALUES) value[k] = val_cat[pos[k]];
+                for (int u = 0; u < UNITS; ++u) {
+#pragma unroll
+                    for (int j = 0; j < G; ++j) {
+                        if ((uint32_t)lane + (uint32_t)(j * WAVE) < left[u]) {
+                            index[u][j] = idx_cat[pos[u] + j * WAVE];
+                            if (VALUES) value[u][j] = val_cat[pos[u] + j * WAVE];
+                        }
                     }
                 }
 #pragma unroll
-                for (int k = 0; k < RED_UNROLL; ++k)
-                    if (live[k]) body(index[k], VALUES ? value[k] : 0.0f);
+                for (int u = 0; u < UNITS; ++u) {
+#pragma unroll
+                    for (int j = 0; j < G; ++j)
+                        if ((uint32_t)lane + (uint32_t)(j * WAVE) < left[u])
+                            body(index[u][j], VALUES ? value[u][j] : 0.0f);
+                }
             }
         }
+    };
+    auto for_each_entry = [&](auto with_values, auto&& body) {
+        if (span_blocks == 4)
+            for_each_entry_in(with_values, std::integral_constant<int, 4>{},
+                              std::integral_constant<int, 3>{}, body);
+        else if (span_blocks == 2)
+            for_each_entry_in(with_values, std::integral_constant<int, 2>{},
+                              std::integral_constant<int, 6>{}, body);
+        else
+            for_each_entry_in(with_values, std::integral_constant<int, 1>{},
+                              std::integral_constant<int, RED_UNROLL>{}, body);
     };
     using Yes = std::true_type;      // sweep needs the values too
     using No = std::false_type;      // sweep needs the indices only
@@ -464,6 +487,10 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
                            max_width, slots, (char*)d_ws, (uint32_t)region_bytes, table_offset,
                            spin_limit_setting());
     }
+    // entries a contribution is expected to have in a tile: longer slices are read
+    // in spans of two or four blocks of 64
+    const uint64_t per_slice = capacity / tiles / P;
+    const uint32_t span_blocks = per_slice >= 128 ? 4u : per_slice >= 64 ? 2u : 1u;
     timing_before(s);
     auto* tile_kernel = shape.kind == RED_SPARSE  ? reduce_tile_kernel<RED_C_SPARSE, RED_S_SPARSE>
                         : shape.kind == RED_DENSE ? reduce_tile_kernel<RED_C_DENSE, RED_C_DENSE>
@@ -472,7 +499,7 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
                        d_idx_cat, d_val_cat, d_seg_begin, seg_stride, d_lo_hi, lo, hi, P, max_width,
                        slots,
                        d_idx_out, d_val_out, capacity, d_nnz_out, d_dense, (char*)d_ws,
-                       (uint32_t)region_bytes, table_offset);
+                       (uint32_t)region_bytes, table_offset, span_blocks);
     timing_after(s);
     return launch_status();
 }

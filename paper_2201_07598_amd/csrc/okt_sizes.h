@@ -117,7 +117,7 @@ inline size_t refresh_ws_bytes(uint64_t n) {
 #define OKT_RED_UNROLL 10
 #endif
 constexpr int RED_BLOCK = OKT_RED_BLOCK;
-constexpr int RED_UNROLL = OKT_RED_UNROLL;      // entries a thread keeps in flight
+constexpr int RED_UNROLL = OKT_RED_UNROLL;      // blocks of 64 entries a wave keeps in flight (short slices)
 constexpr uint32_t RED_C = OKT_RED_C;           // accumulators per tile and round
 #ifndef OKT_RED_S_MAX
 #define OKT_RED_S_MAX 32768
