@@ -88,6 +88,15 @@ def test_argument_errors_are_found_on_the_host():
     assert lib.okt_sparse_reduce_segments(fake, fake, fake, null, 4, 0, 10, fake, fake, 4, fake, null, fake, 1 << 20, null) == INVALID
     assert lib.okt_sparse_reduce_segments(fake, fake, fake, fake, 4, 20, 10, fake, fake, 4, fake, null, fake, 1 << 20, null) == INVALID
     assert lib.okt_sparse_reduce_segments(fake, fake, fake, fake, 4, 0, 1 << 20, fake, fake, 4, fake, null, fake, 64, null) == WORKSPACE
+    # okt_accumulate_topk_select(grad, res, lr, n, k, th, cnt, idx, val, capacity, nnz, ws, ws_bytes, stream)
+    assert lib.okt_accumulate_topk_select(fake, ctypes.c_void_p(0x2000), 1.0, 10, 0, fake, fake, fake, fake, 4, fake, fake, 1 << 20, null) == INVALID   # k = 0
+    assert lib.okt_accumulate_topk_select(fake, ctypes.c_void_p(0x2000), 1.0, 10, 11, fake, fake, fake, fake, 4, fake, fake, 1 << 20, null) == INVALID  # k > n
+    assert lib.okt_accumulate_topk_select(fake, ctypes.c_void_p(0x2000), 1.0, 0, 1, fake, fake, fake, fake, 4, fake, fake, 1 << 20, null) == INVALID    # n = 0
+    assert lib.okt_accumulate_topk_select(fake, fake, 1.0, 10, 5, fake, fake, fake, fake, 4, fake, fake, 1 << 20, null) == INVALID                      # grad is the residual
+    assert lib.okt_accumulate_topk_select(fake, odd, 1.0, 10, 5, fake, fake, fake, fake, 4, fake, fake, 1 << 20, null) == INVALID
+    assert lib.okt_accumulate_topk_select(fake, ctypes.c_void_p(0x2000), 1.0, 10, 5, fake, fake, null, fake, 4, fake, fake, 1 << 20, null) == INVALID   # capacity without idx_out
+    assert lib.okt_accumulate_topk_select(fake, ctypes.c_void_p(0x2000), 1.0, 10, 5, fake, fake, fake, fake, 4, fake, fake, 4096, null) == WORKSPACE
+    assert lib.okt_accumulate_topk_select(fake, ctypes.c_void_p(0x2000), 1.0, 10, 5, fake, fake, fake, fake, 4, fake, null, 1 << 20, null) == WORKSPACE
     assert lib.okt_stream_copy(null, null, 0, null) == 0                                 # n = 0: no-op
     assert lib.okt_stream_copy(fake, odd, 8, null) == INVALID
     assert lib.okt_stream_copy(fake, fake, 1 << 32, null) == INVALID
