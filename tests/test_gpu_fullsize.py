@@ -10,7 +10,7 @@ import paper_2201_07598_amd as okt
 import workloads as wl
 from oracle import okt_oracle as orc
 from tests.okt_harness import (DEV, GpuPath, bits_equal, gpu_reduce, reduce_tolerance, to_dev,
-                               u32, u64)
+                               u32, u64, workspace)
 
 pytestmark = pytest.mark.gpu
 
@@ -96,6 +96,56 @@ def test_full_size_fused_reuse_iterations(name, iterations):
     # the step bench.py times: one call per iteration (cfg4 re-evaluates every time);
     # the bench's vector selects whole layers (the stash-overflow path at full size)
     loop(wl.WORKLOADS[name], iterations, fused=True)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["cfg2", "cfg5"])
+def test_reduce_batch_at_the_size_the_bench_times(name):
+    """The batched reduce as bench.py launches it: B regions of the workload's
+    shape in one call, more than 1 GB of input (490 regions at cfg2).  Every
+    region's count is checked against the union size of its index pattern, and
+    sampled regions - the first, the last, some in between - entry by entry
+    against the oracle."""
+    w = wl.WORKLOADS[name]
+    P, m, width = w.P, w.m, w.n // w.P
+    E1 = P * m
+    B = int(1.0e9 // (8 * E1)) + 1
+    base_sets = min(B, 32)
+    sets = [wl.contributions(w, 0, width, stream=1000 + s) for s in range(base_sets)]
+    assert all(ci.size == E1 for ci, _, _ in sets)
+    idx_cat = np.empty(B * E1, dtype=np.uint32)
+    off = np.empty(B * (P + 1), dtype=np.uint64)
+    lohi = np.empty(2 * B, dtype=np.uint32)
+    for j in range(B):
+        ci, _, co = sets[j % base_sets]
+        rlo = j * width
+        if rlo + width > 0xFFFFFFFF:
+            rlo = (j % 16) * width
+        idx_cat[j * E1:(j + 1) * E1] = ci + np.uint32(rlo)
+        off[j * (P + 1):(j + 1) * (P + 1)] = co + np.uint64(j * E1)
+        lohi[2 * j], lohi[2 * j + 1] = rlo, rlo + width
+    val_cat = np.random.default_rng(4242).standard_normal(B * E1, dtype=np.float32) * np.float32(1e-3)
+    out_idx = torch.full((B * E1,), -1, dtype=torch.int32, device=DEV)
+    out_val = torch.zeros(B * E1, dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2 * B, dtype=torch.int64, device=DEV)
+    ws = workspace(okt.okt_sparse_reduce_batch_workspace_bytes(B, P, width))
+    okt.okt_sparse_reduce_batch(to_dev(idx_cat), to_dev(val_cat), to_dev(off), to_dev(lohi), B, P,
+                                width, out_idx, out_val, E1, nnz, ws)
+    torch.cuda.synchronize()
+    counts = u64(nnz).reshape(B, 2)
+    unions = [np.unique(ci).size for ci, _, _ in sets]
+    assert np.array_equal(counts[:, 0], counts[:, 1])
+    assert np.array_equal(counts[:, 1], np.array([unions[j % base_sets] for j in range(B)], dtype=np.uint64))
+    print(f"{name}: B={B} regions, {B * E1} entries in, {int(counts[:, 1].sum())} out", flush=True)
+    for j in sorted({0, 1, base_sets - 1, base_sets, B // 2, B - 2, B - 1}):
+        lo, hi = int(lohi[2 * j]), int(lohi[2 * j + 1])
+        sl = slice(j * E1, (j + 1) * E1)
+        ref = orc.sparse_reduce(idx_cat[sl], val_cat[sl], off[j * (P + 1):(j + 1) * (P + 1)] - np.uint64(j * E1), lo, hi)
+        U = ref["idx"].size
+        assert U == int(counts[j, 1]), j
+        assert np.array_equal(u32(out_idx[j * E1:j * E1 + U]), ref["idx"]), j
+        err = np.abs(out_val[j * E1:j * E1 + U].cpu().numpy().astype(np.float64) - ref["val"])
+        assert np.all(err <= reduce_tolerance(ref)), j
 
 
 @pytest.mark.timeout(300)
