@@ -271,7 +271,7 @@ __global__ __launch_bounds__(HIST_BLOCK) void sample_hist_kernel(
     if (threadIdx.x == 0) state->cand_lo = (uint32_t)s_result[0] << 20;
 }
 
-constexpr int CNT_BLOCK = 1024;
+constexpr int CNT_BLOCK = SEL_BLOCK;
 constexpr int CNT_WAVES = CNT_BLOCK / WAVE;
 constexpr int CNT_STASH = 1024;                  // keys per wave between flushes
 constexpr int CNT_U = 4;
