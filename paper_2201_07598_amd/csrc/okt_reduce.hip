@@ -21,6 +21,7 @@
 // cache), every output entry is written once, plus 4 B per slot if the dense
 // region is requested.
 #include "okt_device.h"
+#include "okt_search.h"
 #include "okt_sizes.h"
 
 #ifndef OKT_RED_EMIT_BITS
@@ -32,15 +33,6 @@
 namespace okt {
 
 constexpr int RED_WAVES = RED_BLOCK / WAVE;
-
-__device__ __forceinline__ uint64_t lower_bound_idx(const uint32_t* __restrict__ a, uint64_t lo,
-                                                    uint64_t hi, uint32_t x) {
-    while (lo < hi) {
-        const uint64_t mid = lo + ((hi - lo) >> 1);
-        if (a[mid] < x) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
 
 struct RegionView {
     uint32_t lo, hi, width, ntiles;
@@ -60,12 +52,14 @@ __device__ __forceinline__ RegionView region_view(const uint32_t* lo_hi, uint32_
 
 // table[region][t][p] = number of entries of contribution p with index below
 // lo + t * slots (clipped to hi), for t = 0 .. ntiles.
+// from_guess: a launch with so many boundaries that it is bound by the number of
+// probes, not by the latency of one search, starts every search from a guess.
 __global__ __launch_bounds__(256) void reduce_slices_kernel(
     const uint32_t* __restrict__ idx_cat, const uint64_t* __restrict__ seg_begin,
     const uint64_t* __restrict__ seg_end, uint32_t seg_stride,
     const uint32_t* __restrict__ lo_hi, uint32_t lo0, uint32_t hi0, uint32_t P,
     uint32_t max_width, uint32_t slots, char* ws, uint32_t ws_region_bytes,
-    uint32_t table_offset, uint32_t spin_limit) {
+    uint32_t table_offset, uint32_t spin_limit, uint32_t from_guess) {
     const uint32_t region = blockIdx.y;
     const RegionView r = region_view(lo_hi, lo0, hi0, region, max_width, slots);
     uint32_t* table = (uint32_t*)(ws + (size_t)region * ws_region_bytes + table_offset);
@@ -86,7 +80,12 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(
         uint64_t bound = (uint64_t)r.lo + (uint64_t)t * slots;
         if (bound > r.hi) bound = r.hi;
         const uint64_t cb = begin[p], ce = end[p] > cb ? end[p] : cb;
-        table[(size_t)t * P + p] = (uint32_t)(lower_bound_idx(idx_cat, cb, ce, (uint32_t)bound) - cb);
+        // where the boundary would fall if the contribution's indices were spread evenly
+        // over the region (both factors are below 2^32)
+        const uint64_t guess = cb + (r.width ? (ce - cb) * (bound - r.lo) / r.width : 0);
+        table[(size_t)t * P + p] =
+            (uint32_t)((from_guess ? lower_bound_near(idx_cat, cb, ce, (uint32_t)bound, guess)
+                                   : lower_bound_idx(idx_cat, cb, ce, (uint32_t)bound)) - cb);
     }
 }
 
@@ -485,7 +484,7 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
         hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)sblocks, B), dim3(256), 0, s,
                            d_idx_cat, d_seg_begin, d_seg_end, seg_stride, d_lo_hi, lo, hi, P,
                            max_width, slots, (char*)d_ws, (uint32_t)region_bytes, table_offset,
-                           spin_limit_setting());
+                           spin_limit_setting(), cells * B >= (1u << 17) ? 1u : 0u);
     }
     // entries a contribution is expected to have in a tile: longer slices are read
     // in spans of two or four blocks of 64

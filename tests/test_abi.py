@@ -4,6 +4,8 @@ errors are caught on the host before anything is launched."""
 import ctypes
 import os
 import re
+import shutil
+import subprocess
 
 import numpy as np
 import pytest
@@ -154,3 +156,19 @@ def test_balance_plan_library_matches_the_oracle():
         got = okt.okt_balance_plan(sizes)
         assert got[0] == want[0], sizes
         assert [tuple(int(x) for x in c) for c in got[1]] == [tuple(c) for c in want[1]], sizes
+
+
+def test_index_searches_match_std_lower_bound(tmp_path):
+    """The searches behind the reduce's boundary tables (bisection, and the one that
+    starts from a guess) are plain functions a host compiler can build: checked
+    here against std::lower_bound on random lists, ranges and guesses."""
+    gxx = shutil.which("g++")
+    if gxx is None:
+        pytest.skip("no g++")
+    exe = tmp_path / "search_check"
+    subprocess.run([gxx, "-O2", "-std=c++17", "-Wall", "-Werror", "-I",
+                    os.path.join(ROOT, "paper_2201_07598_amd", "csrc"),
+                    os.path.join(ROOT, "tests", "cabi", "search_check.cpp"), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout
+    assert "0 disagreements" in out.stdout

@@ -932,6 +932,68 @@ def test_reduce_batch_matches_single_regions():
         assert np.allclose(d, ref["dense"], rtol=1e-5, atol=1e-12)
 
 
+def test_reduce_batch_with_clustered_contributions():
+    """A launch with so many tile boundaries (more than 2^17) that the boundary
+    search starts from a guess - the place a boundary would have if the indices
+    were spread evenly - and brackets from there.  Here they are not spread
+    evenly: clusters at either end of the region, two clusters, geometric
+    spacing, entries outside the region on both sides, empty contributions."""
+    rng = np.random.default_rng(123)
+    B, P, width, m = 128, 32, 2_000_000, 300
+    idx_parts, val_parts, offs, lohi = [], [], [0], []
+    for j in range(B):
+        lo = 4_000_000 * j + 1000
+        hi = lo + width
+        lohi += [lo, hi]
+        for p in range(P):
+            kind = (j + p) % 7
+            if kind == 0:
+                x = rng.choice(width, m, replace=False)
+            elif kind == 1:
+                x = rng.choice(width // 100, m, replace=False)                     # all at the start
+            elif kind == 2:
+                x = width - 1 - rng.choice(width // 100, m, replace=False)         # all at the end
+            elif kind == 3:
+                x = np.concatenate([rng.choice(5000, m // 2, replace=False) + width // 3,
+                                    rng.choice(5000, m - m // 2, replace=False) + 2 * (width // 3)])
+            elif kind == 4:
+                x = np.unique((width * (1.0 - 0.97 ** np.arange(1, 4 * m))).astype(np.int64))[:m]
+            elif kind == 5:                                                        # mostly outside the region
+                x = np.concatenate([-1 - rng.choice(900, 100, replace=False),
+                                    rng.choice(width, m - 200, replace=False),
+                                    width + rng.choice(900, 100, replace=False)])
+            else:
+                x = np.zeros(0, dtype=np.int64)                                    # nothing at all
+            x = np.sort(np.unique(x.astype(np.int64))) + lo
+            idx_parts.append(x.astype(np.uint32))
+            val_parts.append(rng.standard_normal(x.size).astype(np.float32))
+            offs.append(offs[-1] + x.size)
+        if j < B - 1:
+            offs.append(offs[-1])               # the next region's first offset
+    off = np.array(offs, dtype=np.uint64)
+    assert off.size == B * (P + 1)
+    idx_cat, val_cat = np.concatenate(idx_parts), np.concatenate(val_parts)
+    cap = P * m
+    out_idx = torch.full((B * cap,), -1, dtype=torch.int32, device=DEV)
+    out_val = torch.zeros(B * cap, dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2 * B, dtype=torch.int64, device=DEV)
+    ws = workspace(okt.okt_sparse_reduce_batch_workspace_bytes(B, P, width))
+    okt.okt_sparse_reduce_batch(to_dev(idx_cat), to_dev(val_cat), to_dev(off),
+                                to_dev(np.array(lohi, dtype=np.uint32)), B, P, width,
+                                out_idx, out_val, cap, nnz, ws)
+    counts = u64(nnz)
+    for j in range(B):
+        lo, hi = lohi[2 * j], lohi[2 * j + 1]
+        o = off[j * (P + 1):(j + 1) * (P + 1)]
+        a, b = int(o[0]), int(o[-1])
+        ref = orc.sparse_reduce(idx_cat[a:b], val_cat[a:b], o - o[0], lo, hi)
+        U = ref["idx"].size
+        assert counts[2 * j] == counts[2 * j + 1] == U, j
+        assert np.array_equal(u32(out_idx[j * cap:j * cap + U]), ref["idx"]), j
+        err = np.abs(out_val[j * cap:j * cap + U].cpu().numpy().astype(np.float64) - ref["val"])
+        assert np.all(err <= reduce_tolerance(ref)), j
+
+
 # ----------------------------------------------------------- the whole hot path
 def run_loop(w, iterations, R, fused=False):
     """Alternate the GPU path and the oracle over `iterations` of Ok-Topk SGD's
