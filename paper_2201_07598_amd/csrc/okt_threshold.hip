@@ -454,7 +454,7 @@ __global__ __launch_bounds__(BLOCK) void candidate_select_kernel(
     CandidateSource source{nullptr, res};
     if (use_cand) {
         walked = cand_val;
-        len = (uint32_t)state->m;                           // <= cand_cap <= n
+        len = (uint32_t)state->m;                           // candidates found: at most n
         source.idx_in = cand_idx;
         const uint32_t waves = nseg * (uint32_t)WAVES;
         uint32_t share = ((len + waves - 1) / waves + 255u) / 256u * 256u;   // whole rounds
