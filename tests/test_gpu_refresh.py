@@ -200,3 +200,44 @@ def test_bounded_waits_that_give_up_are_reported():
         okt.okt_debug_spin_limit(0)
     print(outcomes, flush=True)
     check_refresh(g, e, 0.5, k, 2 * k)               # the limit restored: exact again
+
+
+@pytest.mark.timeout(300)
+def test_the_call_captured_in_a_hip_graph_replays_like_eager():
+    """The call enqueues kernels only (its state is cleared by a kernel, not a
+    memset), so it can be captured once and replayed: every replay - with eager
+    work and synchronisations in between - against the oracle, which follows the
+    carried residual.  Long enough for the one-pass path."""
+    n, lr, k, rounds = 4_300_003, 0.5, 43_000, 4
+    grads = [lap(400 + r, n) for r in range(rounds)]
+    d_g = to_dev(grads[0])
+    res = torch.zeros(n, dtype=torch.float32, device=DEV)
+    th = torch.zeros(1, dtype=torch.float32, device=DEV)
+    cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    cap = 2 * k
+    idx = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
+    val = torch.zeros(cap, dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    ws = workspace(okt.okt_workspace_bytes(n, 0))
+    okt.load_library()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        okt.okt_accumulate_topk_select(d_g, res, lr, k, th, cnt, idx, val, nnz, ws, capacity=cap)
+    res.zero_()                                    # capture does not run anything; start clean anyway
+    host_res = np.zeros(n, dtype=np.float32)
+    for r in range(rounds):
+        d_g.copy_(torch.from_numpy(grads[r]))      # eager work between the replays
+        idx.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        acc = orc.residual_accumulate(grads[r], host_res, lr)
+        rth, rcnt = orc.topk_threshold_exact(acc, k, method="partition")
+        ridx, rval, host_res, total = orc.threshold_select(acc, rth, capacity=cap)
+        assert th.cpu().numpy().view(np.uint32)[0] == np.float32(rth).view(np.uint32), r
+        assert int(u64(cnt)[0]) == rcnt == total, r
+        c = u64(nnz)
+        assert (int(c[0]), int(c[1])) == (ridx.size, total), r
+        assert np.array_equal(u32(idx[:total]), ridx) and bits_equal(val[:total].cpu().numpy(), rval), r
+        assert bits_equal(res.cpu().numpy(), host_res), r
