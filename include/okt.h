@@ -167,6 +167,29 @@ int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshol
                          uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * okt_threshold_select for callers that cannot allocate or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without d_ws / ws_bytes, same results bit for bit,
+ * same launches.  The scan state lives in an array of
+ * OKT_SELECT_NOALLOC_SCRATCH_BYTES of device memory that is part of the library
+ * (every GPU the library runs on holds its own copy until the process ends);
+ * the call allocates and frees nothing.
+ *   - The device current on the calling thread must be the one `stream` and the
+ *     buffers belong to.  The first call on a device asks the runtime where the
+ *     array lives there, so make it outside any stream capture.
+ *   - The array suffices for every n the interface allows on GPUs with up to 1024
+ *     compute units; a vector that would need more scan state than it holds is
+ *     refused with OKT_ERR_WORKSPACE before anything is launched.
+ *   - All calls on one GPU share the array (each call clears the part it uses
+ *     with a fill kernel first): calls that overlap in time on one GPU - two
+ *     streams, two host threads - race.  Order them on one stream.
+ */
+#define OKT_SELECT_NOALLOC_SCRATCH_BYTES (144 * 1024)
+int okt_threshold_select_noalloc(float* d_acc_inout, uint64_t n, const float* d_threshold,
+                                 uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                                 uint64_t* d_nnz_out, void* stream);
+
+/*
  * The same selection and packaging without the residual update: d_acc is only
  * read.  For callers that follow Algorithm 2, line 6 to the letter and zero the
  * entries of `indexes` (the locally selected entries that reached the global

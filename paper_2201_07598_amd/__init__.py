@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     okt_time_next_kernel,
     okt_threshold_select,
     okt_threshold_select_copy,
+    okt_threshold_select_noalloc,
     okt_topk_threshold_exact,
     okt_version,
     okt_workspace_bytes,

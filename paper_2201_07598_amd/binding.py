@@ -30,6 +30,7 @@ SIGNATURES = {
     "okt_residual_accumulate": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp]),
     "okt_topk_threshold_exact": (c_int, [c_vp, c_u64, c_u64, c_vp, c_vp, c_vp, c_sz, c_vp]),
     "okt_threshold_select": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_sz, c_vp]),
+    "okt_threshold_select_noalloc": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp]),
     "okt_threshold_select_copy": (c_int, [c_vp, c_u64, c_vp, c_vp, c_vp, c_u64, c_vp, c_vp, c_sz, c_vp]),
     "okt_index_intersect_zero": (c_int, [c_vp, c_u64, c_vp, c_vp, c_u64, c_vp, c_vp, c_u64, c_vp, c_vp,
                                          c_vp, c_sz, c_vp]),
@@ -222,6 +223,22 @@ def okt_threshold_select(acc_inout, threshold, idx_out, val_out, nnz_out, ws, ca
         _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
         _ptr(nnz_out, _u64(torch), "nnz_out"), _ptr(ws, torch.uint8, "ws"), ws.numel(),
         _stream(stream)))
+
+
+def okt_threshold_select_noalloc(acc_inout, threshold, idx_out, val_out, nnz_out, capacity=None,
+                                 stream=None) -> None:
+    """okt_threshold_select on the library's own scan state: no workspace argument."""
+    torch = _torch()
+    cap = min(idx_out.numel(), val_out.numel()) if capacity is None else int(capacity)
+    if cap > idx_out.numel() or cap > val_out.numel():
+        raise ValueError("capacity exceeds the output buffers")
+    if nnz_out.numel() < 2 or threshold.numel() < 1:
+        raise ValueError("nnz_out needs two elements, threshold one")
+    _check("okt_threshold_select_noalloc", load_library().okt_threshold_select_noalloc(
+        _ptr(acc_inout, torch.float32, "acc_inout"), acc_inout.numel(),
+        _ptr(threshold, torch.float32, "threshold"),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"), cap,
+        _ptr(nnz_out, _u64(torch), "nnz_out"), _stream(stream)))
 
 
 def okt_threshold_select_copy(acc, threshold, idx_out, val_out, nnz_out, ws, capacity=None,

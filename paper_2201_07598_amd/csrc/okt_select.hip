@@ -13,6 +13,14 @@
 #include "okt_select_kernel.h"
 #include "okt_sizes.h"
 
+#include <mutex>
+
+// Scan state of okt_threshold_select_noalloc: device memory that belongs to the
+// library, one copy per GPU, held until the process ends.  Host code never uses
+// this name as an address; it asks the runtime where the array lives on the
+// current device (static_scratch below) and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[OKT_SELECT_NOALLOC_SCRATCH_BYTES];
+
 namespace okt {
 
 __global__ void select_empty_kernel(uint64_t* nnz_out) {
@@ -24,23 +32,34 @@ __global__ void select_empty_kernel(uint64_t* nnz_out) {
 
 namespace okt {
 
+// Argument errors of the dense select, found before anything is launched.
+static int dense_select_args(const float* d_acc, uint64_t n, const float* d_threshold,
+                             const uint32_t* d_idx_out, const float* d_val_out, uint64_t capacity,
+                             const uint64_t* d_nnz_out) {
+    if (!d_nnz_out || !aligned(d_nnz_out, 8)) return OKT_ERR_INVALID_ARG;
+    if (n > 0xffffffffull) return OKT_ERR_INVALID_ARG;
+    if (n == 0) return OKT_OK;
+    if (!d_acc || !d_threshold || !aligned(d_acc, 16) || !aligned(d_threshold, 4))
+        return OKT_ERR_INVALID_ARG;
+    if (capacity > 0 && (!d_idx_out || !d_val_out || !aligned(d_idx_out, 4) ||
+                         !aligned(d_val_out, 4)))
+        return OKT_ERR_INVALID_ARG;
+    return OKT_OK;
+}
+
 // The dense select, with (Source = DenseSource) or without (DenseCopySource) the
 // zeroing of the emitted entries.
 template <typename Source>
 static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshold,
                                uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
                                uint64_t* d_nnz_out, void* d_ws, size_t ws_bytes, hipStream_t s) {
-    if (!d_nnz_out || !aligned(d_nnz_out, 8)) return OKT_ERR_INVALID_ARG;
-    if (n > 0xffffffffull) return OKT_ERR_INVALID_ARG;
+    const int args = dense_select_args(d_acc, n, d_threshold, d_idx_out, d_val_out, capacity,
+                                       d_nnz_out);
+    if (args != OKT_OK) return args;
     if (n == 0) {
         hipLaunchKernelGGL(select_empty_kernel, dim3(1), dim3(1), 0, s, d_nnz_out);
         return launch_status();
     }
-    if (!d_acc || !d_threshold || !aligned(d_acc, 16) || !aligned(d_threshold, 4))
-        return OKT_ERR_INVALID_ARG;
-    if (capacity > 0 && (!d_idx_out || !d_val_out || !aligned(d_idx_out, 4) ||
-                         !aligned(d_val_out, 4)))
-        return OKT_ERR_INVALID_ARG;
     const SelectShape shape = select_shape(n);
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(n)) return OKT_ERR_WORKSPACE;
     ScanHeader* hdr = (ScanHeader*)d_ws;
@@ -66,6 +85,53 @@ extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float*
     return okt::launch_dense_select<okt::DenseSource>(d_acc_inout, n, d_threshold, d_idx_out,
                                                       d_val_out, capacity, d_nnz_out, d_ws,
                                                       ws_bytes, (hipStream_t)stream);
+}
+
+namespace okt {
+
+// Address of `scratch` on the calling thread's current device, looked up once per
+// device and kept.
+static int static_scratch(void** out) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex guard;
+    static void* where[MAX_DEVICES] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return launch_failed(e);
+    if (dev < 0 || dev >= MAX_DEVICES) return OKT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(guard);
+    if (!where[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return launch_failed(e);
+        if (!p) return launch_failed(hipErrorInvalidSymbol);
+        where[dev] = p;
+    }
+    *out = where[dev];
+    return OKT_OK;
+}
+
+}  // namespace okt
+
+extern "C" int okt_threshold_select_noalloc(float* d_acc_inout, uint64_t n,
+                                            const float* d_threshold, uint32_t* d_idx_out,
+                                            float* d_val_out, uint64_t capacity,
+                                            uint64_t* d_nnz_out, void* stream) {
+    const int args = okt::dense_select_args(d_acc_inout, n, d_threshold, d_idx_out, d_val_out,
+                                            capacity, d_nnz_out);
+    if (args != OKT_OK) return args;
+    // more workgroups than the array has descriptors for: refuse before anything runs
+    if (okt::select_ws_bytes(n) > sizeof(scratch)) return OKT_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (n != 0) {                      // an empty vector needs no scan state
+        const int rc = okt::static_scratch(&ws);
+        if (rc != OKT_OK) return rc;
+    }
+    // the same launches as okt_threshold_select: a fill kernel that clears the scan
+    // state (the array keeps what the last call left), then the select kernel
+    return okt::launch_dense_select<okt::DenseSource>(d_acc_inout, n, d_threshold, d_idx_out,
+                                                      d_val_out, capacity, d_nnz_out, ws,
+                                                      sizeof(scratch), (hipStream_t)stream);
 }
 
 extern "C" int okt_threshold_select_copy(const float* d_acc, uint64_t n, const float* d_threshold,

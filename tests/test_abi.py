@@ -83,6 +83,11 @@ def test_argument_errors_are_found_on_the_host():
     assert lib.okt_index_intersect_restore(fake, 100, fake, fake, fake, 10, null, fake, 10, null, fake, fake, 1 << 20, null) == INVALID
     assert lib.okt_index_intersect_restore(fake, 100, fake, fake, fake, 10, fake, fake, 10, null, null, fake, 1 << 20, null) == INVALID
     assert lib.okt_index_intersect_restore(fake, 100, fake, fake, fake, 1 << 20, fake, fake, 10, null, fake, fake, 8, null) == WORKSPACE
+    # the entry point on the library's own scan state checks its arguments first, too
+    assert lib.okt_threshold_select_noalloc(fake, 10, null, fake, fake, 4, fake, null) == INVALID
+    assert lib.okt_threshold_select_noalloc(odd, 10, fake, fake, fake, 4, fake, null) == INVALID
+    assert lib.okt_threshold_select_noalloc(fake, 1 << 32, fake, fake, fake, 4, fake, null) == INVALID
+    assert lib.okt_threshold_select_noalloc(fake, 10, fake, null, fake, 4, fake, null) == INVALID
     assert lib.okt_threshold_select_copy(odd, 10, fake, fake, fake, 4, fake, fake, 1 << 20, null) == INVALID
     assert lib.okt_threshold_select_copy(fake, 1 << 20, fake, fake, fake, 4, fake, fake, 8, null) == WORKSPACE
     assert lib.okt_index_intersect_zero(null, 100, fake, fake, 10, fake, fake, 10, null, fake, fake, 1 << 20, null) == INVALID
