@@ -3,36 +3,42 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
-Workload: the ResNet-50-sized configuration (n = 25,557,032 fp32, 161 layer
-segments, density 1 %, P = 16).  One STEP is one refresh period of the local
-part of Ok-Topk SGD for one simulated worker, 10 iterations:
+Headline workload: the BERT-large-sized configuration cfg4, the largest one a
+single GPU runs (n = 336,000,000 fp32, Student-t(3) x 1e-4, density 0.1 %,
+k = 336,000, 64 regions, P = 64).  One STEP is the configuration's schedule for
+one simulated worker, three iterations from a zero residual, every one of which
+re-evaluates the threshold:
 
-    iteration 0:     okt_accumulate_topk_select (accumulate, exact threshold and
-                     select reading the gradient and the residual once: the same
-                     results, bit for bit, as okt_residual_accumulate ->
-                     okt_topk_threshold_exact -> okt_threshold_select)
-                     -> okt_region_partition
-    iterations 1-9:  okt_accumulate_select (the same accumulate and select, bit for
-                     bit, in one pass: the threshold is reused, so it is known
-                     before the accumulator is)
-    every iteration: okt_sparse_reduce (P = 16 contributions over one region of n/16)
+    every iteration:  okt_accumulate_topk_select (accumulate, exact threshold and
+                      select reading the gradient and the residual once: the same
+                      results, bit for bit, as okt_residual_accumulate ->
+                      okt_topk_threshold_exact -> okt_threshold_select)
+                      -> okt_sparse_reduce (P = 64 contributions over the widest
+                      of the 64 regions)
+    iteration 0:      okt_region_partition (R = 64) after the select
 
-with the error-feedback residual carried from iteration to iteration and from
-step to step.  `two_call_path` in the output is the same step made of the separate
-calls (okt_residual_accumulate, okt_topk_threshold_exact at iteration 0,
-okt_threshold_select).  Steps rotate over several independent simulated workers and the
-reduce rotates over a pool of contribution sets, so that no vector is served
-from the 256 MB Infinity Cache on re-use.  All inputs are seeded, synthetic and
-resident in HBM before the timed region starts.
+with the error-feedback residual carried from iteration to iteration.  Every step
+starts from its own zeroed residual buffer (a pool, cleared before the timed
+region), so no step sees what another left behind; the reduce rotates over a pool
+of contribution sets.  `--workload cfg2|cfg3` times those configurations' refresh
+periods instead (there the step starts from a residual brought to its steady state
+beforehand, see steady_state()).  All inputs are seeded, synthetic and resident
+in HBM before the timed region starts.
 
-Prints ONE JSON line (see the driver's contract) with `roofline` (the dominant
-kernel, timed with HIP events inside the timed region) and `cpu_baseline` (the
-numpy oracle on the same workload, on the host cores).
+Prints ONE JSON line (see the driver's contract) with
+  roofline      the dominant kernel of the step, timed with HIP events inside the
+                timed region
+  cpu_baseline  the numpy oracle on the same workload, on the host cores
+  per_config    for cfg1 .. cfg5: every call of the path timed on its own at that
+                configuration's size (select + compact, the fused calls, the exact
+                threshold, the lone reduce) with algorithmic bytes and fraction of
+                the HBM peak, and the batched reduce (> 1 GB of regions of that
+                configuration's shape in one launch)
+  reduce_batch  the batched-reduce rows of per_config side by side
 """
 from __future__ import annotations
 
 import argparse
-import dataclasses
 import json
 import os
 import sys
@@ -43,10 +49,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
-ITERS_PER_STEP = 10
-WORKLOAD = "cfg2"
-CALLS = ("accumulate", "threshold", "select", "accumulate_topk_select", "accumulate_select",
-         "partition", "reduce")
+DEV = "cuda:0"
+BURN_IN = 30                   # iterations that bring a residual to its steady state
 
 
 def log(*a):
@@ -56,37 +60,781 @@ def log(*a):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workers", type=int, default=4, help="independent simulated workers")
-    ap.add_argument("--contrib-sets", type=int, default=24)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4", choices=("cfg2", "cfg3", "cfg4"),
+                    help="the configuration whose schedule is the timed step")
+    ap.add_argument("--iters", type=int, default=0,
+                    help="iterations per step (0 = the configuration's refresh period: "
+                         "cfg2 10, cfg3 32 cut to 8, cfg4 3)")
+    ap.add_argument("--configs", default="cfg1,cfg2,cfg3,cfg4,cfg5",
+                    help="configurations of the per_config block (comma separated; empty = none)")
+    ap.add_argument("--no-headline", action="store_true",
+                    help="skip the timed steps (profiling runs of one configuration's calls)")
+    ap.add_argument("--contrib-sets", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region")
-    ap.add_argument("--reduce-dense", action="store_true",
-                    help="also have every reduce of the step write the densified region "
-                         "(a checking aid, not a step of the method)")
     ap.add_argument("--reduce-batch", type=int, default=0,
-                    help="also time the batched reduce over this many regions (0 = auto)")
+                    help="regions in the batched reduce (0 = as many as make 1 GB of input)")
     return ap.parse_args()
 
 
-class Worker:
-    """Device state of one simulated worker."""
+# ----------------------------------------------------------------------------
+# small helpers (device plumbing only)
+# ----------------------------------------------------------------------------
+def dev_u(torch, np, a):
+    view = {np.dtype(np.uint32): np.int32, np.dtype(np.uint64): np.int64}.get(a.dtype)
+    return torch.from_numpy(a.view(view) if view else a).to(DEV)
 
-    def __init__(self, torch, okt, w, grads_host):
-        dev = "cuda:0"
-        self.grads = [torch.from_numpy(g).to(dev) for g in grads_host]
-        self.residual = torch.zeros(w.n, dtype=torch.float32, device=dev)
-        self.th = torch.zeros(1, dtype=torch.float32, device=dev)
-        self.count_ge = torch.zeros(1, dtype=torch.int64, device=dev)
+
+def u64_host(np, t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def stats(np, us, nbytes=None):
+    if len(us) == 0 or float(np.median(us)) < 0.2:   # the library recorded nothing (no main kernel on this path)
+        return None
+    out = {"us_median": round(float(np.median(us)), 2), "us_min": round(float(np.min(us)), 2),
+           "samples": len(us)}
+    if nbytes is not None:
+        out["algorithmic_bytes"] = float(nbytes)
+        out["achieved_GBs"] = round(nbytes / out["us_median"] * 1e-3, 1)
+        out["frac_of_hbm_peak"] = round(nbytes / out["us_median"] * 1e-3 / HBM_PEAK_GBS, 4)
+    return out
+
+
+class Events:
+    """Event pairs: around a call (whole call, with its small launches) or handed
+    to the library, which records them right around the call's main kernel."""
+
+    def __init__(self, torch, okt):
+        self.torch, self.okt = torch, okt
+
+    def pair(self):
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        return a, b
+
+    def around(self, fn):
+        a, b = self.pair()
+        a.record()
+        fn()
+        b.record()
+        return a, b
+
+    def kernel(self, fn):
+        a, b = self.pair()
+        a.record()
+        b.record()                       # the events exist from here on
+        self.okt.okt_time_next_kernel(a, b)
+        fn()
+        self.okt.okt_time_next_kernel(None, None)   # a call without such a kernel leaves the pair armed
+        return a, b
+
+
+def time_over_slots(torch, ev, call, nslots, restore, reps):
+    """call(slot) timed once per slot and round, both around the whole call and (a
+    second pass) around its main kernel; restore(slot), untimed, rewrites the
+    slot's buffers before every round.  With several slots whose buffers together
+    exceed the 256 MB last-level cache no call finds its input cached.  Returns
+    (us per call, us per main kernel)."""
+    whole, main = [], []
+    for dst, how in ((whole, ev.around), (main, ev.kernel)):
+        while len(dst) < reps:
+            for s in range(nslots):
+                restore(s)
+            torch.cuda.synchronize()
+            pairs = [how(lambda s=s: call(s)) for s in range(nslots)]
+            torch.cuda.synchronize()
+            dst += [a.elapsed_time(b) * 1e3 for a, b in pairs]
+    return whole, main
+
+
+# ----------------------------------------------------------------------------
+# one configuration's device state
+# ----------------------------------------------------------------------------
+class Config:
+    """Inputs of one configuration on the device: gradients of consecutive
+    iterations, the residual a refresh iteration starts from, and what the calls
+    write."""
+
+    def __init__(self, torch, np, okt, wl, name, ngrads, keep_host=False):
+        self.torch, self.np, self.okt, self.wl = torch, np, okt, wl
+        self.w = w = wl.WORKLOADS[name]
+        self.name, self.n, self.k, self.P = name, w.n, w.k, w.P
+        t0 = time.time()
+        self.host_grads, self.grads = [], []
+        for it in range(ngrads):
+            g = wl.gradient(w, it)
+            self.grads.append(torch.from_numpy(g).to(DEV))
+            if keep_host:                      # the oracle's leg runs on the same bytes
+                self.host_grads.append(g)
+        log(f"[bench] {name}: {ngrads} gradients of {w.n} fp32 uploaded ({time.time() - t0:.1f}s)")
         self.cap = 4 * w.k
-        self.idx = torch.zeros(self.cap, dtype=torch.int32, device=dev)
-        self.val = torch.zeros(self.cap, dtype=torch.float32, device=dev)
-        self.nnz = torch.zeros(2, dtype=torch.int64, device=dev)
-        self.bounds = torch.zeros(w.P + 1, dtype=torch.int32, device=dev)
-        self.offsets = torch.zeros(w.P + 1, dtype=torch.int64, device=dev)
-        self.ws = torch.empty(okt.okt_workspace_bytes(w.n, w.P), dtype=torch.uint8, device=dev)
+        self.th = torch.zeros(1, dtype=torch.float32, device=DEV)
+        self.count_ge = torch.zeros(1, dtype=torch.int64, device=DEV)
+        self.idx = torch.zeros(self.cap, dtype=torch.int32, device=DEV)
+        self.val = torch.zeros(self.cap, dtype=torch.float32, device=DEV)
+        self.nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+        self.bounds = torch.zeros(w.P + 1, dtype=torch.int32, device=DEV)
+        self.offsets = torch.zeros(w.P + 1, dtype=torch.int64, device=DEV)
+        self.ws = torch.empty(okt.okt_workspace_bytes(w.n, w.P), dtype=torch.uint8, device=DEV)
+        self.start = torch.zeros(w.n, dtype=torch.float32, device=DEV)   # residual at a step's start
+        self.burn_in = 0
+
+    def steady_state(self, iterations=BURN_IN):
+        """Brings self.start to the steady state of error feedback: `iterations`
+        iterations of accumulate + exact top-k select on noise of the workload's own
+        recipe (same layer table and distribution), drawn on the device.  A
+        residual that starts at zero is far from it: a threshold found on the first
+        accumulator selects 2 to 2.5 k entries from the second iteration on, whereas
+        after this the count stays within a few percent of k while the threshold
+        is reused, as Sec. 5.2 reports for real training.  Input preparation only:
+        nothing here is timed."""
+        torch, np, w = self.torch, self.np, self.w
+        bounds, scale = self.wl.segment_table(w)
+        lengths = torch.from_numpy(np.diff(bounds)).to(DEV)
+        scale_v = torch.repeat_interleave(torch.from_numpy(scale.astype(np.float32)).to(DEV), lengths)
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(w.seed)
+        noise = torch.empty(w.n, dtype=torch.float32, device=DEV)
+        other = torch.empty(w.n, dtype=torch.float32, device=DEV) if w.dist == "laplace" else None
+        for _ in range(iterations):
+            if w.dist == "normal":
+                noise.normal_(generator=gen)
+            elif w.dist == "laplace":                 # the difference of two exponentials
+                noise.exponential_(generator=gen)
+                other.exponential_(generator=gen)
+                noise.sub_(other)
+            else:
+                raise ValueError(f"no device recipe for {w.dist}")
+            noise.mul_(scale_v)
+            self.okt.okt_accumulate_topk_select(noise, self.start, w.lr, w.k, self.th, self.count_ge,
+                                                self.idx, self.val, self.nnz, self.ws, capacity=self.cap)
+        torch.cuda.synchronize()
+        self.burn_in = iterations
+
+
+def widest_region(np, bounds):
+    b = bounds.cpu().numpy().view(np.uint32).astype(np.int64)
+    r = int(np.argmax(np.diff(b)))
+    return r, int(b[r]), int(b[r + 1])
+
+
+def reduce_region(cfg, np):
+    """The region this worker reduces: cfg1-3 a fixed region of n / P, cfg4 the
+    widest region of the balanced partition of its own first selection (the
+    partition must have been computed), cfg5 one region of n / 256 at slot 128."""
+    w = cfg.w
+    if cfg.name == "cfg4":
+        return widest_region(np, cfg.bounds)[1:]
+    if cfg.name == "cfg5":
+        width = -(-w.n // w.P)
+        return 128 * width, 129 * width
+    return 0, w.n // w.P
+
+
+# ----------------------------------------------------------------------------
+# the timed step
+# ----------------------------------------------------------------------------
+def headline(args, torch, np, okt, wl, ev, cfg):
+    w, n, k, P = cfg.w, cfg.n, cfg.k, cfg.P
+    iters = args.iters or {"cfg2": 10, "cfg3": 8, "cfg4": 3}[cfg.name]
+    iters = min(iters, len(cfg.grads))
+    steps_total = args.warmup + args.steps
+    # one residual buffer per step, filled with the starting state before the timed
+    # region; beyond 48 buffers they are reused and refilled inside the step
+    # (timed: that only makes the figure smaller)
+    pool_n = max(1, min(steps_total, 48))
+    pool = [cfg.start.clone() for _ in range(pool_n)]
+
+    # the first selection fixes the partition and with it the region that is reduced
+    scratch = cfg.start.clone()
+    okt.okt_accumulate_topk_select(cfg.grads[0], scratch, w.lr, k, cfg.th, cfg.count_ge, cfg.idx,
+                                   cfg.val, cfg.nnz, cfg.ws, capacity=cfg.cap)
+    okt.okt_region_partition(cfg.idx, cfg.nnz, n, P, cfg.bounds, cfg.offsets)
+    torch.cuda.synchronize()
+    lo, hi = reduce_region(cfg, np)
+    del scratch
+    contrib, host_contrib0 = [], None
+    for s in range(args.contrib_sets):
+        ci, cv, co = wl.contributions(w, lo, hi, stream=s)
+        if s == 0:
+            host_contrib0 = (ci, cv, co)
+        contrib.append((dev_u(torch, np, ci), torch.from_numpy(cv).to(DEV), dev_u(torch, np, co)))
+    E = int(contrib[0][0].numel())
+    red_idx = torch.zeros(E, dtype=torch.int32, device=DEV)
+    red_val = torch.zeros(E, dtype=torch.float32, device=DEV)
+    red_nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    side = torch.cuda.Stream()                 # default priority; the overlapped variant only
+    side_ws = torch.empty(okt.okt_workspace_bytes(hi - lo, P), dtype=torch.uint8, device=DEV)
+    counter = {"reduce": 0, "uses": [0] * pool_n}
+    log(f"[bench] {cfg.name}: region [{lo}, {hi}) of width {hi - lo}, {args.contrib_sets} contribution "
+        f"sets (P={P}, E={E}), {pool_n} residual buffers")
+
+    def run_step(step, record=None, only=None, hook=False, fused=True, overlap=False, nnz_log=None):
+        """One step.  `record` collects (call, start, stop) events for the calls in
+        `only` (all if None); inside the timed region only one launch per step is
+        bracketed, the middle iteration's."""
+        slot = step % pool_n
+        res = pool[slot]
+        if counter["uses"][slot]:
+            res.copy_(cfg.start)
+        counter["uses"][slot] += 1
+
+        def timed(name, fn, it):
+            if record is not None and (only is None or (name in only and it == iters // 2)):
+                a, b = (ev.kernel if hook else ev.around)(fn)
+                record.append((name, a, b))
+            else:
+                fn()
+
+        for it in range(iters):
+            g = cfg.grads[it]
+            if fused and w.refresh(it):
+                timed("accumulate_topk_select", lambda: okt.okt_accumulate_topk_select(
+                    g, res, w.lr, k, cfg.th, cfg.count_ge, cfg.idx, cfg.val, cfg.nnz, cfg.ws,
+                    capacity=cfg.cap), it)
+            elif fused:
+                timed("accumulate_select", lambda: okt.okt_accumulate_select(
+                    g, res, w.lr, cfg.th, cfg.idx, cfg.val, cfg.nnz, cfg.ws, capacity=cfg.cap), it)
+            else:
+                timed("accumulate", lambda: okt.okt_residual_accumulate(g, res, w.lr), it)
+                if w.refresh(it):
+                    timed("threshold", lambda: okt.okt_topk_threshold_exact(
+                        res, k, cfg.th, cfg.count_ge, cfg.ws), it)
+                timed("select", lambda: okt.okt_threshold_select(
+                    res, cfg.th, cfg.idx, cfg.val, cfg.nnz, cfg.ws, capacity=cfg.cap), it)
+            if it == 0:
+                timed("partition", lambda: okt.okt_region_partition(
+                    cfg.idx, cfg.nnz, n, P, cfg.bounds, cfg.offsets), it)
+            ci, cv, co = contrib[counter["reduce"] % len(contrib)]
+            counter["reduce"] += 1
+            if overlap:
+                okt.okt_sparse_reduce(ci, cv, co, lo, hi, red_idx, red_val, red_nnz, side_ws,
+                                      stream=side)
+            else:
+                timed("reduce", lambda: okt.okt_sparse_reduce(
+                    ci, cv, co, lo, hi, red_idx, red_val, red_nnz, cfg.ws), it)
+            if nnz_log is not None:          # untimed passes only: this reads back
+                nnz_log.append(int(u64_host(np, cfg.nnz)[1]))
+
+    def reset_pool():
+        for slot in range(pool_n):
+            pool[slot].copy_(cfg.start)
+            counter["uses"][slot] = 0
+        torch.cuda.synchronize()
+
+    def summarise(rec):
+        per = {}
+        for name, a, b in rec:
+            per.setdefault(name, []).append(a.elapsed_time(b) * 1e3)
+        return per
+
+    calls_per_step = {"accumulate": iters, "select": iters, "partition": 1, "reduce": iters,
+                      "threshold": sum(w.refresh(it) for it in range(iters)),
+                      "accumulate_topk_select": sum(w.refresh(it) for it in range(iters)),
+                      "accumulate_select": sum(not w.refresh(it) for it in range(iters))}
+
+    # ---- warmup (instrumented: finds the dominant call) ----
+    rec = []
+    for s in range(args.warmup):
+        run_step(s, record=rec)
+    torch.cuda.synchronize()
+    warm = {c: float(np.median(v)) for c, v in summarise(rec).items()}
+    dominant = max(warm, key=lambda c: warm[c] * calls_per_step[c]) if warm else "accumulate_topk_select"
+    for c, us in warm.items():
+        log(f"[bench] warmup {c:24s} median {us:9.1f} us x{calls_per_step[c]}/step")
+    log(f"[bench] dominant call: {dominant}")
+
+    # ---- the timed region: exactly K steps ----
+    rec = None if args.no_kernel_events else []
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for s in range(args.steps):
+        run_step(args.warmup + s, record=rec, only=(dominant,), hook=True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = iters * n / (ms_per_step * 1e-3)
+    in_region = summarise(rec) if rec else {}
+
+    # ---- per-call table of the step (instrumented passes, outside the timing) ----
+    reset_pool()
+    whole, main = [], []
+    for s in range(4):
+        run_step(s, record=whole)
+    for s in range(4):
+        run_step(4 + s, record=main, hook=True)
+    reset_pool()
+    sep_whole, sep_main = [], []
+    for s in range(3):
+        run_step(s, record=sep_whole, fused=False)
+    for s in range(3):
+        run_step(3 + s, record=sep_main, fused=False, hook=True)
+    torch.cuda.synchronize()
+    nnz_now = int(u64_host(np, cfg.nnz)[1])
+    U = int(u64_host(np, red_nnz)[1])
+    table, table_main = summarise(whole), summarise(main)
+    for c, v in summarise(sep_whole).items():
+        table.setdefault(c, v)
+    for c, v in summarise(sep_main).items():
+        table_main.setdefault(c, v)
+    alg = algorithmic_bytes(n, nnz_now, E, U)
+    kernels = {}
+    for c, v in table.items():
+        kernels[c] = {"calls_per_step": calls_per_step[c], "us_per_call": stats(np, v, alg.get(c))}
+        if c in table_main:
+            kernels[c]["us_main_kernel"] = stats(np, table_main[c], main_kernel_bytes(c, alg, n))
+
+    dom_us = float(np.mean(in_region[dominant])) if dominant in in_region else \
+        float(np.median(table_main[dominant]))
+    dom_bytes = main_kernel_bytes(dominant, alg, n)
+    achieved = dom_bytes / dom_us * 1e-3
+    roofline = {"bound": "hbm", "kernel": MAIN_KERNEL.get(dominant, dominant), "call": dominant,
+                "timed": "events recorded by the library right before and after the launch of the "
+                         "call's main kernel, one launch per step inside the timed region",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic(cfg.name, dominant), "us_per_launch": round(dom_us, 2),
+                "algorithmic_bytes_per_launch": dom_bytes}
+
+    # ---- the same step made of the separate calls ----
+    reset_pool()
+    t_f = time.perf_counter()
+    for s in range(args.steps):
+        run_step(s, fused=False)
+    torch.cuda.synchronize()
+    ms_two = (time.perf_counter() - t_f) * 1e3 / args.steps
+    separate = {"what": "the same step made of the separate calls: okt_residual_accumulate, "
+                        "okt_topk_threshold_exact (refresh iterations), okt_threshold_select",
+                "ms_per_step": ms_two, "value": iters * n / (ms_two * 1e-3)}
+
+    # ---- the same step with the reduce on a second stream ----
+    reset_pool()
+    t_o = time.perf_counter()
+    for s in range(args.steps):
+        run_step(s, overlap=True)
+    torch.cuda.synchronize()
+    ms_overlap = (time.perf_counter() - t_o) * 1e3 / args.steps
+    overlapped = {"what": "the same step with every okt_sparse_reduce enqueued on a second HIP stream "
+                          "(own workspace), beside the next iteration's accumulate+select; not the "
+                          "headline: one stream is",
+                  "ms_per_step": ms_overlap, "value": iters * n / (ms_overlap * 1e-3)}
+
+    # ---- report only: entries selected per iteration over k ----
+    reset_pool()
+    nnz_log = []
+    run_step(0, nnz_log=nnz_log)
+    sanity = {"selected_per_iteration": nnz_log,
+              "selected_over_k_per_iteration": [round(v / k, 4) for v in nnz_log],
+              "max_abs_drift": round(max(abs(v - k) / k for v in nnz_log), 4),
+              "reduce_union_over_contribution": round(U / max(E // P, 1), 3)}
+    reset_pool()
+
+    schedule = {"cfg2": "exact threshold at iteration 0 (one call for accumulate, threshold and select), "
+                        "reused on iterations 1-9 (accumulate and select in one pass)",
+                "cfg3": "exact threshold at iteration 0, reused afterwards (the first %d iterations of "
+                        "the 32-iteration refresh period)" % iters,
+                "cfg4": "exact threshold every iteration (accumulate, threshold and select in one "
+                        "call), partition into 64 regions at iteration 0"}[cfg.name]
+    out = {
+        "value": value, "ms_per_step": ms_per_step,
+        "config": {"workload": f"{cfg.name}: n={n:,} fp32 ({w.dist}, {w.segments or 1} segment(s)), density "
+                               f"{w.density_num}/{w.density_den} (k={k:,}), {iters} iterations per step "
+                               f"with carried residual, {schedule}, every iteration P={P} contributions "
+                               f"reduced over one region [{lo}, {hi})",
+                   "n": n, "k": k, "P": P, "R": P, "iterations_per_step": iters,
+                   "step_starts_from": "zero residual" if not cfg.burn_in else
+                   f"steady-state residual ({cfg.burn_in} untimed iterations of exact top-k on device noise)",
+                   "residual_buffers": pool_n, "selected_per_iteration": nnz_now,
+                   "reduce_region": [lo, hi], "reduce_entries_in": E, "reduce_union_out": U,
+                   "kernel_events_in_timed_region": not args.no_kernel_events},
+        "roofline": roofline, "kernels": kernels, "separate_calls_path": separate,
+        "overlapped_path": overlapped, "sanity": sanity,
+    }
+    return out, host_contrib0, (lo, hi), iters
+
+
+# the kernel that moves the data in each call
+MAIN_KERNEL = {"accumulate": "accumulate_kernel", "threshold": "collect_kernel", "select": "select_kernel",
+               "select_copy": "select_kernel<DenseCopySource>",
+               "accumulate_select": "accumulate_select_kernel",
+               "accumulate_topk_select": "accumulate_collect_kernel", "partition": "partition_kernel",
+               "reduce": "reduce_tile_kernel"}
+
+
+def algorithmic_bytes(n, nnz, E, U):
+    """Bytes the method has to move per call (what the roofline fractions are taken on)."""
+    return {
+        "accumulate": 12.0 * n,                               # read G, read eps, write acc
+        "threshold": 4.0 * n,                                 # one read of acc is the floor
+        "select": 4.0 * n + 12.0 * nnz,                       # read acc; idx, val, zero per entry
+        "select_copy": 4.0 * n + 8.0 * nnz,                   # the same without the zeroing
+        "accumulate_select": 12.0 * n + 8.0 * nnz,            # read G, eps; write eps; idx, val
+        "accumulate_topk_select": 12.0 * n + 12.0 * nnz,      # the same, and a zero per entry
+        "reduce": 8.0 * E + 8.0 * U,                          # entries in, union out
+    }
+
+
+def main_kernel_bytes(call, alg, n):
+    """Bytes of the call's main kernel alone.  In the one-call refresh iteration that
+    kernel forms the accumulator and sets the candidates aside (12 B per element);
+    the emitted entries and their zeros are written by the small kernels after it."""
+    return 12.0 * n if call == "accumulate_topk_select" else alg.get(call)
+
+
+def read_traffic(workload, call):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) for
+    the configuration being timed, as recorded in profiles/hbm_traffic_<workload>.txt
+    ("<call> <bytes_read> <bytes_written>"); None where no such record exists."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                parts = line.split()
+                if len(parts) >= 3 and parts[0] == call:
+                    return float(parts[1]) + float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
+# ----------------------------------------------------------------------------
+# every call on its own, at one configuration's size
+# ----------------------------------------------------------------------------
+def measure_calls(args, torch, np, okt, wl, ev, cfg):
+    """Times each call of the path at this configuration's size, on inputs that are
+    in no cache: destructive calls run on copies (`slots`) that are rewritten,
+    untimed, before every round, and the slots together exceed the last-level
+    cache.  The iteration measured is a refresh iteration (exact threshold, so
+    exactly count_ge entries are selected) and the reuse iterations after it."""
+    w, n, k, P = cfg.w, cfg.n, cfg.k, cfg.P
+    nslots = max(2, int(400e6 // (4 * n)) + 1)
+    nslots = min(nslots, 8)
+    reps = 12
+    slots = [torch.empty(n, dtype=torch.float32, device=DEV) for _ in range(nslots)]
+    G = len(cfg.grads)
+
+    # states: start (before a refresh iteration), acc0 (accumulated, not yet selected),
+    # res1 (after the refresh iteration: what the first reuse iteration starts from)
+    acc0 = cfg.start.clone()
+    okt.okt_residual_accumulate(cfg.grads[0], acc0, w.lr)
+    res1 = cfg.start.clone()
+    okt.okt_accumulate_topk_select(cfg.grads[0], res1, w.lr, k, cfg.th, cfg.count_ge, cfg.idx, cfg.val,
+                                   cfg.nnz, cfg.ws, capacity=cfg.cap)
+    okt.okt_region_partition(cfg.idx, cfg.nnz, n, P, cfg.bounds, cfg.offsets)
+    torch.cuda.synchronize()
+    nnz0 = int(u64_host(np, cfg.nnz)[1])
+    assert nnz0 == int(u64_host(np, cfg.count_ge)[0]) >= k
+    th0 = cfg.th.clone()
+
+    # how many entries the reuse iterations select with that threshold (report only)
+    drift = []
+    walk = res1.clone()
+    for it in range(1, G):
+        okt.okt_accumulate_select(cfg.grads[it], walk, w.lr, th0, cfg.idx, cfg.val, cfg.nnz, cfg.ws,
+                                  capacity=cfg.cap)
+        drift.append(int(u64_host(np, cfg.nnz)[1]))
+    del walk
+    nnz1 = drift[0] if drift else nnz0
+
+    def from_(src):
+        return lambda s: slots[s].copy_(src)
+
+    calls = {
+        "accumulate": (lambda s: okt.okt_residual_accumulate(cfg.grads[s % G], slots[s], w.lr),
+                       from_(cfg.start), 12.0 * n),
+        "threshold": (lambda s: okt.okt_topk_threshold_exact(slots[s], k, cfg.th, cfg.count_ge, cfg.ws),
+                      from_(acc0), 4.0 * n),
+        "select": (lambda s: okt.okt_threshold_select(slots[s], th0, cfg.idx, cfg.val, cfg.nnz, cfg.ws,
+                                                      capacity=cfg.cap),
+                   from_(acc0), 4.0 * n + 12.0 * nnz0),
+        "select_copy": (lambda s: okt.okt_threshold_select_copy(slots[s], th0, cfg.idx, cfg.val, cfg.nnz,
+                                                                cfg.ws, capacity=cfg.cap),
+                        from_(acc0), 4.0 * n + 8.0 * nnz0),
+        "accumulate_topk_select": (lambda s: okt.okt_accumulate_topk_select(
+            cfg.grads[0], slots[s], w.lr, k, cfg.th, cfg.count_ge, cfg.idx, cfg.val, cfg.nnz, cfg.ws,
+            capacity=cfg.cap), from_(cfg.start), 12.0 * n + 12.0 * nnz0),
+    }
+    if G > 1:
+        calls["accumulate_select"] = (lambda s: okt.okt_accumulate_select(
+            cfg.grads[1], slots[s], w.lr, th0, cfg.idx, cfg.val, cfg.nnz, cfg.ws, capacity=cfg.cap),
+            from_(res1), 12.0 * n + 8.0 * nnz1)
+    out = {"n": n, "k": k, "selected_refresh_iteration": nnz0, "selected_reuse_iteration": nnz1,
+           "slots": nslots,
+           "state": "zero residual" if not cfg.burn_in else
+           f"steady-state residual ({cfg.burn_in} untimed iterations of exact top-k on device noise)",
+           "kernels": {}}
+    for name, (call, restore, nbytes) in calls.items():
+        whole, main = time_over_slots(torch, ev, call, nslots, restore, reps)
+        kbytes = main_kernel_bytes(name, {name: nbytes}, n)
+        out["kernels"][name] = {"kernel": MAIN_KERNEL[name], "us_per_call": stats(np, whole, nbytes),
+                                "us_main_kernel": stats(np, main, kbytes)}
+        log(f"[bench] {cfg.name} {name:24s} call {np.median(whole):9.1f} us  kernel {np.median(main):9.1f} us "
+            f"= {kbytes / max(np.median(main), 0.2) * 1e-3 / HBM_PEAK_GBS * 100:5.1f} % of peak")
+    if drift and cfg.burn_in:
+        out["reuse_selected_over_k"] = [round(v / k, 4) for v in drift]
+        out["max_abs_drift"] = round(max(abs(v - k) / k for v in drift), 4)
+    # restore the selection of the refresh iteration for what follows
+    cfg.th.copy_(th0)
+    del slots, acc0
+    out["_res1"] = res1
+    return out
+
+
+def time_partition(torch, np, okt, ev, cfg):
+    times = []
+    for _ in range(12):
+        a, b = ev.around(lambda: okt.okt_region_partition(cfg.idx, cfg.nnz, cfg.n, cfg.P, cfg.bounds,
+                                                          cfg.offsets))
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) * 1e3)
+    return stats(np, times[2:])
+
+
+def time_reduce(args, torch, np, okt, wl, ev, w, lo, hi, whole_space=False):
+    """The lone-region reduce at the configuration's literal shape (latency bound:
+    a few MB), rotating over contribution sets."""
+    sets = []
+    for s in range(8):
+        ci, cv, co = wl.whole_space_contributions(w) if whole_space else wl.contributions(w, lo, hi, stream=s)
+        sets.append((dev_u(torch, np, ci), torch.from_numpy(cv).to(DEV), dev_u(torch, np, co)))
+        if whole_space:
+            break
+    E = int(sets[0][0].numel())
+    out_idx = torch.zeros(E, dtype=torch.int32, device=DEV)
+    out_val = torch.zeros(E, dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    ws = torch.empty(okt.okt_workspace_bytes(hi - lo, w.P), dtype=torch.uint8, device=DEV)
+    whole, main = [], []
+    for dst, how in ((whole, ev.around), (main, ev.kernel)):
+        pairs = []
+        for r in range(20):
+            ci, cv, co = sets[r % len(sets)]
+            pairs.append(how(lambda: okt.okt_sparse_reduce(ci, cv, co, lo, hi, out_idx, out_val, nnz, ws)))
+        torch.cuda.synchronize()
+        dst += [a.elapsed_time(b) * 1e3 for a, b in pairs[4:]]
+    U = int(u64_host(np, nnz)[1])
+    # entries of the contributions that fall inside the region (all of them, except cfg1)
+    inside = int(((sets[-1][0].cpu().numpy().view(np.uint32) >= lo) &
+                  (sets[-1][0].cpu().numpy().view(np.uint32) < hi)).sum())
+    nbytes = 8.0 * inside + 8.0 * U
+    return {"region": [lo, hi], "P": w.P, "entries_in": inside, "union_out": U,
+            "us_per_call": stats(np, whole, nbytes), "us_main_kernel": stats(np, main, nbytes)}
+
+
+def time_reduce_batch(args, torch, np, okt, wl, w, width):
+    """The same reduce kernel over B independent regions of the configuration's
+    shape in one launch, B sized so that the input exceeds 1 GB (far beyond the
+    caches): the sustained rate of the local reduction."""
+    P, m = w.P, w.m
+    E1 = P * m
+    B = args.reduce_batch or max(1, int(1.0e9 // (8 * E1)) + 1)
+    base_sets = min(B, 8 if w.contrib == "zipf" else 32)   # distinct index patterns; values differ per region
+    t0 = time.time()
+    sets = [wl.contributions(w, 0, width, stream=1000 + s) for s in range(base_sets)]
+    idx_cat = np.empty(B * E1, dtype=np.uint32)
+    off = np.empty(B * (P + 1), dtype=np.uint64)
+    lohi = np.empty(2 * B, dtype=np.uint32)
+    slots_of_space = max(1, 0xFFFFFFFF // width)
+    for j in range(B):
+        ci, _, co = sets[j % base_sets]
+        rlo = (j % slots_of_space) * width
+        idx_cat[j * E1:(j + 1) * E1] = ci + np.uint32(rlo)
+        off[j * (P + 1):(j + 1) * (P + 1)] = co + np.uint64(j * E1)
+        lohi[2 * j], lohi[2 * j + 1] = rlo, rlo + width
+    d_idx = dev_u(torch, np, idx_cat)
+    d_val = torch.randn(B * E1, dtype=torch.float32, device=DEV) * 1e-3   # values: any fp32
+    d_off = dev_u(torch, np, off)
+    d_lohi = dev_u(torch, np, lohi)
+    out_idx = torch.zeros(B * E1, dtype=torch.int32, device=DEV)
+    out_val = torch.zeros(B * E1, dtype=torch.float32, device=DEV)
+    nnz = torch.zeros(2 * B, dtype=torch.int64, device=DEV)
+    ws = torch.empty(okt.okt_sparse_reduce_batch_workspace_bytes(B, P, width), dtype=torch.uint8,
+                     device=DEV)
+    log(f"[bench] {w.name} reduce batch: B={B} regions, {B * E1} entries uploaded ({time.time() - t0:.1f}s)")
+    times = []
+    for rep in range(8):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        okt.okt_sparse_reduce_batch(d_idx, d_val, d_off, d_lohi, B, P, width, out_idx, out_val,
+                                    E1, nnz, ws)
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) * 1e3)
+    us = float(np.median(times[2:]))
+    U = int(u64_host(np, nnz)[1::2].sum())
+    nbytes = 8.0 * B * E1 + 8.0 * U
+    log(f"[bench] {w.name} reduce batch: {us:9.1f} us = {nbytes / us * 1e-3 / HBM_PEAK_GBS * 100:5.1f} % of peak")
+    return {"shape": f"P={P}, {m} entries per contribution, region width {width}", "regions": B,
+            "entries_in": B * E1, "union_out": U, "us_per_launch": round(us, 1),
+            "us_min": round(float(np.min(times[2:])), 1),
+            "algorithmic_bytes": nbytes, "achieved_GBs": round(nbytes / us * 1e-3, 1),
+            "frac_of_hbm_peak": round(nbytes / us * 1e-3 / HBM_PEAK_GBS, 4),
+            "entries_per_s": B * E1 / (us * 1e-6)}
+
+
+def time_ceilings(torch, np, okt, ev, n, srcs):
+    """What plain streaming reaches on this GPU at this vector length: the library's
+    copy kernel (4 B in + 4 B out per element) and its read-only sum (4 B in), over
+    buffers that rotate so that no launch finds its data in the last-level cache,
+    timed by the library's own event pair around the kernel."""
+    nbuf = max(2, min(8, int(400e6 // (4 * n)) + 1))
+    bufs = [torch.empty(n, dtype=torch.float32, device=DEV) for _ in range(nbuf)]
+    for i, b in enumerate(bufs):
+        b.copy_(srcs[i % len(srcs)])
+    parts = torch.zeros(okt.STREAM_SUM_PARTIALS, dtype=torch.float32, device=DEV)
+    out = {"n": n}
+    for name, nbytes in (("copy", 8.0 * n), ("read_sum", 4.0 * n)):
+        pairs = []
+        for r in range(16):
+            if name == "copy":
+                pairs.append(ev.kernel(lambda: okt.okt_stream_copy(srcs[r % len(srcs)], bufs[r % nbuf])))
+            else:
+                pairs.append(ev.kernel(lambda: okt.okt_stream_sum(bufs[r % nbuf], parts)))
+        torch.cuda.synchronize()
+        us = [a.elapsed_time(b) * 1e3 for a, b in pairs[4:]]
+        out[name] = stats(np, us, nbytes)
+    return out
+
+
+def time_global_stage(torch, np, okt, ev, cfg, res1, red):
+    """The calls that follow the reduce: global threshold over the reduced values of
+    the own region, global selection on that region, and indexes = local ∩ global
+    with the residual restore.  The global index list is synthetic: every other
+    locally selected index plus as many indices again drawn between them."""
+    w = cfg.w
+    red_idx, red_val, red_nnz = red
+    U = int(u64_host(np, red_nnz)[0])
+    L = int(u64_host(np, cfg.nnz)[0])
+    kg = max(w.k // w.P, 1)
+    mine = cfg.idx[:L]
+    g_idx = torch.unique(torch.cat([mine[::2], (mine[1::2] + 1).clamp_(max=w.n - 1), mine[1::4] + 2])
+                         .clamp_(max=w.n - 1), sorted=True).contiguous()
+    G = int(g_idx.numel())
+    g_nnz = torch.tensor([G], dtype=torch.int64, device=DEV)
+    gth = torch.zeros(1, dtype=torch.float32, device=DEV)
+    gcnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    sel_idx = torch.zeros(max(U, 1), dtype=torch.int32, device=DEV)
+    sel_val = torch.zeros(max(U, 1), dtype=torch.float32, device=DEV)
+    sel_nnz = torch.zeros(2, dtype=torch.int64, device=DEV)
+    inter = torch.zeros(cfg.cap, dtype=torch.int32, device=DEV)
+    icnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    vals = red_val[:U]
+    other = res1.clone()
+    calls = {
+        "global_threshold": lambda: okt.okt_topk_threshold_exact(vals, min(kg, U), gth, gcnt, cfg.ws),
+        "global_select": lambda: okt.okt_coo_threshold_select(
+            red_idx, red_val, red_nnz[:1], gth, sel_idx, sel_val, sel_nnz, cfg.ws, max_nnz=U),
+        "intersect_restore": lambda: okt.okt_index_intersect_restore(
+            res1, cfg.idx, cfg.val, cfg.nnz[:1], g_idx, g_nnz, icnt, cfg.ws, indexes_out=inter,
+            max_local=L),
+        "intersect_zero": lambda: okt.okt_index_intersect_zero(
+            other, cfg.idx, cfg.nnz[:1], g_idx, g_nnz, icnt, cfg.ws, indexes_out=inter, max_local=L),
+    }
+    out = {"reduced_entries": U, "region_k": min(kg, U), "local_entries": L, "global_entries": G}
+    for name, fn in calls.items():
+        times = []
+        for rep in range(10):
+            a, b = ev.around(fn)
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b) * 1e3)
+        out[name + "_us"] = round(float(np.median(times[2:])), 2)
+    out["global_selected"] = int(u64_host(np, sel_nnz)[1])
+    out["intersection"] = int(u64_host(np, icnt)[0])
+    return out
+
+
+def per_config(args, torch, np, okt, wl, ev, name, cfg=None):
+    """Everything measured at one configuration's own size and shape."""
+    w = wl.WORKLOADS[name]
+    out = {"workload": f"{name}: n={w.n:,}, density {w.density_num}/{w.density_den} (k={w.k:,}), "
+                       f"P={w.P}, contributions of {w.m} entries ({w.contrib})"}
+    if name == "cfg5":                         # reduce only
+        width = -(-w.n // w.P)
+        out["reduce"] = time_reduce(args, torch, np, okt, wl, ev, w, 128 * width, 129 * width)
+        out["reduce_batch"] = time_reduce_batch(args, torch, np, okt, wl, w, width)
+        return out
+    if cfg is None:
+        cfg = Config(torch, np, okt, wl, name, ngrads=1 if name == "cfg1" else 4)
+        if w.segments and name != "cfg1":
+            cfg.steady_state()
+    calls = measure_calls(args, torch, np, okt, wl, ev, cfg)
+    res1 = calls.pop("_res1")
+    out.update(calls)
+    # cfg.idx / cfg.nnz hold a reuse iteration's selection: partition what is there
+    out["kernels"]["partition"] = {"kernel": MAIN_KERNEL["partition"],
+                                   "us_per_call": time_partition(torch, np, okt, ev, cfg)}
+    # the selection of the refresh iteration fixes cfg4's region
+    scratch = cfg.start.clone()
+    okt.okt_accumulate_topk_select(cfg.grads[0], scratch, w.lr, w.k, cfg.th, cfg.count_ge, cfg.idx, cfg.val,
+                                   cfg.nnz, cfg.ws, capacity=cfg.cap)
+    okt.okt_region_partition(cfg.idx, cfg.nnz, w.n, w.P, cfg.bounds, cfg.offsets)
+    torch.cuda.synchronize()
+    del scratch
+    lo, hi = reduce_region(cfg, np)
+    out["reduce"] = time_reduce(args, torch, np, okt, wl, ev, w, lo, hi, whole_space=(name == "cfg1"))
+    if name != "cfg1":                         # cfg1's contributions span the whole space: no batch
+        out["reduce_batch"] = time_reduce_batch(args, torch, np, okt, wl, w, hi - lo if name == "cfg4"
+                                                else w.n // w.P)
+        out["ceilings"] = time_ceilings(torch, np, okt, ev, w.n, cfg.grads)
+    if name == "cfg2":
+        # the calls after the reduce, on this configuration's sizes
+        ci, cv, co = wl.contributions(w, lo, hi)
+        E = ci.size
+        red = (torch.zeros(E, dtype=torch.int32, device=DEV), torch.zeros(E, dtype=torch.float32, device=DEV),
+               torch.zeros(2, dtype=torch.int64, device=DEV))
+        okt.okt_sparse_reduce(dev_u(torch, np, ci), torch.from_numpy(cv).to(DEV), dev_u(torch, np, co), lo, hi,
+                              red[0], red[1], red[2], cfg.ws)
+        torch.cuda.synchronize()
+        out["global_stage"] = time_global_stage(torch, np, okt, ev, cfg, res1, red)
+    return out
+
+
+# ----------------------------------------------------------------------------
+# the oracle on the host cores
+# ----------------------------------------------------------------------------
+def cpu_baseline(np, wl, cfg, contrib, region, iters, seconds=14.0):
+    """The numpy oracle, as it stands, on the timed workload and the same inputs:
+    iterations of the step's schedule from a zero residual, one after the other,
+    until about `seconds` of CPU work are done (a bounded sample: an iteration of
+    cfg4 takes several seconds on one core); numpy's own routines use one thread."""
+    from oracle import okt_oracle as orc
+    w = cfg.w
+    lo, hi = region
+    t0 = time.perf_counter()
+    res = np.zeros(w.n, dtype=np.float32)
+    done, th = 0, None
+    while True:
+        it = done % iters
+        if it == 0:
+            res[:] = 0
+        acc = orc.residual_accumulate(cfg.host_grads[it], res, w.lr)
+        if w.refresh(it):
+            th, _ = orc.topk_threshold_exact(acc, w.k, method="partition")
+        idx, val, res, _ = orc.threshold_select(acc, th, capacity=4 * w.k)
+        del acc
+        if it == 0:
+            orc.region_partition(idx, w.n, w.P)
+        orc.sparse_reduce(contrib[0], contrib[1], contrib[2], lo, hi)
+        done += 1
+        dt = time.perf_counter() - t0
+        if dt >= seconds or done >= 64 * iters:
+            break
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as fh:
+            model = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), "")
+    except OSError:
+        pass
+    return {"value": done * w.n / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
+            "seconds": round(dt, 2), "host_cpu": model, "host_threads_available": os.cpu_count(),
+            "sample": f"{done} iteration(s) of the {cfg.name} step (n={w.n:,}: accumulate, exact threshold "
+                      f"by np.partition where the schedule re-evaluates it, select, partition at "
+                      f"iteration 0, reduce of P={w.P} contributions), numpy oracle, same inputs"}
 
 
 def main():
@@ -104,523 +852,45 @@ def main():
 
     okt.load_library()            # fails loudly when the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = wl.WORKLOADS[WORKLOAD]
-    n, k, P = w.n, w.k, w.P
-    lo, hi = 0, n // P                         # the region this worker reduces
+    ev = Events(torch, okt)
+    names = [c for c in args.configs.split(",") if c]
     t0 = time.time()
 
-    # ---------------- inputs: generated on the host, uploaded before timing ----
-    workers = []
-    host_grads0 = None
-    for r in range(args.workers):
-        wr = w if r == 0 else dataclasses.replace(w, seed=w.seed + 7919 * r)
-        grads = [wl.gradient(wr, it) for it in range(ITERS_PER_STEP)]
-        if r == 0:
-            host_grads0 = grads
-        workers.append(Worker(torch, okt, w, grads))
-        log(f"[bench] worker {r}: {ITERS_PER_STEP} gradients of {n} fp32 uploaded "
-            f"({time.time() - t0:.1f}s)")
-    contrib = []
-    host_contrib0 = None
-    for s in range(args.contrib_sets):
-        ci, cv, co = wl.contributions(w, lo, hi, stream=s)
-        if s == 0:
-            host_contrib0 = (ci, cv, co)
-        contrib.append((torch.from_numpy(ci.view(np.int32)).to(dev), torch.from_numpy(cv).to(dev),
-                        torch.from_numpy(co.view(np.int64)).to(dev)))
-    E = int(contrib[0][0].numel())
-    red_idx = torch.zeros(E, dtype=torch.int32, device=dev)
-    red_val = torch.zeros(E, dtype=torch.float32, device=dev)
-    red_nnz = torch.zeros(2, dtype=torch.int64, device=dev)
-    # the reduced region stays sparse, as in Alg.1 (its global top-k selection comes next);
-    # the optional densified copy is a checking aid
-    red_dense = torch.zeros(hi - lo, dtype=torch.float32, device=dev) if args.reduce_dense else None
-    log(f"[bench] {args.contrib_sets} contribution sets (P={P}, E={E}) uploaded "
-        f"({time.time() - t0:.1f}s)")
-
-    stream = torch.cuda.current_stream()
-    side = torch.cuda.Stream()                 # default priority; used by the overlapped variant only
-    side_ws = torch.empty(okt.okt_workspace_bytes(hi - lo, P), dtype=torch.uint8, device=dev)
-    counter = {"reduce": 0}
-
-    def event_pairs(count):
-        """Events that exist already (recorded once), for okt_time_next_kernel."""
-        pairs = []
-        for _ in range(count):
-            a = torch.cuda.Event(enable_timing=True)
-            b = torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            b.record(stream)
-            pairs.append((a, b))
-        return pairs
-
-    def run_step(step, ev=None, only=None, fused=True, overlap=False, kernel_pairs=None,
-                 nnz_log=None):
-        """One step = ITERS_PER_STEP iterations of one worker.  `ev` collects
-        (call, start_event, end_event) for the calls named in `only`.  overlap: the
-        reduce of an iteration goes to a second stream (own workspace), where it runs
-        beside the next iteration's accumulate+select, which does not depend on it."""
-        st = workers[step % len(workers)]
-
-        def timed(name, fn):
-            # inside the timed region only one launch per step is bracketed (the
-            # middle iteration): an event pair costs several microseconds
-            if ev is not None and (only is None or (name in only and it == ITERS_PER_STEP // 2)):
-                if kernel_pairs is not None:
-                    # the library records the pair around the call's main kernel
-                    a, b = kernel_pairs.pop()
-                    okt.okt_time_next_kernel(a, b)
-                    fn()
-                else:
-                    a = torch.cuda.Event(enable_timing=True)
-                    b = torch.cuda.Event(enable_timing=True)
-                    a.record(stream)
-                    fn()
-                    b.record(stream)
-                ev.append((name, a, b))
-            else:
-                fn()
-
-        for it in range(ITERS_PER_STEP):
-            if fused and it == 0:
-                # refresh iteration: accumulate, exact threshold and select in one call
-                timed("accumulate_topk_select", lambda: okt.okt_accumulate_topk_select(
-                    st.grads[it], st.residual, w.lr, k, st.th, st.count_ge, st.idx, st.val,
-                    st.nnz, st.ws, capacity=st.cap))
-            elif fused:
-                # reuse iteration: the threshold is already known, one pass does both
-                timed("accumulate_select", lambda: okt.okt_accumulate_select(
-                    st.grads[it], st.residual, w.lr, st.th, st.idx, st.val, st.nnz, st.ws,
-                    capacity=st.cap))
-            else:
-                timed("accumulate", lambda: okt.okt_residual_accumulate(
-                    st.grads[it], st.residual, w.lr))
-                if it == 0:
-                    timed("threshold", lambda: okt.okt_topk_threshold_exact(
-                        st.residual, k, st.th, st.count_ge, st.ws))
-                timed("select", lambda: okt.okt_threshold_select(
-                    st.residual, st.th, st.idx, st.val, st.nnz, st.ws, capacity=st.cap))
-            if it == 0:
-                timed("partition", lambda: okt.okt_region_partition(
-                    st.idx, st.nnz, n, P, st.bounds, st.offsets))
-            ci, cv, co = contrib[counter["reduce"] % len(contrib)]
-            counter["reduce"] += 1
-            if overlap:
-                okt.okt_sparse_reduce(ci, cv, co, lo, hi, red_idx, red_val, red_nnz, side_ws,
-                                      dense_out=red_dense, stream=side)
-            else:
-                timed("reduce", lambda: okt.okt_sparse_reduce(
-                    ci, cv, co, lo, hi, red_idx, red_val, red_nnz, st.ws, dense_out=red_dense))
-            if nnz_log is not None:          # untimed passes only: this reads back
-                nnz_log.append(int(st.nnz.cpu().numpy().view(np.uint64)[1]))
-
-    def summarise(ev, tail=1.0):
-        """name -> (mean, median, count, min) of the event times in us; `tail` keeps only
-        the last fraction of each call's samples (the first ones run cold)."""
-        per = {}
-        for name, a, b in ev:
-            per.setdefault(name, []).append(a.elapsed_time(b) * 1e3)      # us
-        out = {}
-        for name, v in per.items():
-            v = v[len(v) - max(1, int(len(v) * tail)):]
-            out[name] = (float(np.mean(v)), float(np.median(v)), len(v), float(np.min(v)))
-        return out
-
-    # ---------------- warmup (instrumented: finds the dominant call) ----------
-    ev = []
-    for s in range(args.warmup):
-        run_step(s, ev=ev)
-    torch.cuda.synchronize()
-    warm = summarise(ev, tail=0.5) if ev else {}
-    nnz_seen = int(workers[0].nnz.cpu().numpy().view(np.uint64)[1]) if args.warmup else k
-    calls_per_step = {"accumulate": 1, "threshold": 1, "select": 1, "accumulate_topk_select": 1,
-                      "accumulate_select": ITERS_PER_STEP - 1, "partition": 1,
-                      "reduce": ITERS_PER_STEP}
-    if warm:
-        dominant = max(warm, key=lambda c: warm[c][1] * calls_per_step[c])   # by median
-    else:
-        dominant = "accumulate"
-    for c in CALLS:
-        if c in warm:
-            log(f"[bench] warmup {c:10s} mean {warm[c][0]:8.1f} us  median {warm[c][1]:8.1f} us "
-                f"x{calls_per_step[c]}/step")
-    log(f"[bench] dominant call: {dominant}")
-
-    # ---------------- the timed region: exactly K steps -----------------------
-    ev = None if args.no_kernel_events else []
-    pairs = event_pairs(args.steps + 1) if ev is not None else None
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for s in range(args.steps):
-        run_step(args.warmup + s, ev=ev, only=(dominant,), kernel_pairs=pairs)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    ms_per_step = elapsed * 1e3 / args.steps
-    value = ITERS_PER_STEP * n / (ms_per_step * 1e-3)
-    timed_stats = summarise(ev) if ev else {}
-
-    # ---------------- per-call table (instrumented pass, outside the timing) --
-    ev2 = []
-    for s in range(max(4, args.warmup)):
-        run_step(args.warmup + args.steps + s, ev=ev2)
-    torch.cuda.synchronize()
-    table = summarise(ev2)
-    # the same pass again with the events around the main kernel of every call
-    ev2k = []
-    pairs2 = event_pairs(64 * max(4, args.warmup))
-    for s in range(max(4, args.warmup)):
-        run_step(args.warmup + args.steps + s, ev=ev2k, kernel_pairs=pairs2)
-    torch.cuda.synchronize()
-    table_kernel = summarise(ev2k)
-    # the separate calls (not part of the step any more) for the same table
-    ev2s, ev2sk = [], []
-    pairs3 = event_pairs(64 * 4)
-    for s in range(4):
-        run_step(args.warmup + args.steps + s, ev=ev2s, fused=False)
-    for s in range(4):
-        run_step(args.warmup + args.steps + s, ev=ev2sk, fused=False, kernel_pairs=pairs3)
-    torch.cuda.synchronize()
-    for c, v in summarise(ev2s).items():
-        table.setdefault(c, v)
-    for c, v in summarise(ev2sk).items():
-        table_kernel.setdefault(c, v)
-    nnz_now = int(workers[0].nnz.cpu().numpy().view(np.uint64)[1])
-    U = int(red_nnz.cpu().numpy().view(np.uint64)[1])
-
-    # algorithmic bytes per launch of each call at this workload
-    alg_bytes = {
-        "accumulate": 12.0 * n,                               # read G, read eps, write acc
-        "threshold": 4.0 * n,                                 # one read of acc is the floor
-        "select": 4.0 * n + 12.0 * nnz_now,                   # read acc; idx, val, zero per entry
-        "accumulate_select": 12.0 * n + 8.0 * nnz_now,        # read G, eps; write eps; idx, val
-        "accumulate_topk_select": 12.0 * n + 12.0 * nnz_now,  # the same, and a zero per entry
-        "reduce": 8.0 * E + 8.0 * U + (4.0 * (hi - lo) if args.reduce_dense else 0.0),   # entries in, union out
-    }
-    kernels = {}
-    for c in CALLS:
-        if c in table and c in alg_bytes:
-            us = table[c][0]
-            kernels[c] = {"us_per_call": round(us, 2), "us_median": round(table[c][1], 2),
-                          "us_min": round(table[c][3], 2), "samples": table[c][2],
-                          "calls_per_step": calls_per_step[c],
-                          "algorithmic_bytes": alg_bytes[c],
-                          "achieved_GBs": round(alg_bytes[c] / us * 1e-3, 1),
-                          "frac_of_hbm_peak": round(alg_bytes[c] / us * 1e-3 / HBM_PEAK_GBS, 4)}
-            if c in table_kernel:
-                kernels[c]["us_main_kernel"] = round(table_kernel[c][0], 2)
-        elif c in table:
-            kernels[c] = {"us_per_call": round(table[c][0], 2), "calls_per_step": calls_per_step[c]}
-    dom_us = timed_stats[dominant][0] if dominant in timed_stats else table[dominant][0]
-    achieved = alg_bytes[dominant] / dom_us * 1e-3
-    roofline = {"bound": "hbm", "kernel": dominant, "timed": "events recorded by the library right "
-                "before and after the launch of the call's main kernel, one launch per step inside "
-                "the timed region", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": read_traffic(dominant), "us_per_launch": round(dom_us, 2),
-                "algorithmic_bytes_per_launch": alg_bytes[dominant]}
-
-    # ---------------- the same step with two calls on the reuse iterations ----
-    torch.cuda.synchronize()
-    t_f = time.perf_counter()
-    for s in range(args.steps):
-        run_step(args.warmup + s, fused=False)
-    torch.cuda.synchronize()
-    ms_two = (time.perf_counter() - t_f) * 1e3 / args.steps
-    ev3 = []
-    for s in range(4):
-        run_step(s, ev=ev3, only=("accumulate", "select"), fused=False)
-    torch.cuda.synchronize()
-    two = summarise(ev3)
-    two_call_path = {"what": "the same step made of the separate calls: okt_residual_accumulate, "
-                             "okt_topk_threshold_exact (iteration 0), okt_threshold_select",
-                     "ms_per_step": ms_two, "value": ITERS_PER_STEP * n / (ms_two * 1e-3)}
-    for c in ("accumulate", "select"):
-        us = two[c][0]
-        two_call_path[c] = {"us_per_call": round(us, 2), "algorithmic_bytes": alg_bytes[c],
-                            "achieved_GBs": round(alg_bytes[c] / us * 1e-3, 1),
-                            "frac_of_hbm_peak": round(alg_bytes[c] / us * 1e-3 / HBM_PEAK_GBS, 4)}
-
-    # ---------------- the same step with the reduce on a second stream --------
-    torch.cuda.synchronize()
-    t_o = time.perf_counter()
-    for s in range(args.steps):
-        run_step(args.warmup + s, overlap=True)
-    torch.cuda.synchronize()
-    ms_overlap = (time.perf_counter() - t_o) * 1e3 / args.steps
-    overlapped_path = {"what": "the same step with every okt_sparse_reduce enqueued on a second HIP "
-                               "stream (own workspace), beside the next iteration's accumulate+select; "
-                               "not the headline: one stream is",
-                       "ms_per_step": ms_overlap, "value": ITERS_PER_STEP * n / (ms_overlap * 1e-3)}
-
-    # ---------------- sustained reduce over a batch of regions ----------------
-    reduce_batch = time_reduce_batch(args, torch, np, okt, wl, w, lo, hi)
-
-    # ---------------- report only: how far a reused threshold drifts ----------
-    # entries selected in each iteration of one more (untimed) step over k
-    # (Sec. 5.2 reports the same ratio for real training runs), and the size of
-    # the reduced union over the k/P entries one worker contributes (fill-in)
-    nnz_log = []
-    run_step(args.warmup + args.steps, nnz_log=nnz_log)
-    sanity = {"selected_over_k_per_iteration": [round(v / k, 4) for v in nnz_log],
-              "max_abs_drift": round(max(abs(v - k) / k for v in nnz_log), 4),
-              "reduce_union_over_contribution": round(U / max(E // P, 1), 3)}
-
-    # ---------------- plain streaming kernels: the achievable ceiling ---------
-    ceilings = time_ceilings(torch, np, okt, w, workers)
-    roofline["frac_of_copy_kernel"] = round(achieved / ceilings["copy"]["GBs"], 4)
-    for c in kernels:
-        if "achieved_GBs" in kernels[c] and c != "reduce":
-            kernels[c]["frac_of_copy_kernel"] = round(
-                kernels[c]["achieved_GBs"] / ceilings["copy"]["GBs"], 4)
-
-    # ---------------- the global stage on this worker's share -----------------
-    global_stage = time_global_stage(torch, np, okt, w, workers, red_idx, red_val, red_nnz)
-
-    # ---------------- the oracle on the host cores ----------------------------
+    out = {"metric": "gradient elems/s sparsified & sparse-reduce GB/s; % of MI355X HBM peak",
+           "value": None, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic"}
+    head = None
     cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(np, w, host_grads0, host_contrib0, lo, hi)
+    if not args.no_headline:
+        ngrads = {"cfg2": 10, "cfg3": 8, "cfg4": 3}[args.workload]
+        if args.iters:
+            ngrads = max(2, min(ngrads, args.iters))
+        head = Config(torch, np, okt, wl, args.workload, ngrads=ngrads,
+                      keep_host=not args.no_cpu_baseline)
+        if head.w.segments:
+            head.steady_state()
+        res, host_contrib0, region, iters = headline(args, torch, np, okt, wl, ev, head)
+        out.update(res)
+        log(f"[bench] headline {args.workload}: {res['ms_per_step']:.3f} ms per step, "
+            f"{res['value']:.4g} elements/s ({time.time() - t0:.1f}s)")
+        if not args.no_cpu_baseline:
+            cpu = cpu_baseline(np, wl, head, host_contrib0, region, iters)
+            log(f"[bench] cpu baseline: {cpu['value']:.4g} elements/s ({time.time() - t0:.1f}s)")
+    out["cpu_baseline"] = cpu
 
-    out = {
-        "metric": "gradient elems/s sparsified & sparse-reduce GB/s; % of MI355X HBM peak",
-        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "cfg2: n=25,557,032 fp32 (ResNet-50-sized, 161 segments), "
-                               "density 1% (k=255,571), 10 iterations per step with carried "
-                               "residual, exact threshold at iteration 0 then reused (iterations "
-                               "1-9 accumulate and select in one pass), P=16 contributions "
-                               "reduced over one region of n/16",
-                   "n": n, "k": k, "P": P, "iterations_per_step": ITERS_PER_STEP,
-                   "simulated_workers": len(workers), "selected_per_iteration": nnz_now,
-                   "reduce_entries_in": E, "reduce_union_out": U,
-                   "kernel_events_in_timed_region": not args.no_kernel_events},
-        "roofline": roofline,
-        "cpu_baseline": cpu,
-        "kernels": kernels,
-        "reduce_batch": reduce_batch,
-        "two_call_path": two_call_path,
-        "overlapped_path": overlapped_path,
-        "global_stage": global_stage,
-        "ceilings": ceilings,
-        "sanity": sanity,
-    }
+    blocks = {}
+    for name in names:
+        reuse = head if head is not None and name == args.workload else None
+        blocks[name] = per_config(args, torch, np, okt, wl, ev, name, cfg=reuse)
+        torch.cuda.synchronize()
+        if reuse is None:
+            torch.cuda.empty_cache()
+        log(f"[bench] per_config {name} done ({time.time() - t0:.1f}s)")
+    out["per_config"] = blocks
+    out["reduce_batch"] = {name: b["reduce_batch"] for name, b in blocks.items() if "reduce_batch" in b}
     print(json.dumps(out), flush=True)
-
-
-def read_traffic(call):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-    as recorded in profiles/hbm_traffic_cfg2.txt ("<call> <fetch_bytes> <write_bytes>")."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.txt")
-    try:
-        with open(path) as fh:
-            for line in fh:
-                parts = line.split()
-                if len(parts) >= 3 and parts[0] == call:
-                    return float(parts[1]) + float(parts[2])
-    except OSError:
-        pass
-    return None
-
-
-def time_reduce_batch(args, torch, np, okt, wl, w, lo, hi):
-    """The same reduce kernel over B independent regions of the workload's shape in
-    one launch, B sized so that the input exceeds 1 GB (far beyond the caches)."""
-    dev = "cuda:0"
-    P, m, width = w.P, w.m, hi - lo
-    E1 = P * m
-    B = args.reduce_batch or max(1, int(1.0e9 // (8 * E1)) + 1)
-    base_sets = min(B, 32)            # distinct index patterns; values differ per region
-    t0 = time.time()
-    sets = [wl.contributions(w, 0, width, stream=1000 + s) for s in range(base_sets)]
-    idx_cat = np.empty(B * E1, dtype=np.uint32)
-    off = np.empty(B * (P + 1), dtype=np.uint64)
-    lohi = np.empty(2 * B, dtype=np.uint32)
-    for j in range(B):
-        ci, _, co = sets[j % base_sets]
-        rlo = j * width
-        if rlo + width > 0xFFFFFFFF:
-            rlo = (j % 16) * width
-        idx_cat[j * E1:(j + 1) * E1] = ci + np.uint32(rlo)
-        off[j * (P + 1):(j + 1) * (P + 1)] = co + np.uint64(j * E1)
-        lohi[2 * j], lohi[2 * j + 1] = rlo, rlo + width
-    d_idx = torch.from_numpy(idx_cat.view(np.int32)).to(dev)
-    d_val = torch.randn(B * E1, dtype=torch.float32, device=dev) * 1e-3   # values: any fp32
-    d_off = torch.from_numpy(off.view(np.int64)).to(dev)
-    d_lohi = torch.from_numpy(lohi.view(np.int32)).to(dev)
-    out_idx = torch.zeros(B * E1, dtype=torch.int32, device=dev)
-    out_val = torch.zeros(B * E1, dtype=torch.float32, device=dev)
-    nnz = torch.zeros(2 * B, dtype=torch.int64, device=dev)
-    ws = torch.empty(okt.okt_sparse_reduce_batch_workspace_bytes(B, P, width), dtype=torch.uint8,
-                     device=dev)
-    log(f"[bench] reduce batch: B={B} regions, {B * E1} entries uploaded ({time.time() - t0:.1f}s)")
-    times = []
-    for rep in range(8):
-        a = torch.cuda.Event(enable_timing=True)
-        b = torch.cuda.Event(enable_timing=True)
-        a.record()
-        okt.okt_sparse_reduce_batch(d_idx, d_val, d_off, d_lohi, B, P, width, out_idx, out_val,
-                                    E1, nnz, ws)
-        b.record()
-        torch.cuda.synchronize()
-        times.append(a.elapsed_time(b) * 1e3)
-    us = float(np.median(times[2:]))
-    U = int(nnz.cpu().numpy().view(np.uint64)[1::2].sum())
-    nbytes = 8.0 * B * E1 + 8.0 * U
-    return {"regions": B, "entries_in": B * E1, "union_out": U, "us_per_launch": round(us, 1),
-            "algorithmic_bytes": nbytes, "achieved_GBs": round(nbytes / us * 1e-3, 1),
-            "frac_of_hbm_peak": round(nbytes / us * 1e-3 / HBM_PEAK_GBS, 4),
-            "entries_per_s": B * E1 / (us * 1e-6)}
-
-
-def time_ceilings(torch, np, okt, w, workers):
-    """What plain streaming reaches on this GPU at this vector length: the library's
-    copy kernel (4 B in + 4 B out per element) and its read-only sum (4 B in), over
-    buffers that rotate (40 sources, 3 destinations: no launch finds its data in
-    the 256 MB last-level cache), timed by the library's own event pair around the
-    kernel like the roofline figure."""
-    dev = "cuda:0"
-    srcs = [g for st in workers for g in st.grads]
-    dsts = [torch.empty(w.n, dtype=torch.float32, device=dev) for _ in range(3)]
-    parts = torch.zeros(okt.STREAM_SUM_PARTIALS, dtype=torch.float32, device=dev)
-    reps = 24
-    out = {"n": w.n}
-    for name, nbytes in (("copy", 8.0 * w.n), ("read_sum", 4.0 * w.n)):
-        pairs = []
-        for r in range(reps):
-            a = torch.cuda.Event(enable_timing=True)
-            b = torch.cuda.Event(enable_timing=True)
-            a.record(); b.record()
-            okt.okt_time_next_kernel(a, b)
-            if name == "copy":
-                okt.okt_stream_copy(srcs[r % len(srcs)], dsts[r % len(dsts)])
-            else:
-                okt.okt_stream_sum(srcs[r % len(srcs)], parts)
-            pairs.append((a, b))
-        torch.cuda.synchronize()
-        us = float(np.median([a.elapsed_time(b) * 1e3 for a, b in pairs[4:]]))
-        out[name] = {"us_per_launch": round(us, 2), "bytes": nbytes,
-                     "GBs": round(nbytes / us * 1e-3, 1),
-                     "frac_of_hbm_peak": round(nbytes / us * 1e-3 / HBM_PEAK_GBS, 4)}
-    return out
-
-
-def time_global_stage(torch, np, okt, w, workers, red_idx, red_val, red_nnz):
-    """The calls that follow the reduce (outside the step): global threshold over the
-    reduced values of the own region, global selection on that region, and
-    indexes = local ∩ global with the residual restore.  The global index list is
-    synthetic: every other locally selected index of this worker plus the
-    selection of another simulated worker, about 1.5 k ascending indices."""
-    dev = "cuda:0"
-    st, other = workers[0], workers[1 % len(workers)]
-    U = int(red_nnz.cpu().numpy().view(np.uint64)[0])
-    L = int(st.nnz.cpu().numpy().view(np.uint64)[0])
-    Lo = int(other.nnz.cpu().numpy().view(np.uint64)[0])
-    kg = max(w.k // w.P, 1)
-    g_idx = torch.unique(torch.cat([st.idx[:L:2], other.idx[:Lo]]), sorted=True).contiguous()
-    G = int(g_idx.numel())
-    g_nnz = torch.tensor([G], dtype=torch.int64, device=dev)
-    gth = torch.zeros(1, dtype=torch.float32, device=dev)
-    gcnt = torch.zeros(1, dtype=torch.int64, device=dev)
-    sel_idx = torch.zeros(max(U, 1), dtype=torch.int32, device=dev)
-    sel_val = torch.zeros(max(U, 1), dtype=torch.float32, device=dev)
-    sel_nnz = torch.zeros(2, dtype=torch.int64, device=dev)
-    inter = torch.zeros(st.cap, dtype=torch.int32, device=dev)
-    icnt = torch.zeros(1, dtype=torch.int64, device=dev)
-    vals = red_val[:U]
-    sel_idx2 = torch.zeros(st.cap, dtype=torch.int32, device=dev)
-    sel_val2 = torch.zeros(st.cap, dtype=torch.float32, device=dev)
-    sel_nnz2 = torch.zeros(2, dtype=torch.int64, device=dev)
-    calls = {
-        "global_threshold": lambda: okt.okt_topk_threshold_exact(vals, min(kg, U), gth, gcnt, st.ws),
-        "global_select": lambda: okt.okt_coo_threshold_select(
-            red_idx, red_val, red_nnz[:1], gth, sel_idx, sel_val, sel_nnz, st.ws, max_nnz=U),
-        "intersect_restore": lambda: okt.okt_index_intersect_restore(
-            st.residual, st.idx, st.val, st.nnz[:1], g_idx, g_nnz, icnt, st.ws, indexes_out=inter,
-            max_local=L),
-        "intersect_zero": lambda: okt.okt_index_intersect_zero(
-            other.residual, st.idx, st.nnz[:1], g_idx, g_nnz, icnt, st.ws, indexes_out=inter,
-            max_local=L),
-        "select_copy": lambda: okt.okt_threshold_select_copy(
-            workers[2 % len(workers)].residual, st.th, sel_idx2, sel_val2, sel_nnz2, st.ws),
-    }
-    out = {"reduced_entries": U, "region_k": min(kg, U), "local_entries": L, "global_entries": G}
-    for name, fn in calls.items():
-        times = []
-        for rep in range(10):
-            a = torch.cuda.Event(enable_timing=True)
-            b = torch.cuda.Event(enable_timing=True)
-            a.record()
-            fn()
-            b.record()
-            torch.cuda.synchronize()
-            times.append(a.elapsed_time(b) * 1e3)
-        out[name + "_us"] = round(float(np.median(times[2:])), 2)
-    out["global_selected"] = int(sel_nnz.cpu().numpy().view(np.uint64)[1])
-    out["intersection"] = int(icnt.cpu().numpy().view(np.uint64)[0])
-    return out
-
-
-def cpu_baseline(np, w, grads, contrib, lo, hi, seconds=12.0):
-    """The numpy oracle, as it stands, on whole steps (10 iterations each) of the
-    same workload and the same inputs, repeated until about `seconds` of CPU work
-    are done; the threads numpy's own routines use (none of these do)."""
-    from oracle import okt_oracle as orc
-    t0 = time.perf_counter()
-    res = np.zeros(w.n, dtype=np.float32)
-    steps = 0
-    while True:
-        th = None
-        for it in range(ITERS_PER_STEP):
-            acc = orc.residual_accumulate(grads[it], res, w.lr)
-            if it == 0:
-                th, _ = orc.topk_threshold_exact(acc, w.k, method="partition")
-            idx, val, res, _ = orc.threshold_select(acc, th, capacity=4 * w.k)
-            if it == 0:
-                orc.region_partition(idx, w.n, w.P)
-            orc.sparse_reduce(contrib[0], contrib[1], contrib[2], lo, hi)
-        steps += 1
-        dt = time.perf_counter() - t0
-        if dt >= seconds or steps >= 64:
-            break
-    # the two steps that split trivially (accumulate, select), static chunks over the
-    # host's threads: the same oracle functions, called on slices
-    from concurrent.futures import ThreadPoolExecutor
-    threads = max(1, min(16, os.cpu_count() or 1))
-    cuts = np.linspace(0, w.n, threads + 1).astype(np.int64)
-    pres = np.zeros(w.n, dtype=np.float32)
-
-    def chunk(j, it):
-        a, b = int(cuts[j]), int(cuts[j + 1])
-        acc = orc.residual_accumulate(grads[it][a:b], pres[a:b], w.lr)
-        idx, _, r, _ = orc.threshold_select(acc, th)
-        pres[a:b] = r
-        return idx.size
-
-    t1 = time.perf_counter()
-    piters = 0
-    with ThreadPoolExecutor(threads) as pool:
-        while time.perf_counter() - t1 < seconds / 4 and piters < 200:
-            list(pool.map(lambda j: chunk(j, piters % ITERS_PER_STEP), range(threads)))
-            piters += 1
-    pdt = time.perf_counter() - t1
-    parallel = {"value": piters * w.n / pdt, "unit": "elements/s", "threads": threads,
-                "sample": f"{piters} iterations of accumulate + select only (the steps that split "
-                          "into independent chunks), one static chunk per thread"}
-    model = ""
-    try:
-        with open("/proc/cpuinfo") as fh:
-            model = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), "")
-    except OSError:
-        pass
-    return {"value": steps * ITERS_PER_STEP * w.n / dt, "unit": "elements/s", "cores": 1,
-            "kind": "oracle", "seconds": round(dt, 2), "host_cpu": model,
-            "host_threads_available": os.cpu_count(),
-            "parallel_accumulate_select": parallel,
-            "sample": f"{steps} full steps (10 iterations each, n=25,557,032, residual carried) of "
-                      "the same workload, numpy oracle, np.partition for the exact threshold"}
 
 
 if __name__ == "__main__":

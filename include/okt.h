@@ -147,9 +147,9 @@ int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t k,
 
 /*
  * Threshold top-k selection, packaging into one consecutive COO buffer and
- * residual update (Sec. 3.1.3 "selection according to a threshold only requires
- * n comparisons"; Sec. 3.1.2 packaging; Algorithm 2, line 6, with `indexes`
- * taken as all locally selected entries).
+ * residual update (Sec. 3.1.3: with a threshold at hand the selection is one
+ * comparison per element; Sec. 3.1.2 packaging; Algorithm 2, line 6, with
+ * `indexes` taken as all locally selected entries).
  *   S = {i : key(acc[i]) >= key(*d_threshold)} in ascending i.
  *   d_acc_inout  in   fp32[n] acc;  out  the residual: +0.0f at the emitted
  *                entries, untouched elsewhere
@@ -243,12 +243,16 @@ int okt_accumulate_topk_select(const float* d_grad, float* d_residual_inout, flo
 
 /*
  * Balanced split of the index space [0, n) into R regions by the local top-k
- * entries (Algorithm 1, lines 5-7, space_repartition; Sec. 3.1.1 "each worker
- * calculates the local boundaries of the P regions by balancing the local top-k
- * values"), and the split of the sorted COO buffer by those boundaries.
+ * entries (Algorithm 1, lines 5-7, space_repartition; Sec. 3.1.1: every worker
+ * derives region boundaries that give each region an equal share of its own
+ * top-k entries), and the split of the sorted COO buffer by those boundaries.
  *   d_idx         in   uint32[*d_nnz] ascending (the output of
  *                      okt_threshold_select)
- *   d_nnz         in   uint64[1] on the device (d_nnz_out of the select works)
+ *   d_nnz         in   uint64[1] on the device (d_nnz_out of the select works).
+ *                      A count above n - the all-ones word of a select whose
+ *                      bounded wait gave up - is never used to address d_idx: the
+ *                      call then writes the equal split b[r] = floor(r * n / R)
+ *                      and sets every offset to UINT64_MAX
  *   R             number of regions, >= 1
  *   d_bounds_out  out  uint32[R+1]  b[0] = 0, b[R] = n,
  *                      b[r] = idx[floor(r * nnz / R)]; if nnz = 0 the equal

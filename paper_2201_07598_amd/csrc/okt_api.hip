@@ -29,6 +29,28 @@ void timing_after(hipStream_t stream) {
     g_time_stop = nullptr;
 }
 
+uint32_t device_cus() {
+    constexpr int MAX_DEVICES = 64;
+    constexpr uint32_t FALLBACK = 256;
+    static std::atomic<uint32_t> known[MAX_DEVICES];     // zero-initialised: not asked yet
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();                         // no device is not a launch error
+        return FALLBACK;
+    }
+    uint32_t cus = known[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) {
+            (void)hipGetLastError();
+            v = (int)FALLBACK;
+        }
+        cus = (uint32_t)v > SEL_CUS_MAX ? SEL_CUS_MAX : (uint32_t)v;
+        known[dev].store(cus, std::memory_order_relaxed);
+    }
+    return cus;
+}
+
 static std::atomic<uint32_t> g_spin_limit{0};
 uint32_t spin_limit_setting() { return g_spin_limit.load(std::memory_order_relaxed); }
 

@@ -171,6 +171,11 @@ hipError_t launch_clear_scan_state(void* p, uint64_t words, hipStream_t stream);
 // okt_debug_spin_limit (0 = SPIN_LIMIT).
 uint32_t spin_limit_setting();
 
+// Compute units of the calling thread's current device, asked of the runtime once
+// per device and kept (host side, no allocation); 256 where there is no device
+// to ask, never above 1024.  Sizes the launches that want one workgroup per CU.
+uint32_t device_cus();
+
 // Status of the launches an entry point has just made: OKT_OK, or OKT_ERR_HIP
 // with the runtime's error kept for okt_last_hip_error.
 int launch_status();

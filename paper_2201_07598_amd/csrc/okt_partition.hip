@@ -5,17 +5,9 @@
 // equal-count quantiles is the index stored at position floor(r * nnz / R).
 // O(R) gathers and O(R log nnz) probes; latency only.
 #include "okt_device.h"
+#include "okt_search.h"
 
 namespace okt {
-
-__device__ __forceinline__ uint64_t lower_bound_u32(const uint32_t* a, uint64_t len, uint32_t x) {
-    uint64_t lo = 0, hi = len;
-    while (lo < hi) {
-        const uint64_t mid = lo + ((hi - lo) >> 1);
-        if (a[mid] < x) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
 
 __global__ __launch_bounds__(256) void partition_kernel(
     const uint32_t* __restrict__ idx, const uint64_t* __restrict__ d_nnz, uint64_t n, uint32_t R,
@@ -23,20 +15,9 @@ __global__ __launch_bounds__(256) void partition_kernel(
     const uint64_t nnz = *d_nnz;
     for (uint64_t r = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; r <= R;
          r += (uint64_t)gridDim.x * blockDim.x) {
-        uint32_t b;
-        uint64_t off;
-        if (r == 0) {
-            b = 0; off = 0;
-        } else if (r == R) {
-            b = (uint32_t)n; off = nnz;
-        } else if (nnz == 0) {
-            b = (uint32_t)((r * n) / R); off = 0;      // the naive equal split
-        } else {
-            b = idx[(r * nnz) / R];                    // r, nnz < 2^32: no overflow
-            off = lower_bound_u32(idx, nnz, b);
-        }
-        bounds[r] = b;
-        offsets[r] = off;
+        const PartitionCut cut = partition_cut(idx, nnz, n, R, r);
+        bounds[r] = cut.bound;
+        offsets[r] = cut.offset;
     }
 }
 

@@ -24,10 +24,6 @@
 #include "okt_search.h"
 #include "okt_sizes.h"
 
-#ifndef OKT_RED_EMIT_BITS
-#define OKT_RED_EMIT_BITS 4      // bits of a bitmap word one thread writes out (dense tiles)
-#endif
-
 #include <type_traits>
 
 namespace okt {
@@ -360,7 +356,7 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
         // a thread writes out the hit slots of one EMIT_BITS-wide piece of a bitmap
         // word: a tile has fewer words than the workgroup has threads, a word up
         // to 32 hits, and the slowest thread sets the pace
-        constexpr uint32_t EMIT_BITS = OKT_RED_EMIT_BITS, EMIT_PER = 32 / EMIT_BITS;
+        constexpr uint32_t EMIT_BITS = 4, EMIT_PER = 32 / EMIT_BITS;   // bits of a bitmap word per thread
         for (uint32_t u = tid; u < words * EMIT_PER; u += RED_BLOCK) {
             const uint32_t w = u / EMIT_PER, shift = (u % EMIT_PER) * EMIT_BITS;
             const uint32_t word = s_bits[w];
@@ -462,7 +458,7 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
     // The wide dense tile is for throughput.  A launch that cannot fill the chip
     // anyway is nothing but the latency of its tiles: it takes the narrower dense
     // tile of the ranked shape (more, shorter tiles).
-    if (shape.kind == RED_DENSE && (uint64_t)B * reduce_tiles(max_width, RED_C) <= 3 * 256)
+    if (shape.kind == RED_DENSE && (uint64_t)B * reduce_tiles(max_width, RED_C) <= 3 * (uint64_t)device_cus())
         shape = ReduceShape{RED_C, RED_RANKED};
     const uint32_t slots = shape.slots;
     const size_t region_bytes = reduce_ws_bytes_region(max_width, P, slots);

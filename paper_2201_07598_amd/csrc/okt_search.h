@@ -55,5 +55,23 @@ OKT_SEARCH_FN uint64_t lower_bound_near(const uint32_t* a, uint64_t lo, uint64_t
     }
 }
 
+// Boundary r (0 <= r <= R) of the balanced split of [0, n) by a sorted index list
+// of nnz entries (Sec. 3.1.1), and the list position where region r begins:
+// b[r] = idx[floor(r * nnz / R)], b[0] = 0, b[R] = n; without entries the equal
+// split floor(r * n / R).  A count above n cannot come from a select over n
+// elements - it is the all-ones word a failed call leaves in its counts - and is
+// answered without reading idx: the equal split, every offset all ones, so that
+// whatever consumes the offsets sees empty slices and the failure stays visible.
+struct PartitionCut { uint32_t bound; uint64_t offset; };
+OKT_SEARCH_FN PartitionCut partition_cut(const uint32_t* idx, uint64_t nnz, uint64_t n, uint32_t R,
+                                         uint64_t r) {
+    if (nnz > n) return PartitionCut{r == R ? (uint32_t)n : (uint32_t)((r * n) / R), ~0ull};
+    if (r == 0) return PartitionCut{0u, 0ull};
+    if (r == R) return PartitionCut{(uint32_t)n, nnz};
+    if (nnz == 0) return PartitionCut{(uint32_t)((r * n) / R), 0ull};     // r, n < 2^32: no overflow
+    const uint32_t b = idx[(r * nnz) / R];                                 // r, nnz < 2^32
+    return PartitionCut{b, lower_bound_idx(idx, 0, nnz, b)};
+}
+
 }  // namespace okt
 #endif

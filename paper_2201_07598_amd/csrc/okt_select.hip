@@ -60,7 +60,7 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
         hipLaunchKernelGGL(select_empty_kernel, dim3(1), dim3(1), 0, s, d_nnz_out);
         return launch_status();
     }
-    const SelectShape shape = select_shape(n);
+    const SelectShape shape = select_shape(n, device_cus());
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(n)) return OKT_ERR_WORKSPACE;
     ScanHeader* hdr = (ScanHeader*)d_ws;
     uint64_t* seg_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
@@ -68,7 +68,7 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
     if (launch_clear_scan_state(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
     timing_before(s);
-    hipLaunchKernelGGL((select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET, Source>),
+    hipLaunchKernelGGL((select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, Source>),
                        dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_acc, (uint32_t)n, d_threshold,
                        d_idx_out, d_val_out, capacity, d_nnz_out, hdr, seg_desc, group_desc,
                        shape.nseg, shape.piece);
@@ -162,7 +162,7 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
     if (capacity > 0 && (!d_idx_out || !d_val_out || !aligned(d_idx_out, 4) ||
                          !aligned(d_val_out, 4)))
         return OKT_ERR_INVALID_ARG;
-    const SelectShape shape = select_shape(n);
+    const SelectShape shape = select_shape(n, device_cus());
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(n)) return OKT_ERR_WORKSPACE;
     ScanHeader* hdr = (ScanHeader*)d_ws;
     uint64_t* seg_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
@@ -170,7 +170,7 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
     if (launch_clear_scan_state(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
     timing_before(s);
-    hipLaunchKernelGGL((accumulate_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET>),
+    hipLaunchKernelGGL((accumulate_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH>),
                        dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout, lr,
                        (uint32_t)n, d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out, hdr,
                        seg_desc, group_desc, shape.nseg, shape.piece);
@@ -197,7 +197,7 @@ extern "C" int okt_coo_threshold_select(const uint32_t* d_idx_in, const float* d
     if (capacity > 0 && (!d_idx_out || !d_val_out || !aligned(d_idx_out, 4) ||
                          !aligned(d_val_out, 4)))
         return OKT_ERR_INVALID_ARG;
-    const SelectShape shape = select_shape(max_nnz);
+    const SelectShape shape = select_shape(max_nnz, device_cus());
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(max_nnz))
         return OKT_ERR_WORKSPACE;
     ScanHeader* hdr = (ScanHeader*)d_ws;
@@ -206,7 +206,7 @@ extern "C" int okt_coo_threshold_select(const uint32_t* d_idx_in, const float* d
     if (launch_clear_scan_state(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
     timing_before(s);
-    hipLaunchKernelGGL((coo_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, SEL_TICKET>),
+    hipLaunchKernelGGL((coo_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH>),
                        dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_idx_in, d_val_in, d_nnz_in,
                        (uint32_t)max_nnz, d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out,
                        hdr, seg_desc, group_desc, shape.nseg, shape.piece);

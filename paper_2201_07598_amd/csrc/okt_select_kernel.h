@@ -287,7 +287,7 @@ __device__ __forceinline__ void select_finish(
 // the loop, parks the few selected (index, value) pairs in its LDS stash and
 // zeroes them on the spot, while their cache line is still close by: zeroing
 // them later costs a read-modify-write of a line long gone from the caches.
-template <int BLOCK, int U, int STASH, bool TICKET, typename Test, typename Source>
+template <int BLOCK, int U, int STASH, typename Test, typename Source>
 __device__ __forceinline__ void select_body(
     float* __restrict__ acc, uint32_t n, Test test, Source source, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
@@ -322,7 +322,7 @@ __device__ __forceinline__ void select_body(
 // unzeroed and left to the second walk of select_finish.  With ZERO false the
 // residual is written without the zeros (the parked entries are candidates only:
 // the pass that collects them for the exact threshold of a refresh iteration).
-template <int BLOCK, int U, int STASH, bool TICKET, bool ZERO, typename Test>
+template <int BLOCK, int U, int STASH, bool ZERO, typename Test>
 __device__ __forceinline__ void accumulate_select_body(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, Test test,
     uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
@@ -430,13 +430,8 @@ __device__ __forceinline__ void accumulate_select_body(
                                    stashed, mine, s_count, s_before);
 }
 
-#ifndef OKT_SEL_WAVES_PER_EU
-#define OKT_SEL_ATTR
-#else
-#define OKT_SEL_ATTR __attribute__((amdgpu_waves_per_eu(OKT_SEL_WAVES_PER_EU, OKT_SEL_WAVES_PER_EU)))
-#endif
-template <int BLOCK, int U, int STASH, bool TICKET, typename Source = DenseSource>
-__global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void select_kernel(
+template <int BLOCK, int U, int STASH, typename Source = DenseSource>
+__global__ __launch_bounds__(BLOCK) void select_kernel(
     float* __restrict__ acc, uint32_t n, const float* __restrict__ d_threshold,
     uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
     uint64_t* __restrict__ nnz_out, ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc,
@@ -448,19 +443,17 @@ __global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void select_kernel(
     __shared__ uint32_t s_seg;
     __shared__ uint32_t s_before[2];           // within the group, across groups
 
-    if (TICKET) {
-        if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
-        __syncthreads();
-    }
-    const uint32_t seg = TICKET ? s_seg : blockIdx.x;
+    if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    const uint32_t seg = s_seg;
     const float th = *d_threshold;
     if (th == th) {
-        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestFloat{__builtin_fabsf(th)}, Source{}, idx_out,
+        select_body<BLOCK, U, STASH>(acc, n, TestFloat{__builtin_fabsf(th)}, Source{}, idx_out,
                                              val_out, capacity, nnz_out, hdr, seg_desc,
                                              group_desc, nseg, piece, seg, s_stash, s_count,
                                              s_before);
     } else {
-        select_body<BLOCK, U, STASH, TICKET>(acc, n, TestKey{magnitude_key(th)}, Source{}, idx_out, val_out,
+        select_body<BLOCK, U, STASH>(acc, n, TestKey{magnitude_key(th)}, Source{}, idx_out, val_out,
                                              capacity, nnz_out, hdr, seg_desc, group_desc, nseg,
                                              piece, seg, s_stash, s_count, s_before);
     }
@@ -469,7 +462,7 @@ __global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void select_kernel(
 // The same selection over the values of a sorted COO list whose length is on the
 // device (at most max_nnz): entries at or above the threshold are copied, in
 // order, with their indices; the input is not modified.
-template <int BLOCK, int U, int STASH, bool TICKET>
+template <int BLOCK, int U, int STASH>
 __global__ __launch_bounds__(BLOCK) void coo_select_kernel(
     const uint32_t* __restrict__ idx_in, const float* __restrict__ val_in,
     const uint64_t* __restrict__ d_nnz_in, uint32_t max_nnz,
@@ -481,30 +474,28 @@ __global__ __launch_bounds__(BLOCK) void coo_select_kernel(
     __shared__ uint32_t s_count[WAVES];
     __shared__ uint32_t s_seg;
     __shared__ uint32_t s_before[2];
-    if (TICKET) {
-        if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
-        __syncthreads();
-    }
-    const uint32_t seg = TICKET ? s_seg : blockIdx.x;
+    if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    const uint32_t seg = s_seg;
     const uint64_t have = *d_nnz_in;
     const uint32_t n = have < max_nnz ? (uint32_t)have : max_nnz;
     float* vals = const_cast<float*>(val_in);         // CooSource never writes
     const float th = *d_threshold;
     if (th == th) {
-        select_body<BLOCK, U, STASH, TICKET>(vals, n, TestFloat{__builtin_fabsf(th)},
+        select_body<BLOCK, U, STASH>(vals, n, TestFloat{__builtin_fabsf(th)},
                                              CooSource{idx_in}, idx_out, val_out, capacity,
                                              nnz_out, hdr, seg_desc, group_desc, nseg, piece, seg,
                                              s_stash, s_count, s_before);
     } else {
-        select_body<BLOCK, U, STASH, TICKET>(vals, n, TestKey{magnitude_key(th)},
+        select_body<BLOCK, U, STASH>(vals, n, TestKey{magnitude_key(th)},
                                              CooSource{idx_in}, idx_out, val_out, capacity,
                                              nnz_out, hdr, seg_desc, group_desc, nseg, piece, seg,
                                              s_stash, s_count, s_before);
     }
 }
 
-template <int BLOCK, int U, int STASH, bool TICKET>
-__global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void accumulate_select_kernel(
+template <int BLOCK, int U, int STASH>
+__global__ __launch_bounds__(BLOCK) void accumulate_select_kernel(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n,
     const float* __restrict__ d_threshold, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
@@ -514,18 +505,16 @@ __global__ __launch_bounds__(BLOCK) OKT_SEL_ATTR void accumulate_select_kernel(
     __shared__ uint32_t s_count[WAVES];
     __shared__ uint32_t s_seg;
     __shared__ uint32_t s_before[2];
-    if (TICKET) {
-        if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
-        __syncthreads();
-    }
-    const uint32_t seg = TICKET ? s_seg : blockIdx.x;
+    if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    const uint32_t seg = s_seg;
     const float th = *d_threshold;
     if (th == th) {
-        accumulate_select_body<BLOCK, U, STASH, TICKET, true>(
+        accumulate_select_body<BLOCK, U, STASH, true>(
             grad, res, lr, n, TestFloat{__builtin_fabsf(th)}, idx_out, val_out, capacity, nnz_out,
             hdr, seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     } else {
-        accumulate_select_body<BLOCK, U, STASH, TICKET, true>(
+        accumulate_select_body<BLOCK, U, STASH, true>(
             grad, res, lr, n, TestKey{magnitude_key(th)}, idx_out, val_out, capacity, nnz_out,
             hdr, seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     }

@@ -13,28 +13,15 @@ namespace okt {
 // SEL_U rounds in flight.  The piece length (select_shape below) is never above
 // SEL_PIECE_MAX, which keeps the selected entries of a piece inside the wave's
 // LDS stash up to a local density of SEL_STASH / SEL_PIECE_MAX = 9.8 %.
-#ifndef OKT_SEL_U
-#define OKT_SEL_U 4
-#endif
-#ifndef OKT_SEL_TICKET
-#define OKT_SEL_TICKET true
-#endif
-#ifndef OKT_SEL_BLOCK
-#define OKT_SEL_BLOCK 1024
-#endif
-constexpr int SEL_BLOCK = OKT_SEL_BLOCK;
+constexpr int SEL_BLOCK = 1024;
 constexpr int SEL_WAVES = SEL_BLOCK / 64;
-constexpr int SEL_U = OKT_SEL_U;
+constexpr int SEL_U = 4;
 // The kernels need more than 64 registers, so a CU holds one workgroup at a time
 // anyway: its stash takes nearly the whole LDS (16 waves x 1600 entries x 6 bytes
 // = 150 KB of 160).  Gradients select unevenly - whole layers above the
 // threshold next to layers with nothing - and a piece that overflows its stash
 // is partly walked twice.
-#ifndef OKT_SEL_STASH
-#define OKT_SEL_STASH 1600
-#endif
-constexpr int SEL_STASH = OKT_SEL_STASH;       // entries per wave
-constexpr bool SEL_TICKET = OKT_SEL_TICKET;    // false: measurement builds only
+constexpr int SEL_STASH = 1600;                // entries per wave
 constexpr uint32_t SEL_ROUND = 256u * SEL_U;
 constexpr uint32_t SEL_PIECE_MAX = 16384;
 
@@ -42,27 +29,26 @@ struct SelectShape { uint32_t nseg, piece; };
 // The select kernels run one 1024-thread workgroup per CU at a time, and a
 // workgroup streams for tens of microseconds, so a last round of workgroups that
 // fills only part of the chip costs as much as a full one.  The vector is
-// therefore cut for whole rounds: `rounds` x SEL_CUS workgroups of equal pieces
-// (a multiple of 256 elements, at most SEL_PIECE_MAX).
-#ifndef OKT_SEL_CUS
-#define OKT_SEL_CUS 256
-#endif
-constexpr uint32_t SEL_CUS = OKT_SEL_CUS;
-inline uint64_t select_rounds(uint64_t n) {
-    const uint64_t per_round = (uint64_t)SEL_CUS * SEL_WAVES * SEL_PIECE_MAX;
+// therefore cut for whole rounds: `rounds` x `cus` workgroups of equal pieces
+// (a multiple of 256 elements, at most SEL_PIECE_MAX), `cus` being the number of
+// compute units of the device at hand (device_cus(), never above SEL_CUS_MAX).
+constexpr uint32_t SEL_CUS_MAX = 1024;
+inline uint64_t select_rounds(uint64_t n, uint32_t cus) {
+    const uint64_t per_round = (uint64_t)cus * SEL_WAVES * SEL_PIECE_MAX;
     const uint64_t rounds = (n + per_round - 1) / per_round;
     return rounds ? rounds : 1;
 }
-inline SelectShape select_shape(uint64_t n) {
-    const uint64_t waves = (uint64_t)SEL_CUS * SEL_WAVES * select_rounds(n);
+inline SelectShape select_shape(uint64_t n, uint32_t cus) {
+    const uint64_t waves = (uint64_t)cus * SEL_WAVES * select_rounds(n, cus);
     uint64_t piece = ((n + waves - 1) / waves + 255) / 256 * 256;
     if (piece < SEL_ROUND) piece = SEL_ROUND;
     const uint64_t per_wg = piece * SEL_WAVES;
     return SelectShape{(uint32_t)((n + per_wg - 1) / per_wg), (uint32_t)piece};
 }
-inline size_t select_ws_bytes(uint64_t n) {       // header, segment and group descriptors
-    // never more workgroups than whole rounds: a bound that grows with n
-    const uint64_t t = (uint64_t)SEL_CUS * select_rounds(n);
+// Header, segment and group descriptors.  A bound for any device: a launch has at
+// most cus x rounds <= n / (SEL_WAVES x SEL_PIECE_MAX) + 1 + cus workgroups.
+inline size_t select_ws_bytes(uint64_t n) {
+    const uint64_t t = n / ((uint64_t)SEL_WAVES * SEL_PIECE_MAX) + 1 + SEL_CUS_MAX;
     return 64 + 8 * (size_t)(t + (t + 63) / 64);
 }
 
@@ -107,55 +93,29 @@ inline size_t refresh_ws_bytes(uint64_t n) {
 // sparsely hit region a tile is up to RED_S_MAX slots wide: a first sweep marks
 // the hit slots in a bitmap, the popcount prefix of the bitmap ranks them, and
 // the accumulators are indexed by rank, so the LDS holds hit slots only.
-#ifndef OKT_RED_C
-#define OKT_RED_C 4096
-#endif
-#ifndef OKT_RED_BLOCK
-#define OKT_RED_BLOCK 512
-#endif
-#ifndef OKT_RED_UNROLL
-#define OKT_RED_UNROLL 10
-#endif
-constexpr int RED_BLOCK = OKT_RED_BLOCK;
-constexpr int RED_UNROLL = OKT_RED_UNROLL;      // blocks of 64 entries a wave keeps in flight (short slices)
-constexpr uint32_t RED_C = OKT_RED_C;           // accumulators per tile and round
-#ifndef OKT_RED_S_MAX
-#define OKT_RED_S_MAX 32768
-#endif
-constexpr uint32_t RED_S_MAX = OKT_RED_S_MAX;   // widest tile (bits in the bitmap)
-#ifndef OKT_RED_CHUNKS
-#define OKT_RED_CHUNKS 256
-#endif
-constexpr int RED_CHUNKS = OKT_RED_CHUNKS;      // contributions handled per sweep
+constexpr int RED_BLOCK = 512;
+constexpr int RED_UNROLL = 10;                  // blocks of 64 entries a wave keeps in flight (short slices)
+constexpr uint32_t RED_C = 4096;                // accumulators per tile and round
+constexpr uint32_t RED_S_MAX = 32768;           // widest tile (bits in the bitmap)
+constexpr int RED_CHUNKS = 256;                 // contributions handled per sweep
 
 // Two more shapes of the same kernel spend the same LDS differently.  Very
 // sparsely hit regions: a wider bitmap paid for with fewer accumulators, so that
 // a tile is not cut short by the bitmap with half of its accumulators unused.
 // Densely hit regions (accumulator = slot): no rank-to-slot array and a bitmap
 // only as wide as the accumulators, which leaves room for more of them.
-#ifndef OKT_RED_C_SPARSE
-#define OKT_RED_C_SPARSE 3840
-#endif
-#ifndef OKT_RED_S_SPARSE
-#define OKT_RED_S_SPARSE 49152
-#endif
-#ifndef OKT_RED_C_DENSE
-#define OKT_RED_C_DENSE 6016
-#endif
-constexpr uint32_t RED_C_SPARSE = OKT_RED_C_SPARSE;
-constexpr uint32_t RED_S_SPARSE = OKT_RED_S_SPARSE;
-constexpr uint32_t RED_C_DENSE = OKT_RED_C_DENSE;      // a multiple of 32
+constexpr uint32_t RED_C_SPARSE = 3840;
+constexpr uint32_t RED_S_SPARSE = 49152;
+constexpr uint32_t RED_C_DENSE = 6016;                 // a multiple of 32
 
 // Tile shape for a region `width` wide whose union is expected to hold at most
 // `expected` entries.  Densely hit (at most RED_C_DENSE / RED_C slots per expected
 // entry and accumulator): RED_C_DENSE slots, accumulator = slot, one sweep.  Else
 // ranked tiles as wide - any multiple of 32 slots - as keeps the expected number
-// of hit slots per tile at OKT_RED_FILL of the accumulators: up to RED_S_MAX
+// of hit slots per tile at RED_FILL of the accumulators: up to RED_S_MAX
 // slots with RED_C accumulators, beyond that up to RED_S_SPARSE slots with
 // RED_C_SPARSE accumulators.
-#ifndef OKT_RED_FILL
-#define OKT_RED_FILL 0.9
-#endif
+constexpr double RED_FILL = 0.9;
 enum ReduceKind { RED_DENSE = 0, RED_RANKED = 1, RED_SPARSE = 2 };
 struct ReduceShape {
     uint32_t slots;
@@ -165,7 +125,7 @@ inline ReduceShape reduce_tile_shape(uint64_t width, uint64_t expected) {
     if (width == 0 || expected == 0)
         return expected == 0 && width > RED_C_DENSE ? ReduceShape{RED_S_SPARSE, RED_SPARSE}
                                                     : ReduceShape{RED_C_DENSE, RED_DENSE};
-    const double per_acc = OKT_RED_FILL * (double)width / (double)expected;   // slots per accumulator
+    const double per_acc = RED_FILL * (double)width / (double)expected;   // slots per accumulator
     const double want = per_acc * RED_C;
     if (want <= RED_C_DENSE) return ReduceShape{RED_C_DENSE, RED_DENSE};
     if (want > RED_S_MAX) {

@@ -417,11 +417,11 @@ __global__ __launch_bounds__(BLOCK) void accumulate_collect_kernel(
     const uint32_t lo_key = state->cand_lo;
     const float lo = __uint_as_float(lo_key);               // a key below the Inf/NaN range, or NaN
     if (lo == lo) {
-        accumulate_select_body<BLOCK, U, STASH, true, false>(
+        accumulate_select_body<BLOCK, U, STASH, false>(
             grad, res, lr, n, TestFloat{lo}, cand_idx, cand_val, cand_cap, state->collected, hdr,
             seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     } else {
-        accumulate_select_body<BLOCK, U, STASH, true, false>(
+        accumulate_select_body<BLOCK, U, STASH, false>(
             grad, res, lr, n, TestKey{lo_key}, cand_idx, cand_val, cand_cap, state->collected, hdr,
             seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     }
@@ -463,11 +463,11 @@ __global__ __launch_bounds__(BLOCK) void candidate_select_kernel(
     }
     const float th = *d_threshold;
     if (th == th) {
-        select_body<BLOCK, U, STASH, true>(walked, len, TestFloat{__builtin_fabsf(th)}, source, idx_out,
+        select_body<BLOCK, U, STASH>(walked, len, TestFloat{__builtin_fabsf(th)}, source, idx_out,
                                            val_out, capacity, nnz_out, hdr, seg_desc, group_desc,
                                            nseg, piece, seg, s_stash, s_count, s_before);
     } else {
-        select_body<BLOCK, U, STASH, true>(walked, len, TestKey{magnitude_key(th)}, source, idx_out,
+        select_body<BLOCK, U, STASH>(walked, len, TestKey{magnitude_key(th)}, source, idx_out,
                                            val_out, capacity, nnz_out, hdr, seg_desc, group_desc,
                                            nseg, piece, seg, s_stash, s_count, s_before);
     }
@@ -509,7 +509,7 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
                            dim3(HIST_BLOCK), 0, s, d_acc, (const float*)nullptr, 0.0f,
                            (uint32_t)nsamp, (uint32_t)stride, hist_sample, state, n, k);
         static_assert(CNT_WAVES == SEL_WAVES, "the collect pass is cut like the select");
-        const SelectShape shape = select_shape(n);
+        const SelectShape shape = select_shape(n, device_cus());
         timing_before(s);
         hipLaunchKernelGGL(collect_kernel, dim3(shape.nseg), dim3(CNT_BLOCK), 0, s, d_acc,
                            (uint32_t)n, shape.piece, state, cand, cand_cap);
@@ -523,7 +523,7 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
     // every workgroup ends with up to 2048 returning atomics on the shared histogram:
     // over the candidates (a few MB) a workgroup per CU is plenty, over a whole
     // vector the passes want the memory parallelism of many more
-    const uint64_t grid_max = sampled ? 256 : 2048;
+    const uint64_t grid_max = sampled ? device_cus() : 8 * device_cus();
     const unsigned grid = (unsigned)(steps < grid_max ? (steps ? steps : 1) : grid_max);
     const int was_sampled = sampled ? 1 : 0;
     hipLaunchKernelGGL((radix_hist_kernel<20, RS_BITS1, 1>), dim3(grid), dim3(HIST_BLOCK), 0, s,
@@ -559,7 +559,7 @@ extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual
                                                                            : select_ws_bytes(n);
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < separate) return OKT_ERR_WORKSPACE;
 
-    const SelectShape shape = select_shape(n);
+    const SelectShape shape = select_shape(n, device_cus());
     const size_t scan_bytes = refresh_scan_bytes(n);
     const size_t fixed = threshold_ws_min_bytes() + 2 * scan_bytes;
     const uint64_t cand_cap = ws_bytes > fixed ? ((ws_bytes - fixed) / 8) & ~(uint64_t)63 : 0;
@@ -609,7 +609,8 @@ extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual
     timing_after(s);
 
     const uint64_t steps = (((n / 16) >> 2) + HIST_STEP4 - 1) / HIST_STEP4;
-    const unsigned grid = (unsigned)(steps < 256 ? (steps ? steps : 1) : 256);
+    const uint64_t one_per_cu = device_cus();
+    const unsigned grid = (unsigned)(steps < one_per_cu ? (steps ? steps : 1) : one_per_cu);
     const uint32_t* cand_keys = reinterpret_cast<const uint32_t*>(cand_val);
     hipLaunchKernelGGL((radix_hist_kernel<20, RS_BITS1, 1>), dim3(grid), dim3(HIST_BLOCK), 0, s,
                        d_residual_inout, cand_keys, state, hist1, n, k, cand_cap, 2, d_threshold_out,

@@ -88,7 +88,23 @@ def gpu_reduce(idx_cat, val_cat, chunk_off, lo, hi, capacity=None, dense=True):
             "dense": d_dense[:hi - lo].cpu().numpy() if dense else None}
 
 
-def reduce_tolerance(ref):
+def stated_tolerance(ref):
     """|gpu - ref| <= rtol * sum|v|: rtol 1e-6, or 1e-5 where more than 64
     contributions collide (the stated acceptance of the reduced fp32 values)."""
     return np.where(ref["hits"] > 64, 1e-5, 1e-6) * ref["abs_sum"]
+
+
+def rounding_bound(ref):
+    """What a sum accumulated in fp64, in any order, and rounded once to fp32 can
+    differ from the oracle's by: one fp32 rounding step of the result
+    (2^-23 |ref|, or the subnormal spacing 2^-149) plus the two fp64 sums' own
+    error, at most hits * 2^-53 * sum|v| each."""
+    return (2.0 ** -23 * np.abs(ref["val"].astype(np.float64)) + 2.0 ** -149 +
+            ref["hits"] * 2.0 ** -52 * ref["abs_sum"])
+
+
+def reduce_tolerance(ref):
+    """The bound every reduced value is held to: the stated tolerance AND the
+    rounding bound above (the smaller of the two per entry), so that a dropped or
+    doubled contribution cannot hide inside 1e-6 * sum|v|."""
+    return np.minimum(stated_tolerance(ref), rounding_bound(ref))

@@ -1,7 +1,9 @@
 """GPU parity at the full sizes of the five configurations, through the same
-entry points and launch shapes bench.py times.  The oracle still checks every
-element (numpy handles these lengths in seconds); only the number of iterations
-is cut where the full schedule would take minutes of host time."""
+entry points and launch shapes bench.py times.  The oracle checks every element
+of every iteration (numpy handles these lengths in seconds): cfg2's ten
+iterations, cfg4's three, and cfg3 through its second threshold re-evaluation
+(iterations 0 to 32: the refresh at iteration 32 runs on a residual carried for
+31 iterations of a reused threshold)."""
 import numpy as np
 import pytest
 import torch
@@ -15,10 +17,12 @@ from tests.okt_harness import (DEV, GpuPath, bits_equal, gpu_reduce, reduce_tole
 pytestmark = pytest.mark.gpu
 
 
-def loop(w, iterations, fused=False):
+def loop(w, iterations, fused=False, capsys=None):
     """fused: as bench.py's step does, the iterations that re-evaluate the
     threshold take okt_accumulate_topk_select and those that reuse it
-    okt_accumulate_select."""
+    okt_accumulate_select.  With capsys the per-iteration line goes to the real
+    stdout (a long schedule must not look hung to whoever watches the run)."""
+    import contextlib
     gpu = GpuPath(w.n, 4 * w.k)
     res = np.zeros(w.n, dtype=np.float32)
     th = None
@@ -54,7 +58,8 @@ def loop(w, iterations, fused=False):
         assert bits_equal(gpu.residual.cpu().numpy(), res), it
         if w.refresh(it):
             assert total == cnt
-        print(f"{w.name} it={it} nnz={total} |nnz-k|/k={abs(total - w.k) / w.k:.4f}", flush=True)
+        with capsys.disabled() if capsys is not None else contextlib.nullcontext():
+            print(f"{w.name} it={it} nnz={total} |nnz-k|/k={abs(total - w.k) / w.k:.4f}", flush=True)
     return gpu, ridx
 
 
@@ -90,12 +95,19 @@ def test_cfg2_full_size():
     assert ref["idx"].size > 0.9 * w.P * w.m
 
 
-@pytest.mark.timeout(600)
-@pytest.mark.parametrize("name,iterations", [("cfg2", 3), ("cfg3", 2), ("cfg4", 2)])
-def test_full_size_fused_reuse_iterations(name, iterations):
-    # the step bench.py times: one call per iteration (cfg4 re-evaluates every time);
-    # the bench's vector selects whole layers (the stash-overflow path at full size)
-    loop(wl.WORKLOADS[name], iterations, fused=True)
+@pytest.mark.timeout(800)
+@pytest.mark.parametrize("name,iterations", [("cfg2", 10), ("cfg3", 33), ("cfg4", 3)])
+def test_full_size_full_schedule(name, iterations, capsys):
+    """The schedule bench.py times, at full length: one call per iteration -
+    okt_accumulate_topk_select where Alg.1 re-evaluates the threshold (0-based
+    iteration it with it mod tau' = 0: cfg2 at 0, cfg3 at 0 and 32, cfg4 always),
+    okt_accumulate_select where it reuses it - with threshold, count, index set,
+    values and the whole residual compared with the oracle after every iteration.
+    The layered vectors select whole layers (the stash-overflow path at full size)."""
+    w = wl.WORKLOADS[name]
+    assert [it for it in range(iterations) if w.refresh(it)] == \
+        {"cfg2": [0], "cfg3": [0, 32], "cfg4": [0, 1, 2]}[name]
+    loop(w, iterations, fused=True, capsys=capsys)
 
 
 @pytest.mark.timeout(600)
