@@ -68,8 +68,9 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
     if (launch_clear_scan_state(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
     timing_before(s);
-    hipLaunchKernelGGL((select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, Source>),
-                       dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_acc, (uint32_t)n, d_threshold,
+    auto* kernel = stream_past_cache(n) ? select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, Source, true>
+                                        : select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, Source, false>;
+    hipLaunchKernelGGL(kernel, dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_acc, (uint32_t)n, d_threshold,
                        d_idx_out, d_val_out, capacity, d_nnz_out, hdr, seg_desc, group_desc,
                        shape.nseg, shape.piece);
     timing_after(s);
@@ -170,8 +171,9 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
     if (launch_clear_scan_state(d_ws, scan_ws_bytes(shape.nseg) / 8, s) != hipSuccess)
         return OKT_ERR_HIP;
     timing_before(s);
-    hipLaunchKernelGGL((accumulate_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH>),
-                       dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout, lr,
+    auto* kernel = stream_past_cache(n) ? accumulate_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, true>
+                                        : accumulate_select_kernel<SEL_BLOCK, SEL_U, SEL_STASH, false>;
+    hipLaunchKernelGGL(kernel, dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout, lr,
                        (uint32_t)n, d_threshold, d_idx_out, d_val_out, capacity, d_nnz_out, hdr,
                        seg_desc, group_desc, shape.nseg, shape.piece);
     timing_after(s);

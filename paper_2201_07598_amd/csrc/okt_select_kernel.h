@@ -54,6 +54,21 @@ struct StashMemory {                                 // the stashes of a workgro
     }
 };
 
+// A 16-byte load, optionally with the non-temporal hint.  The hint pays on vectors
+// far larger than the last-level cache (nothing of them is found there again:
+// 4 to 7 % on the walks below) and costs as much on vectors that fit it, where
+// what one iteration writes the next one still finds cached; the host decides by
+// the vector's length.
+template <bool NT>
+__device__ __forceinline__ float4 load_quad(const float4* p) {
+    if (NT) {
+        typedef float v4f __attribute__((ext_vector_type(4)));
+        const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+        return make_float4(v.x, v.y, v.z, v.w);
+    }
+    return *p;
+}
+
 // One round of a wave: 64 lanes x float4 = 256 consecutive elements starting at
 // `first` (lane l holds first + 4l .. first + 4l + 3); sx..sw say which of the
 // lane's components are selected.  Calls sink(rank, index, value) for every
@@ -105,7 +120,7 @@ struct WalkMark {
 // in flight, and feeds every selected element to `sink` in ascending index
 // order, ranks counting from `count`.  Returns the count at the end.  If `mark`
 // is given, it records the first batch after which the count exceeds `limit`.
-template <int U, typename Test, typename Sink>
+template <int U, bool NT = false, typename Test, typename Sink>
 __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start, uint64_t end,
                                                 Test test, Sink&& sink, uint32_t count = 0,
                                                 WalkMark* mark = nullptr, uint32_t limit = 0) {
@@ -121,7 +136,7 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
     auto load_batch = [&](float4* dst, uint64_t at) {     // start is 16-byte aligned
         const float4* src = reinterpret_cast<const float4*>(acc + at) + lane;
 #pragma unroll
-        for (int u = 0; u < U; ++u) dst[u] = src[u * WAVE];
+        for (int u = 0; u < U; ++u) dst[u] = load_quad<NT>(src + u * WAVE);
     };
     if (r + 256 * U <= end) load_batch(v, r);
     for (; r + 256 * U <= end; r += 256 * U) {
@@ -137,7 +152,7 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
     }
     for (; r + 256 <= end; r += 256) {                    // whole rounds short of a batch
         const uint32_t before = count;
-        const float4 x = reinterpret_cast<const float4*>(acc + r)[lane];
+        const float4 x = load_quad<NT>(reinterpret_cast<const float4*>(acc + r) + lane);
         count = select_round((uint32_t)r, x, test(x.x), test(x.y), test(x.z), test(x.w), count, sink);
         note(r, before);
     }
@@ -159,39 +174,64 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
     return count;
 }
 
-// What the select runs over.  DenseSource: a dense vector whose selected elements
-// are zeroed in place (the residual update) and whose positions are the output
-// indices; DenseCopySource: the same without the zeroing.  CooSource: the value
-// array of a sorted COO list, left untouched; the output index of position i is
-// idx_in[i].  CandidateSource: a sorted COO list of candidates drawn from a dense
-// residual (idx_in set), or that residual itself (idx_in null); nothing is
-// zeroed during the walk, an entry's place in the residual is zeroed when the
-// entry is written out.
+// What the select runs over, and what happens to an element of it once its entry
+// has been written to the output.  No walk stores into what it reads: a store
+// between the loads of a streaming loop makes every later load wait for the
+// store's acknowledgement (loads and stores retire through one in-order
+// counter), which cost the zeroing select 15 to 40 % of its time.  The zeros are
+// written when the entries go out, from the stash, in index order - neighbouring
+// lanes, neighbouring addresses - after the walk.
+//   stash_emit(walked, i, o)  entry i of the walked array left the stash for
+//                             output position holding index o
+//   walk_emit(walked, i, o)   the same for an entry written by the second walk of
+//                             a piece that overflowed its stash
+//   restore                   the first pass already zeroed the stashed entries
+//                             (the fused kernel's dense write-back): those that
+//                             do not fit the output are put back
+// DenseSource: a dense vector whose emitted elements are zeroed (the residual
+// update); DenseZeroedSource: the same after a first pass that wrote the zeros of
+// the stashed entries itself; DenseCopySource: a dense vector that is only read.
+// CooSource: the value array of a sorted COO list, left untouched; the output
+// index of position i is idx_in[i].  CandidateSource: a sorted COO list of
+// candidates drawn from a dense residual (idx_in set), or that residual itself
+// (idx_in null); an entry's place in the residual is zeroed when it goes out.
 struct DenseSource {
-    static constexpr bool zero = true;
+    static constexpr bool restore = false;
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return i; }
-    __device__ __forceinline__ void on_emit(float*, uint32_t, uint32_t) const {}
+    __device__ __forceinline__ void stash_emit(float* walked, uint32_t i, uint32_t) const { walked[i] = 0.0f; }
+    __device__ __forceinline__ void walk_emit(float* walked, uint32_t i, uint32_t) const { walked[i] = 0.0f; }
 };
-struct DenseCopySource {                     // a dense vector that is only read
-    static constexpr bool zero = false;
+struct DenseZeroedSource {
+    static constexpr bool restore = true;
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return i; }
-    __device__ __forceinline__ void on_emit(float*, uint32_t, uint32_t) const {}
+    __device__ __forceinline__ void stash_emit(float*, uint32_t, uint32_t) const {}
+    __device__ __forceinline__ void walk_emit(float* walked, uint32_t i, uint32_t) const { walked[i] = 0.0f; }
+};
+struct DenseCopySource {
+    static constexpr bool restore = false;
+    __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return i; }
+    __device__ __forceinline__ void stash_emit(float*, uint32_t, uint32_t) const {}
+    __device__ __forceinline__ void walk_emit(float*, uint32_t, uint32_t) const {}
 };
 struct CooSource {
-    static constexpr bool zero = false;
+    static constexpr bool restore = false;
     const uint32_t* idx_in;
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return idx_in[i]; }
-    __device__ __forceinline__ void on_emit(float*, uint32_t, uint32_t) const {}
+    __device__ __forceinline__ void stash_emit(float*, uint32_t, uint32_t) const {}
+    __device__ __forceinline__ void walk_emit(float*, uint32_t, uint32_t) const {}
 };
 struct CandidateSource {
-    static constexpr bool zero = false;
+    static constexpr bool restore = false;
     const uint32_t* idx_in;
     float* res;                              // used only when idx_in is set
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return idx_in ? idx_in[i] : i; }
     // `walked` is the array the walk runs over, `i` the position in it, `o` the output index
-    __device__ __forceinline__ void on_emit(float* walked, uint32_t i, uint32_t o) const {
+    __device__ __forceinline__ void stash_emit(float* walked, uint32_t i, uint32_t o) const {
         if (idx_in) res[o] = 0.0f;
         else walked[i] = 0.0f;
+    }
+    __device__ __forceinline__ void walk_emit(float* walked, uint32_t i, uint32_t o) const {
+        stash_emit(walked, i, o);
     }
 };
 
@@ -199,13 +239,12 @@ struct CandidateSource {
 // everything before it from the chained scan, and each wave writes its pairs to
 // their final place.  On entry the wave has seen `count` selected entries in its
 // piece [start, end) and holds the first `stashed` of them (in index order) in
-// its LDS stash, already zeroed in the residual (if the source is zeroed at
-// all); entries past the stash are untouched.  Entries that do not fit the
-// output are put back.  A wave whose stash did not hold everything (locally
-// dense selection) writes out the `resume_count` entries that lie before
-// `resume_at`, puts the other stashed ones back, and walks the rest of its piece,
-// from `resume_at`, a second time, writing directly.
-template <int BLOCK, int U, int STASH, typename Test, typename Source>
+// its LDS stash; nothing of the piece has been changed, unless the source says
+// that the first pass zeroed the stashed entries itself.  A wave whose stash did
+// not hold everything (locally dense selection) writes out the `resume_count`
+// entries that lie before `resume_at` and walks the rest of its piece, from
+// `resume_at`, a second time, writing directly.
+template <int BLOCK, int U, int STASH, bool NT, typename Test, typename Source>
 __device__ __forceinline__ void select_finish(
     float* __restrict__ acc, Test test, Source source, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
@@ -248,28 +287,21 @@ __device__ __forceinline__ void select_finish(
             const uint32_t o = source.out_index(e.idx);
             idx_out[pos] = o;
             val_out[pos] = e.val;
-            source.on_emit(acc, e.idx, o);
-        } else if (Source::zero) {
+            source.stash_emit(acc, e.idx, o);
+        } else if (Source::restore) {
             acc[e.idx] = e.val;             // output full: the entry stays in the residual
         }
     }
     if (!all_stashed) {
         (void)start;
-        if (Source::zero) {
-            for (uint32_t j = resume_count + lane; j < stashed; j += WAVE) {
-                const StashEntry e = mine[j];
-                acc[e.idx] = e.val;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // stores land before the re-read
-        }
-        select_walk<U>(acc, resume_at, end, test, [&](uint32_t rank, uint32_t i, float x) {
+        // every stashed entry at or after resume_at is met again by this walk, untouched
+        select_walk<U, NT>(acc, resume_at, end, test, [&](uint32_t rank, uint32_t i, float x) {
             const uint64_t pos = first + rank;
             if (pos < capacity) {
                 const uint32_t o = source.out_index(i);
                 idx_out[pos] = o;
                 val_out[pos] = x;
-                if (Source::zero) acc[i] = 0.0f;
-                source.on_emit(acc, i, o);
+                source.walk_emit(acc, i, o);
             }
         }, resume_count);
     }
@@ -283,11 +315,11 @@ __device__ __forceinline__ void select_finish(
 }
 
 // Workgroup `seg` (a ticket) owns WAVES consecutive pieces of `piece` elements,
-// one per wave.  A wave streams its piece once, with no barrier and no wait in
-// the loop, parks the few selected (index, value) pairs in its LDS stash and
-// zeroes them on the spot, while their cache line is still close by: zeroing
-// them later costs a read-modify-write of a line long gone from the caches.
-template <int BLOCK, int U, int STASH, typename Test, typename Source>
+// one per wave.  A wave streams its piece once, with no barrier, no wait and no
+// store in the loop, and parks the few selected (index, value) pairs in its LDS
+// stash; what the source wants done to an emitted element (the zero of the
+// residual update) happens when the stash is written out.
+template <int BLOCK, int U, int STASH, bool NT, typename Test, typename Source>
 __device__ __forceinline__ void select_body(
     float* __restrict__ acc, uint32_t n, Test test, Source source, uint32_t* __restrict__ idx_out,
     float* __restrict__ val_out, uint64_t capacity, uint64_t* __restrict__ nnz_out,
@@ -300,16 +332,13 @@ __device__ __forceinline__ void select_body(
     const WaveStash mine = s_stash.of(wave, start);
     WalkMark over = {start, 0u, false};          // the batch in which the stash ran full
     const uint32_t count =
-        select_walk<U>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
-            if (rank < (uint32_t)STASH) {
-                mine.put(rank, i, x);
-                if (Source::zero) acc[i] = 0.0f;
-            }
+        select_walk<U, NT>(acc, start, end, test, [&](uint32_t rank, uint32_t i, float x) {
+            if (rank < (uint32_t)STASH) mine.put(rank, i, x);
         }, 0u, &over, (uint32_t)STASH);
-    select_finish<BLOCK, U, STASH>(acc, test, source, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
-                                   group_desc, nseg, seg, start, end, count,
-                                   count < (uint32_t)STASH ? count : (uint32_t)STASH, over.at,
-                                   over.count, mine, s_count, s_before);
+    select_finish<BLOCK, U, STASH, NT>(acc, test, source, idx_out, val_out, capacity, nnz_out, hdr,
+                                       seg_desc, group_desc, nseg, seg, start, end, count,
+                                       count < (uint32_t)STASH ? count : (uint32_t)STASH, over.at,
+                                       over.count, mine, s_count, s_before);
 }
 
 // The accumulate and the select in one pass (reuse iterations of Ok-Topk SGD,
@@ -322,7 +351,7 @@ __device__ __forceinline__ void select_body(
 // unzeroed and left to the second walk of select_finish.  With ZERO false the
 // residual is written without the zeros (the parked entries are candidates only:
 // the pass that collects them for the exact threshold of a refresh iteration).
-template <int BLOCK, int U, int STASH, bool ZERO, typename Test>
+template <int BLOCK, int U, int STASH, bool ZERO, bool NT, typename Test>
 __device__ __forceinline__ void accumulate_select_body(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, Test test,
     uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
@@ -377,8 +406,8 @@ __device__ __forceinline__ void accumulate_select_body(
         const float4* esrc = reinterpret_cast<const float4*>(res + at) + lane;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            g[u] = gsrc[u * WAVE];
-            e[u] = esrc[u * WAVE];
+            g[u] = load_quad<NT>(gsrc + u * WAVE);
+            e[u] = load_quad<NT>(esrc + u * WAVE);
         }
     };
     if (r + 256 * U <= end) load_batch(r);
@@ -399,8 +428,8 @@ __device__ __forceinline__ void accumulate_select_body(
                                    test(a[u].z), test(a[u].w));
     }
     for (; r + 256 <= end; r += 256) {               // whole rounds short of a batch
-        const float4 gq = reinterpret_cast<const float4*>(grad + r)[lane];
-        const float4 eq = reinterpret_cast<const float4*>(res + r)[lane];
+        const float4 gq = load_quad<NT>(reinterpret_cast<const float4*>(grad + r) + lane);
+        const float4 eq = load_quad<NT>(reinterpret_cast<const float4*>(res + r) + lane);
         const float4 a = make_float4(fma2(eq.x, gq.x), fma2(eq.y, gq.y), fma2(eq.z, gq.z),
                                      fma2(eq.w, gq.w));
         reinterpret_cast<float4*>(res + r)[lane] =
@@ -423,14 +452,14 @@ __device__ __forceinline__ void accumulate_select_body(
         if (inside[2]) res[i + 2] = out.z;
         if (inside[3]) res[i + 3] = out.w;
     }
-    // every stashed entry lies before resume_at: nothing to put back before the second walk
-    using Source = typename std::conditional<ZERO, DenseSource, DenseCopySource>::type;
-    select_finish<BLOCK, U, STASH>(res, test, Source{}, idx_out, val_out, capacity, nnz_out, hdr, seg_desc,
-                                   group_desc, nseg, seg, start, end, count, stashed, resume_at,
-                                   stashed, mine, s_count, s_before);
+    // every stashed entry lies before resume_at, and is already zeroed where ZERO is set
+    using Source = typename std::conditional<ZERO, DenseZeroedSource, DenseCopySource>::type;
+    select_finish<BLOCK, U, STASH, NT>(res, test, Source{}, idx_out, val_out, capacity, nnz_out, hdr,
+                                       seg_desc, group_desc, nseg, seg, start, end, count, stashed,
+                                       resume_at, stashed, mine, s_count, s_before);
 }
 
-template <int BLOCK, int U, int STASH, typename Source = DenseSource>
+template <int BLOCK, int U, int STASH, typename Source, bool NT>
 __global__ __launch_bounds__(BLOCK) void select_kernel(
     float* __restrict__ acc, uint32_t n, const float* __restrict__ d_threshold,
     uint32_t* __restrict__ idx_out, float* __restrict__ val_out, uint64_t capacity,
@@ -448,12 +477,12 @@ __global__ __launch_bounds__(BLOCK) void select_kernel(
     const uint32_t seg = s_seg;
     const float th = *d_threshold;
     if (th == th) {
-        select_body<BLOCK, U, STASH>(acc, n, TestFloat{__builtin_fabsf(th)}, Source{}, idx_out,
+        select_body<BLOCK, U, STASH, NT>(acc, n, TestFloat{__builtin_fabsf(th)}, Source{}, idx_out,
                                              val_out, capacity, nnz_out, hdr, seg_desc,
                                              group_desc, nseg, piece, seg, s_stash, s_count,
                                              s_before);
     } else {
-        select_body<BLOCK, U, STASH>(acc, n, TestKey{magnitude_key(th)}, Source{}, idx_out, val_out,
+        select_body<BLOCK, U, STASH, NT>(acc, n, TestKey{magnitude_key(th)}, Source{}, idx_out, val_out,
                                              capacity, nnz_out, hdr, seg_desc, group_desc, nseg,
                                              piece, seg, s_stash, s_count, s_before);
     }
@@ -482,19 +511,19 @@ __global__ __launch_bounds__(BLOCK) void coo_select_kernel(
     float* vals = const_cast<float*>(val_in);         // CooSource never writes
     const float th = *d_threshold;
     if (th == th) {
-        select_body<BLOCK, U, STASH>(vals, n, TestFloat{__builtin_fabsf(th)},
+        select_body<BLOCK, U, STASH, false>(vals, n, TestFloat{__builtin_fabsf(th)},
                                              CooSource{idx_in}, idx_out, val_out, capacity,
                                              nnz_out, hdr, seg_desc, group_desc, nseg, piece, seg,
                                              s_stash, s_count, s_before);
     } else {
-        select_body<BLOCK, U, STASH>(vals, n, TestKey{magnitude_key(th)},
+        select_body<BLOCK, U, STASH, false>(vals, n, TestKey{magnitude_key(th)},
                                              CooSource{idx_in}, idx_out, val_out, capacity,
                                              nnz_out, hdr, seg_desc, group_desc, nseg, piece, seg,
                                              s_stash, s_count, s_before);
     }
 }
 
-template <int BLOCK, int U, int STASH>
+template <int BLOCK, int U, int STASH, bool NT>
 __global__ __launch_bounds__(BLOCK) void accumulate_select_kernel(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n,
     const float* __restrict__ d_threshold, uint32_t* __restrict__ idx_out,
@@ -510,11 +539,11 @@ __global__ __launch_bounds__(BLOCK) void accumulate_select_kernel(
     const uint32_t seg = s_seg;
     const float th = *d_threshold;
     if (th == th) {
-        accumulate_select_body<BLOCK, U, STASH, true>(
+        accumulate_select_body<BLOCK, U, STASH, true, NT>(
             grad, res, lr, n, TestFloat{__builtin_fabsf(th)}, idx_out, val_out, capacity, nnz_out,
             hdr, seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     } else {
-        accumulate_select_body<BLOCK, U, STASH, true>(
+        accumulate_select_body<BLOCK, U, STASH, true, NT>(
             grad, res, lr, n, TestKey{magnitude_key(th)}, idx_out, val_out, capacity, nnz_out,
             hdr, seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     }

@@ -52,6 +52,11 @@ inline size_t select_ws_bytes(uint64_t n) {
     return 64 + 8 * (size_t)(t + (t + 63) / 64);
 }
 
+// Vectors far longer than the 256 MB last-level cache are read with the
+// non-temporal hint (nothing of them is found cached again); shorter ones are not:
+// what one iteration writes the next one still finds there.
+inline bool stream_past_cache(uint64_t n) { return n >= (96u << 20); }      // 384 MB of fp32 and up
+
 // ---- index intersection and residual restore ----
 constexpr int RST_BLOCK = 256;
 constexpr int RST_ROWS = 4;                              // entries per thread

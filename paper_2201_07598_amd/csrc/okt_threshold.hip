@@ -401,7 +401,7 @@ __global__ void refresh_init_kernel(RadixState* state, uint32_t* hist, uint32_t 
 // residual becomes the accumulator (no zeros), every element at or above the
 // bound goes, in index order, to the candidate list, whose length (written,
 // found) lands in state->collected.
-template <int BLOCK, int U, int STASH>
+template <int BLOCK, int U, int STASH, bool NT>
 __global__ __launch_bounds__(BLOCK) void accumulate_collect_kernel(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, RadixState* state,
     uint32_t* __restrict__ cand_idx, float* __restrict__ cand_val, uint64_t cand_cap,
@@ -417,11 +417,11 @@ __global__ __launch_bounds__(BLOCK) void accumulate_collect_kernel(
     const uint32_t lo_key = state->cand_lo;
     const float lo = __uint_as_float(lo_key);               // a key below the Inf/NaN range, or NaN
     if (lo == lo) {
-        accumulate_select_body<BLOCK, U, STASH, false>(
+        accumulate_select_body<BLOCK, U, STASH, false, NT>(
             grad, res, lr, n, TestFloat{lo}, cand_idx, cand_val, cand_cap, state->collected, hdr,
             seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     } else {
-        accumulate_select_body<BLOCK, U, STASH, false>(
+        accumulate_select_body<BLOCK, U, STASH, false, NT>(
             grad, res, lr, n, TestKey{lo_key}, cand_idx, cand_val, cand_cap, state->collected, hdr,
             seg_desc, group_desc, nseg, piece, seg, s_stash, s_count, s_before);
     }
@@ -463,11 +463,11 @@ __global__ __launch_bounds__(BLOCK) void candidate_select_kernel(
     }
     const float th = *d_threshold;
     if (th == th) {
-        select_body<BLOCK, U, STASH>(walked, len, TestFloat{__builtin_fabsf(th)}, source, idx_out,
+        select_body<BLOCK, U, STASH, false>(walked, len, TestFloat{__builtin_fabsf(th)}, source, idx_out,
                                            val_out, capacity, nnz_out, hdr, seg_desc, group_desc,
                                            nseg, piece, seg, s_stash, s_count, s_before);
     } else {
-        select_body<BLOCK, U, STASH>(walked, len, TestKey{magnitude_key(th)}, source, idx_out,
+        select_body<BLOCK, U, STASH, false>(walked, len, TestKey{magnitude_key(th)}, source, idx_out,
                                            val_out, capacity, nnz_out, hdr, seg_desc, group_desc,
                                            nseg, piece, seg, s_stash, s_count, s_before);
     }
@@ -602,7 +602,9 @@ extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual
                        dim3(HIST_BLOCK), 0, s, d_residual_inout, d_grad, lr, (uint32_t)nsamp,
                        (uint32_t)stride, hist_sample, state, n, k);
     timing_before(s);
-    hipLaunchKernelGGL((accumulate_collect_kernel<SEL_BLOCK, SEL_U, SEL_STASH>), dim3(shape.nseg),
+    auto* collect = stream_past_cache(n) ? accumulate_collect_kernel<SEL_BLOCK, SEL_U, SEL_STASH, true>
+                                         : accumulate_collect_kernel<SEL_BLOCK, SEL_U, SEL_STASH, false>;
+    hipLaunchKernelGGL(collect, dim3(shape.nseg),
                        dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout, lr, (uint32_t)n, state,
                        cand_idx, cand_val, cand_cap, header(scan_a), segs(scan_a),
                        segs(scan_a) + shape.nseg, shape.nseg, shape.piece);
