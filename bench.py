@@ -133,17 +133,30 @@ class Events:
         return a, b
 
 
+_FLUSH = {}
+
+
+def flush_caches(torch):
+    """One read of 512 MB that nothing else uses: afterwards the 256 MB last-level
+    cache holds neither a timed call's input nor dirty lines of the untimed copies
+    that prepared it (which the timed call would otherwise pay to write back)."""
+    if "buf" not in _FLUSH:
+        _FLUSH["buf"] = torch.ones(1 << 27, dtype=torch.float32, device=DEV)
+    _FLUSH["buf"].sum()
+
+
 def time_over_slots(torch, ev, call, nslots, restore, reps):
     """call(slot) timed once per slot and round, both around the whole call and (a
     second pass) around its main kernel; restore(slot), untimed, rewrites the
-    slot's buffers before every round.  With several slots whose buffers together
-    exceed the 256 MB last-level cache no call finds its input cached.  Returns
-    (us per call, us per main kernel)."""
+    slot's buffers before every round, and the caches are flushed after that.
+    With several slots whose buffers together exceed the 256 MB last-level cache
+    no call finds its input cached.  Returns (us per call, us per main kernel)."""
     whole, main = [], []
     for dst, how in ((whole, ev.around), (main, ev.kernel)):
         while len(dst) < reps:
             for s in range(nslots):
                 restore(s)
+            flush_caches(torch)
             torch.cuda.synchronize()
             pairs = [how(lambda s=s: call(s)) for s in range(nslots)]
             torch.cuda.synchronize()

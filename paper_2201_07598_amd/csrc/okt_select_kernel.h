@@ -119,8 +119,9 @@ struct WalkMark {
 // Walks the wave's piece [start, end) of acc in rounds of 256 elements, U rounds
 // in flight, and feeds every selected element to `sink` in ascending index
 // order, ranks counting from `count`.  Returns the count at the end.  If `mark`
-// is given, it records the first batch after which the count exceeds `limit`.
-template <int U, bool NT = false, typename Test, typename Sink>
+// is given, it records the first batch after which the count exceeds `limit`;
+// with STOP the walk ends right there (what it returns is then no total).
+template <int U, bool NT = false, bool STOP = false, typename Test, typename Sink>
 __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start, uint64_t end,
                                                 Test test, Sink&& sink, uint32_t count = 0,
                                                 WalkMark* mark = nullptr, uint32_t limit = 0) {
@@ -129,9 +130,6 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
     auto note = [&](uint64_t batch_start, uint32_t before) {
         if (mark && !mark->hit && count > limit) *mark = WalkMark{batch_start, before, true};
     };
-    // The sink may store to acc.  Loads and stores retire through one in-order
-    // counter, so the loads of the next batch are issued before this batch is
-    // handed to the sink: they never queue behind its stores.
     float4 v[U], w[U];
     auto load_batch = [&](float4* dst, uint64_t at) {     // start is 16-byte aligned
         const float4* src = reinterpret_cast<const float4*>(acc + at) + lane;
@@ -149,12 +147,14 @@ __device__ __forceinline__ uint32_t select_walk(const float* acc, uint64_t start
             count = select_round((uint32_t)r + 256u * u, w[u], test(w[u].x), test(w[u].y),
                                  test(w[u].z), test(w[u].w), count, sink);
         note(r, before);
+        if (STOP && mark->hit) return count;
     }
     for (; r + 256 <= end; r += 256) {                    // whole rounds short of a batch
         const uint32_t before = count;
         const float4 x = load_quad<NT>(reinterpret_cast<const float4*>(acc + r) + lane);
         count = select_round((uint32_t)r, x, test(x.x), test(x.y), test(x.z), test(x.w), count, sink);
         note(r, before);
+        if (STOP && mark->hit) return count;
     }
     for (; r < end; r += 256) {                           // the ragged end of the vector
         const uint32_t before = count;
@@ -293,17 +293,37 @@ __device__ __forceinline__ void select_finish(
         }
     }
     if (!all_stashed) {
+        // The rest of the piece, from resume_at on, is walked again, a stash-full at
+        // a time: a walk that only reads until the stash has run over, then the
+        // entries that lie before the batch in which it did are written out (the
+        // positions are known now), and so on from that batch.  Loads and stores
+        // stay apart, as in the first walk.  A batch holds at most 256 * U elements,
+        // fewer than the stash does, so every turn emits at least one batch.
+        static_assert(256 * U <= STASH, "a batch of rounds fits the stash");
         (void)start;
-        // every stashed entry at or after resume_at is met again by this walk, untouched
-        select_walk<U, NT>(acc, resume_at, end, test, [&](uint32_t rank, uint32_t i, float x) {
-            const uint64_t pos = first + rank;
-            if (pos < capacity) {
-                const uint32_t o = source.out_index(i);
-                idx_out[pos] = o;
-                val_out[pos] = x;
-                source.walk_emit(acc, i, o);
+        uint64_t at = resume_at;
+        uint32_t done = resume_count;               // entries of the piece written so far
+        while (at < end) {
+            WalkMark over = {end, 0u, false};
+            const uint32_t seen = select_walk<U, NT, true>(
+                acc, at, end, test, [&](uint32_t rank, uint32_t i, float x) {
+                    if (rank - done < (uint32_t)STASH) mine.put(rank - done, i, x);
+                }, done, &over, done + (uint32_t)STASH);
+            const uint32_t upto = over.hit ? over.count : seen;
+            for (uint32_t j = lane; j < upto - done; j += WAVE) {
+                const uint64_t pos = first + done + j;
+                const StashEntry e = mine[j];
+                if (pos < capacity) {
+                    const uint32_t o = source.out_index(e.idx);
+                    idx_out[pos] = o;
+                    val_out[pos] = e.val;
+                    source.walk_emit(acc, e.idx, o);
+                }
             }
-        }, resume_count);
+            if (!over.hit) break;
+            at = over.at;
+            done = over.count;
+        }
     }
     if (seg == nseg - 1 && tid == 0) {
         const uint64_t total = (uint64_t)exclusive + aggregate;

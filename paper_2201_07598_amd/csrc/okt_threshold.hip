@@ -281,7 +281,7 @@ constexpr int CNT_U = 4;
 // a candidate and is copied to `cand`, in any order (per-wave LDS stash; a stash
 // that fills up is flushed with an atomic of its own, the rest of a workgroup
 // with one atomic at the end).
-template <typename Test>
+template <bool NT, typename Test>
 __device__ __forceinline__ void collect_body(const float* __restrict__ acc, uint32_t n,
                                              uint32_t piece, RadixState* state,
                                              uint32_t* __restrict__ cand, uint64_t cand_cap,
@@ -314,13 +314,13 @@ __device__ __forceinline__ void collect_body(const float* __restrict__ acc, uint
         const float4* src = reinterpret_cast<const float4*>(acc + r) + lane;
         float4 v[CNT_U];
 #pragma unroll
-        for (int u = 0; u < CNT_U; ++u) v[u] = src[u * WAVE];
+        for (int u = 0; u < CNT_U; ++u) v[u] = load_quad<NT>(src + u * WAVE);
 #pragma unroll
         for (int u = 0; u < CNT_U; ++u)
             round(v[u], test(v[u].x), test(v[u].y), test(v[u].z), test(v[u].w));
     }
     for (; r + 256 <= end; r += 256) {                    // whole rounds short of a batch
-        const float4 v = reinterpret_cast<const float4*>(acc + r)[lane];
+        const float4 v = load_quad<NT>(reinterpret_cast<const float4*>(acc + r) + lane);
         round(v, test(v.x), test(v.y), test(v.z), test(v.w));
     }
     for (; r < end; r += 256) {                           // the ragged end of the vector
@@ -353,6 +353,7 @@ __device__ __forceinline__ void collect_body(const float* __restrict__ acc, uint
         if (base + j < cand_cap) cand[base + j] = mine[j];
 }
 
+template <bool NT>
 __global__ __launch_bounds__(CNT_BLOCK) void collect_kernel(
     const float* __restrict__ acc, uint32_t n, uint32_t piece, RadixState* state,
     uint32_t* __restrict__ cand, uint64_t cand_cap) {
@@ -361,10 +362,10 @@ __global__ __launch_bounds__(CNT_BLOCK) void collect_kernel(
     __shared__ unsigned long long s_base;
     const float lo = __uint_as_float(state->cand_lo);       // a key below the Inf/NaN range, or NaN
     if (lo == lo)
-        collect_body(acc, n, piece, state, cand, cand_cap, TestFloat{lo}, s_stash, s_left, &s_base);
+        collect_body<NT>(acc, n, piece, state, cand, cand_cap, TestFloat{lo}, s_stash, s_left, &s_base);
     else
-        collect_body(acc, n, piece, state, cand, cand_cap, TestKey{state->cand_lo}, s_stash, s_left,
-                     &s_base);
+        collect_body<NT>(acc, n, piece, state, cand, cand_cap, TestKey{state->cand_lo}, s_stash, s_left,
+                         &s_base);
 }
 
 __global__ void radix_init_kernel(RadixState* state, uint32_t* hist, uint32_t words) {
@@ -511,8 +512,9 @@ extern "C" int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t
         static_assert(CNT_WAVES == SEL_WAVES, "the collect pass is cut like the select");
         const SelectShape shape = select_shape(n, device_cus());
         timing_before(s);
-        hipLaunchKernelGGL(collect_kernel, dim3(shape.nseg), dim3(CNT_BLOCK), 0, s, d_acc,
-                           (uint32_t)n, shape.piece, state, cand, cand_cap);
+        hipLaunchKernelGGL(stream_past_cache(n) ? collect_kernel<true> : collect_kernel<false>,
+                           dim3(shape.nseg), dim3(CNT_BLOCK), 0, s, d_acc, (uint32_t)n, shape.piece,
+                           state, cand, cand_cap);
         timing_after(s);
     }
 
