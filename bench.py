@@ -681,8 +681,28 @@ def time_reduce_batch(args, torch, np, okt, wl, w, width):
     us = float(np.median(times[2:]))
     U = int(u64_host(np, nnz)[1::2].sum())
     nbytes = 8.0 * B * E1 + 8.0 * U
-    log(f"[bench] {w.name} reduce batch: {us:9.1f} us = {nbytes / us * 1e-3 / HBM_PEAK_GBS * 100:5.1f} % of peak")
-    return {"shape": f"P={P}, {m} entries per contribution, region width {width}", "regions": B,
+    # the same tiles and slices read once, and as many entries written as the union
+    # holds (the first ones of every region: the capacity cuts the rest off), nothing
+    # summed or ranked: what the access pattern alone costs
+    gcap = min(E1, -(-U // B))
+    gtimes = []
+    for rep in range(6):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        okt.okt_stream_gather(d_idx, d_val, d_off, d_lohi, B, P, width, out_idx, out_val, gcap, ws)
+        b.record()
+        torch.cuda.synchronize()
+        gtimes.append(a.elapsed_time(b) * 1e3)
+    gus = float(np.median(gtimes[2:]))
+    gbytes = 8.0 * B * E1 + 8.0 * B * gcap
+    gather = {"what": "okt_stream_gather: same tiles, same slice table, every entry read once and as "
+                      "many written as the union holds, no arithmetic", "us_per_launch": round(gus, 1), "bytes": gbytes,
+              "GBs": round(gbytes / gus * 1e-3, 1), "frac_of_hbm_peak": round(gbytes / gus * 1e-3 / HBM_PEAK_GBS, 4)}
+    log(f"[bench] {w.name} reduce batch: {us:9.1f} us = {nbytes / us * 1e-3 / HBM_PEAK_GBS * 100:5.1f} % of peak; "
+        f"gather ceiling {gus:9.1f} us = {gbytes / gus * 1e-3 / HBM_PEAK_GBS * 100:5.1f} % of peak")
+    return {"gather_ceiling": gather, "frac_of_gather_ceiling": round((nbytes / us) / (gbytes / gus), 4),
+            "shape": f"P={P}, {m} entries per contribution, region width {width}", "regions": B,
             "entries_in": B * E1, "union_out": U, "us_per_launch": round(us, 1),
             "us_min": round(float(np.min(times[2:])), 1),
             "algorithmic_bytes": nbytes, "achieved_GBs": round(nbytes / us * 1e-3, 1),

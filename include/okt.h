@@ -105,6 +105,23 @@ void okt_time_next_kernel(void* start_event, void* stop_event);
 int okt_stream_copy(const float* d_src, float* d_dst, uint64_t n, void* stream);
 int okt_stream_sum(const float* d_src, uint64_t n, float* d_partials_out, void* stream);
 
+/*
+ * Measurement only: the memory traffic of okt_sparse_reduce_batch without its
+ * arithmetic.  Arguments as okt_sparse_reduce_batch (no counts, no dense copy):
+ * the region is cut into the same tiles, the same kernel builds the same table of
+ * slice boundaries, and then one workgroup per tile reads every entry of the
+ * tile's slices once - short sorted runs of (index, value) pairs scattered over
+ * d_idx_cat / d_val_cat - and writes it to d_idx_out / d_val_out[j * capacity + p],
+ * p being the entry's position among region j's input entries (entries beyond
+ * `capacity` are dropped).  Nothing is summed, ranked or scanned: the time of this
+ * call is what the reduce's access pattern alone costs on the GPU at hand.
+ * okt_time_next_kernel brackets the tile kernel, as for the reduce.
+ */
+int okt_stream_gather(const uint32_t* d_idx_cat, const float* d_val_cat,
+                      const uint64_t* d_chunk_off, const uint32_t* d_lo_hi, uint32_t B, uint32_t P,
+                      uint32_t max_width, uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                      void* d_ws, size_t ws_bytes, void* stream);
+
 /* Library version, major * 10000 + minor * 100 + patch. */
 int okt_version(void);
 

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     okt_sparse_reduce_segments,
     okt_status_string,
     okt_stream_copy,
+    okt_stream_gather,
     okt_stream_sum,
     okt_time_next_kernel,
     okt_threshold_select,

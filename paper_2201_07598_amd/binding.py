@@ -25,6 +25,8 @@ SIGNATURES = {
     "okt_version": (c_int, []),
     "okt_stream_copy": (c_int, [c_vp, c_vp, c_u64, c_vp]),
     "okt_stream_sum": (c_int, [c_vp, c_u64, c_vp, c_vp]),
+    "okt_stream_gather": (c_int, [c_vp, c_vp, c_vp, c_vp, c_u32, c_u32, c_u32, c_vp, c_vp, c_u64, c_vp,
+                                  c_sz, c_vp]),
     "okt_workspace_bytes": (c_sz, [c_u64, c_u32]),
     "okt_sparse_reduce_batch_workspace_bytes": (c_sz, [c_u32, c_u32, c_u32]),
     "okt_residual_accumulate": (c_int, [c_vp, c_vp, c_f32, c_u64, c_vp]),
@@ -196,6 +198,22 @@ def okt_stream_sum(src, partials_out, stream=None) -> None:
     _check("okt_stream_sum", load_library().okt_stream_sum(
         _ptr(src, torch.float32, "src"), src.numel(),
         _ptr(partials_out, torch.float32, "partials_out"), _stream(stream)))
+
+
+def okt_stream_gather(idx_cat, val_cat, chunk_off, lo_hi, B: int, P: int, max_width: int, idx_out,
+                      val_out, capacity: int, ws, stream=None) -> None:
+    """Measurement only: the batched reduce's reads and writes without its arithmetic."""
+    torch = _torch()
+    if chunk_off.numel() < B * (P + 1) or lo_hi.numel() < 2 * B:
+        raise ValueError("chunk_off needs B*(P+1), lo_hi 2*B elements")
+    if idx_out.numel() < B * capacity or val_out.numel() < B * capacity:
+        raise ValueError("output buffers need B*capacity elements")
+    _check("okt_stream_gather", load_library().okt_stream_gather(
+        _ptr(idx_cat, _u32(torch), "idx_cat"), _ptr(val_cat, torch.float32, "val_cat"),
+        _ptr(chunk_off, _u64(torch), "chunk_off"), _ptr(lo_hi, _u32(torch), "lo_hi"),
+        int(B), int(P), int(max_width),
+        _ptr(idx_out, _u32(torch), "idx_out"), _ptr(val_out, torch.float32, "val_out"),
+        int(capacity), _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(stream)))
 
 
 def okt_topk_threshold_exact(acc, k: int, threshold_out, count_ge_out, ws, stream=None) -> None:

@@ -82,6 +82,85 @@ __global__ __launch_bounds__(CEIL_BLOCK) void stream_sum_kernel(
     }
 }
 
+// The memory traffic of the batched sparse reduce without its arithmetic.  Same
+// launch shape (one 512-thread workgroup per tile, grid = tiles x regions) and the
+// same slice table, so the same pieces of the same arrays are read by the same
+// number of waves, in the same way: the slice starts and lengths of up to 256
+// contributions are staged in LDS, slice q goes to wave q mod 8, a wave reads a
+// slice 64 consecutive entries at a time and keeps ten such blocks, across its
+// slices, in flight, index and value together; every entry is then written to the
+// output at the place it has in its region's input.  No accumulators, no bitmap,
+// no ticket, no scan: what is left is what the gather of these short sorted runs,
+// and the write of as many entries, costs on the chip.
+__global__ __launch_bounds__(512) void gather_ceiling_kernel(
+    const uint32_t* __restrict__ idx_cat, const float* __restrict__ val_cat,
+    const uint64_t* __restrict__ seg_begin, uint32_t seg_stride, const uint32_t* __restrict__ lo_hi,
+    uint32_t P, uint32_t max_width, uint32_t slots, uint32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, uint64_t capacity, const char* __restrict__ ws,
+    uint32_t ws_region_bytes, uint32_t table_offset) {
+    constexpr int CHUNK = 256, UNITS = 10, WAVES = 8;
+    __shared__ uint64_t s_start[CHUNK];
+    __shared__ uint32_t s_len[CHUNK];
+    const uint32_t region = blockIdx.y, tile = blockIdx.x;
+    const uint32_t lo = lo_hi[2 * region], hi = lo_hi[2 * region + 1];
+    if (hi < lo || hi - lo > max_width) return;
+    const uint32_t ntiles = (uint32_t)(((uint64_t)(hi - lo) + slots - 1) / slots);
+    if (tile >= ntiles) return;
+    const uint32_t* table = (const uint32_t*)(ws + (size_t)region * ws_region_bytes + table_offset);
+    const uint32_t* row0 = table + (size_t)tile * P;
+    const uint32_t* row1 = row0 + P;
+    const uint64_t* off = seg_begin + (size_t)region * seg_stride;
+    const uint64_t first = off[0];                         // the region's entries lie back to back
+    idx_out += (size_t)region * capacity;
+    val_out += (size_t)region * capacity;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);
+    for (uint32_t p0 = 0; p0 < P; p0 += CHUNK) {
+        const uint32_t np = P - p0 < (uint32_t)CHUNK ? P - p0 : (uint32_t)CHUNK;
+        __syncthreads();
+        for (uint32_t q = tid; q < np; q += blockDim.x) {
+            const uint32_t b = row0[p0 + q], e = row1[p0 + q];
+            s_start[q] = off[p0 + q] + b;
+            s_len[q] = e > b ? e - b : 0u;
+        }
+        __syncthreads();
+        uint32_t q = wave, o = 0;                          // next block: slice q, from entry o
+        while (q < np) {
+            uint64_t pos[UNITS];
+            uint32_t left[UNITS];
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                while (q < np && s_len[q] == 0) q += WAVES;
+                const bool have = q < np;
+                const uint32_t len = have ? (uint32_t)__builtin_amdgcn_readfirstlane(s_len[q]) : 0u;
+                left[u] = have ? len - o : 0u;
+                pos[u] = have ? s_start[q] + o + lane : 0;
+                if (have) {
+                    o += 64u;
+                    if (o >= len) { q += WAVES; o = 0; }
+                }
+            }
+            uint32_t index[UNITS];
+            float value[UNITS];
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                if (lane < left[u]) {
+                    index[u] = idx_cat[pos[u]];
+                    value[u] = val_cat[pos[u]];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                const uint64_t at = pos[u] - first;
+                if (lane < left[u] && at < capacity) {
+                    idx_out[at] = index[u];
+                    val_out[at] = value[u];
+                }
+            }
+        }
+    }
+}
+
 }  // namespace okt
 
 extern "C" int okt_stream_copy(const float* d_src, float* d_dst, uint64_t n, void* stream) {

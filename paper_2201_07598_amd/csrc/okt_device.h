@@ -186,6 +186,16 @@ int launch_failed(hipError_t e);
 void timing_before(hipStream_t stream);
 void timing_after(hipStream_t stream);
 
+// Measurement only (okt_ceiling.hip): one workgroup per tile of the sparse
+// reduce, reading the tile's slices through the reduce's own slice table and
+// writing every entry once; no sums, no ranks, no scan.
+__global__ void gather_ceiling_kernel(const uint32_t* idx_cat, const float* val_cat,
+                                      const uint64_t* seg_begin, uint32_t seg_stride,
+                                      const uint32_t* lo_hi, uint32_t P, uint32_t max_width,
+                                      uint32_t slots, uint32_t* idx_out, float* val_out,
+                                      uint64_t capacity, const char* ws, uint32_t ws_region_bytes,
+                                      uint32_t table_offset);
+
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 }  // namespace okt

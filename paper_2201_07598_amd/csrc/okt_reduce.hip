@@ -438,14 +438,17 @@ __global__ __launch_bounds__(RED_BLOCK) void reduce_tile_kernel(
     }
 }
 
-static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
-                         const uint64_t* d_seg_begin, const uint64_t* d_seg_end,
-                         uint32_t seg_stride, const uint32_t* d_lo_hi, uint32_t lo,
-                         uint32_t hi, uint32_t B, uint32_t P, uint32_t max_width,
-                         uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
-                         uint64_t* d_nnz_out, float* d_dense, void* d_ws, size_t ws_bytes,
-                         hipStream_t s) {
-    if (!d_idx_cat || !d_val_cat || !d_seg_begin || !d_seg_end || !d_nnz_out)
+// traffic_only: the measurement entry point okt_stream_gather - the same tiles and
+// the same slice table, but the tile kernel is replaced by one that only moves
+// the entries (d_nnz_out and d_dense are not used then).
+int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
+                  const uint64_t* d_seg_begin, const uint64_t* d_seg_end,
+                  uint32_t seg_stride, const uint32_t* d_lo_hi, uint32_t lo,
+                  uint32_t hi, uint32_t B, uint32_t P, uint32_t max_width,
+                  uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
+                  uint64_t* d_nnz_out, float* d_dense, void* d_ws, size_t ws_bytes,
+                  hipStream_t s, bool traffic_only) {
+    if (!d_idx_cat || !d_val_cat || !d_seg_begin || !d_seg_end || (!d_nnz_out && !traffic_only))
         return OKT_ERR_INVALID_ARG;
     if (P == 0 || P > 65535 || B == 0 || B > 65535) return OKT_ERR_INVALID_ARG;
     if (capacity > 0 && (!d_idx_out || !d_val_out)) return OKT_ERR_INVALID_ARG;
@@ -486,6 +489,15 @@ static int reduce_launch(const uint32_t* d_idx_cat, const float* d_val_cat,
     // in spans of two or four blocks of 64
     const uint64_t per_slice = capacity / tiles / P;
     const uint32_t span_blocks = per_slice >= 128 ? 4u : per_slice >= 64 ? 2u : 1u;
+    if (traffic_only) {
+        timing_before(s);
+        hipLaunchKernelGGL(gather_ceiling_kernel, dim3((unsigned)tiles, B), dim3(RED_BLOCK), 0, s,
+                           d_idx_cat, d_val_cat, d_seg_begin, seg_stride, d_lo_hi, P, max_width, slots,
+                           d_idx_out, d_val_out, capacity, (const char*)d_ws, (uint32_t)region_bytes,
+                           table_offset);
+        timing_after(s);
+        return launch_status();
+    }
     timing_before(s);
     auto* tile_kernel = shape.kind == RED_SPARSE  ? reduce_tile_kernel<RED_C_SPARSE, RED_S_SPARSE>
                         : shape.kind == RED_DENSE ? reduce_tile_kernel<RED_C_DENSE, RED_C_DENSE>
@@ -512,7 +524,7 @@ extern "C" int okt_sparse_reduce(const uint32_t* d_idx_cat, const float* d_val_c
     return okt::reduce_launch(d_idx_cat, d_val_cat, d_chunk_off, d_chunk_off + 1, P + 1, nullptr,
                               lo, hi, 1, P, hi - lo,
                               d_idx_out, d_val_out, capacity, d_nnz_out, d_dense_out_or_null,
-                              d_ws, ws_bytes, (hipStream_t)stream);
+                              d_ws, ws_bytes, (hipStream_t)stream, false);
 }
 
 extern "C" int okt_sparse_reduce_batch(const uint32_t* d_idx_cat, const float* d_val_cat,
@@ -525,7 +537,18 @@ extern "C" int okt_sparse_reduce_batch(const uint32_t* d_idx_cat, const float* d
     return okt::reduce_launch(d_idx_cat, d_val_cat, d_chunk_off, d_chunk_off + 1, P + 1, d_lo_hi,
                               0, 0, B, P, max_width,
                               d_idx_out, d_val_out, capacity, d_nnz_out, d_dense_out_or_null,
-                              d_ws, ws_bytes, (hipStream_t)stream);
+                              d_ws, ws_bytes, (hipStream_t)stream, false);
+}
+
+extern "C" int okt_stream_gather(const uint32_t* d_idx_cat, const float* d_val_cat,
+                                 const uint64_t* d_chunk_off, const uint32_t* d_lo_hi, uint32_t B,
+                                 uint32_t P, uint32_t max_width, uint32_t* d_idx_out,
+                                 float* d_val_out, uint64_t capacity, void* d_ws, size_t ws_bytes,
+                                 void* stream) {
+    if (!d_lo_hi || !d_chunk_off || !d_idx_out || !d_val_out) return OKT_ERR_INVALID_ARG;
+    return okt::reduce_launch(d_idx_cat, d_val_cat, d_chunk_off, d_chunk_off + 1, P + 1, d_lo_hi,
+                              0, 0, B, P, max_width, d_idx_out, d_val_out, capacity, nullptr, nullptr,
+                              d_ws, ws_bytes, (hipStream_t)stream, true);
 }
 
 extern "C" int okt_sparse_reduce_segments(const uint32_t* d_idx_cat, const float* d_val_cat,
@@ -537,5 +560,5 @@ extern "C" int okt_sparse_reduce_segments(const uint32_t* d_idx_cat, const float
     if (lo > hi) return OKT_ERR_INVALID_ARG;
     return okt::reduce_launch(d_idx_cat, d_val_cat, d_seg_begin, d_seg_end, P, nullptr, lo, hi, 1, P,
                               hi - lo, d_idx_out, d_val_out, capacity, d_nnz_out,
-                              d_dense_out_or_null, d_ws, ws_bytes, (hipStream_t)stream);
+                              d_dense_out_or_null, d_ws, ws_bytes, (hipStream_t)stream, false);
 }

@@ -66,6 +66,38 @@ def test_streaming_ceiling_kernels(n):
     assert abs(total - float(x.astype(np.float64).sum())) <= 1e-6 * float(np.abs(x).sum()) + 1e-30
 
 
+def test_gather_ceiling_kernel_moves_every_entry_once():
+    """The measurement kernel behind the reduce's traffic ceiling: same tiles and
+    slice table as the batched reduce; every input entry of a region must come out
+    at its own position, bit for bit, and nothing else may be written."""
+    w = wl.WORKLOADS["cfg3"]
+    B, P, width, m = 7, 12, 50_000, 1_900
+    parts, offs, lohi = [], [], []
+    base = 0
+    for j in range(B):
+        lo = 3_000_000 * j + 11
+        hi = lo + width - 777 * j
+        ci, cv, co = wl.contributions(w, lo, hi, m=m, P=P, stream=40 + j)
+        parts.append((ci, cv))
+        offs.append(co + np.uint64(base))
+        lohi += [lo, hi]
+        base += ci.size
+    idx_cat = np.concatenate([p[0] for p in parts])
+    val_cat = np.concatenate([p[1] for p in parts])
+    cap = max(p[0].size for p in parts) + 5
+    out_idx = torch.full((B * cap,), -1, dtype=torch.int32, device=DEV)
+    out_val = torch.full((B * cap,), 7.0, dtype=torch.float32, device=DEV)
+    ws = workspace(okt.okt_sparse_reduce_batch_workspace_bytes(B, P, width))
+    okt.okt_stream_gather(to_dev(idx_cat), to_dev(val_cat), to_dev(np.concatenate(offs)),
+                          to_dev(np.array(lohi, dtype=np.uint32)), B, P, width, out_idx, out_val, cap, ws)
+    torch.cuda.synchronize()
+    gi, gv = u32(out_idx).reshape(B, cap), out_val.cpu().numpy().reshape(B, cap)
+    for j in range(B):
+        e = parts[j][0].size
+        assert np.array_equal(gi[j, :e], parts[j][0]) and bits_equal(gv[j, :e], parts[j][1]), j
+        assert np.all(gi[j, e:] == 0xFFFFFFFF) and np.all(gv[j, e:] == 7.0), j
+
+
 def test_accumulate_not_fused_and_subnormals():
     lr = 1.0 + 2.0 ** -12
     g = np.array([1.0 + 2.0 ** -12, 1e-40, -1e-45, 3e-39] * 8, dtype=np.float32)
