@@ -446,9 +446,6 @@ __global__ __launch_bounds__(BLOCK) void candidate_select_kernel(
     __shared__ uint32_t s_count[WAVES];
     __shared__ uint32_t s_seg;
     __shared__ uint32_t s_before[2];
-    if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
-    __syncthreads();
-    const uint32_t seg = s_seg;
     const bool use_cand = state->use_cand != 0;
     float* walked = res;
     uint32_t len = n;
@@ -461,7 +458,21 @@ __global__ __launch_bounds__(BLOCK) void candidate_select_kernel(
         uint32_t share = ((len + waves - 1) / waves + 255u) / 256u * 256u;   // whole rounds
         if (share == 0) share = 256u;
         if (share < piece) piece = share;                   // never longer than the launch's piece
+        // The launch is sized for a walk over the whole residual; the candidates
+        // fill only the first few segments.  The workgroups beyond them leave before
+        // they take a ticket (tickets on one counter are served one after the other,
+        // some 30 ns each: over a thousand idle workgroups queuing for theirs took
+        // longer than the selection itself), so the tickets 0 .. used - 1 go to the
+        // `used` workgroups that stay, all of them running.
+        const uint32_t per_seg = piece * (uint32_t)WAVES;
+        uint32_t used = (len + per_seg - 1) / per_seg;
+        if (used == 0) used = 1;
+        if (used < nseg) nseg = used;
+        if (blockIdx.x >= nseg) return;
     }
+    if (threadIdx.x == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    const uint32_t seg = s_seg;
     const float th = *d_threshold;
     if (th == th) {
         select_body<BLOCK, U, STASH, false>(walked, len, TestFloat{__builtin_fabsf(th)}, source, idx_out,
