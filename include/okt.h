@@ -30,7 +30,8 @@
  *   - Host threads may call the library at the same time as long as the calls
  *     share no workspace and no output buffer; the library keeps no state
  *     between calls.  okt_time_next_kernel and okt_last_hip_error act per
- *     thread, okt_debug_spin_limit on the whole process.
+ *     thread, okt_debug_spin_limit and okt_debug_slot_min_n on the whole
+ *     process.
  *   - The kernels that place their output through a scan across workgroups
  *     (the select family, the reduce family, the index intersection) wait for
  *     one another through device memory.  Every such wait ends by construction
@@ -72,6 +73,15 @@ const char* okt_last_hip_error(void);
  * reports UINT64_MAX counts as described above; it never hangs or faults.
  */
 void okt_debug_spin_limit(uint32_t polls);
+
+/*
+ * Test hook: the shortest vector for which the select calls take their
+ * three-pass form (per-tile slots in the workspace; see okt_threshold_select),
+ * for every call made after this one, process-wide (0 = the built-in length,
+ * 2^20 elements).  Both forms give the same output; with a length of 1 small
+ * test vectors exercise the three-pass form.
+ */
+void okt_debug_slot_min_n(uint64_t n);
 
 /*
  * Measurement hook.  The next call this thread makes records `start_event` right

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     okt_accumulate_topk_select,
     okt_balance_plan,
     okt_coo_threshold_select,
+    okt_debug_slot_min_n,
     okt_debug_spin_limit,
     okt_index_intersect_restore,
     okt_index_intersect_zero,

@@ -22,6 +22,7 @@ SIGNATURES = {
     "okt_last_hip_error": (ctypes.c_char_p, []),
     "okt_time_next_kernel": (None, [c_vp, c_vp]),
     "okt_debug_spin_limit": (None, [c_u32]),
+    "okt_debug_slot_min_n": (None, [c_u64]),
     "okt_version": (c_int, []),
     "okt_stream_copy": (c_int, [c_vp, c_vp, c_u64, c_vp]),
     "okt_stream_sum": (c_int, [c_vp, c_u64, c_vp, c_vp]),
@@ -107,6 +108,11 @@ def okt_time_next_kernel(start_event, stop_event) -> None:
 def okt_debug_spin_limit(polls: int) -> None:
     """Test hook: polls a wait between workgroups may take (0 = built-in limit)."""
     load_library().okt_debug_spin_limit(int(polls))
+
+
+def okt_debug_slot_min_n(n: int) -> None:
+    """Test hook: shortest vector that takes the three-pass select (0 = built-in length)."""
+    load_library().okt_debug_slot_min_n(int(n))
 
 
 def okt_version() -> int:

@@ -12,7 +12,9 @@
 // look-back), so acc is read exactly once.
 #include "okt_select_kernel.h"
 #include "okt_sizes.h"
+#include "okt_slots.h"
 
+#include <atomic>
 #include <mutex>
 
 // Scan state of okt_threshold_select_noalloc: device memory that belongs to the
@@ -47,6 +49,44 @@ static int dense_select_args(const float* d_acc, uint64_t n, const float* d_thre
     return OKT_OK;
 }
 
+// Shortest vector that takes the slot path (okt_debug_slot_min_n; 0 = SLOT_MIN_N).
+static std::atomic<uint64_t> g_slot_min_n{0};
+uint64_t slot_min_n() {
+    const uint64_t set = g_slot_min_n.load(std::memory_order_relaxed);
+    return set ? set : SLOT_MIN_N;
+}
+static bool slots_apply(uint64_t n, size_t ws_bytes) {
+    return n >= slot_min_n() && ws_bytes >= slot_ws_bytes(n);
+}
+
+int launch_slot_finish(float* d_acc, uint64_t n, const float* d_threshold, const SlotPlan& plan,
+                       char* ws, int after, bool dense_zero, uint32_t* d_idx_out, float* d_val_out,
+                       uint64_t capacity, uint64_t* d_nnz_out, hipStream_t s) {
+    ScanHeader* hdr = (ScanHeader*)ws;
+    uint64_t* seg_desc = (uint64_t*)(ws + SCAN_HEADER_BYTES);
+    uint64_t* group_desc = seg_desc + plan.nseg;
+    const uint16_t* counts = (const uint16_t*)(ws + plan.counts_at);
+    uint32_t* place = (uint32_t*)(ws + plan.place_at);
+    const SlotEntry* slots = (const SlotEntry*)(ws + plan.slots_at);
+    uint32_t* dense_list = (uint32_t*)(ws + plan.dense_at);
+    hipLaunchKernelGGL(slot_scan_kernel<SLOT_SCAN_BLOCK>, dim3(plan.nseg), dim3(SLOT_SCAN_BLOCK), 0, s, counts, place,
+                       dense_list, plan.ntiles, plan.tpt, capacity, d_nnz_out, hdr, seg_desc,
+                       group_desc, plan.nseg);
+    // a lane per tile, and at least a full load of waves on every compute unit for the
+    // dense tiles, which are shared out over all the waves of the launch
+    constexpr uint32_t per_wg = (SLOT_EMIT_BLOCK / WAVE) * SLOT_EMIT_TILES;
+    uint32_t grid = (plan.ntiles + per_wg - 1) / per_wg;
+    if (grid < 8 * device_cus()) grid = 8 * device_cus();
+    auto* emit = after == SLOT_ZERO      ? slot_emit_kernel<SLOT_ZERO, true>
+                 : after == SLOT_RESTORE ? slot_emit_kernel<SLOT_RESTORE, true>
+                 : dense_zero            ? slot_emit_kernel<SLOT_KEEP, true>
+                                         : slot_emit_kernel<SLOT_KEEP, false>;
+    hipLaunchKernelGGL(emit, dim3(grid), dim3(SLOT_EMIT_BLOCK), 0, s, d_acc, (uint32_t)n, d_threshold,
+                       counts, place, slots, dense_list, hdr, plan.ntiles, d_idx_out, d_val_out,
+                       capacity);
+    return launch_status();
+}
+
 // The dense select, with (Source = DenseSource) or without (DenseCopySource) the
 // zeroing of the emitted entries.
 template <typename Source>
@@ -62,6 +102,22 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
     }
     const SelectShape shape = select_shape(n, device_cus());
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(n)) return OKT_ERR_WORKSPACE;
+    if (slots_apply(n, ws_bytes)) {
+        const SlotPlan plan = slot_plan(n, device_cus());
+        char* ws = (char*)d_ws;
+        if (launch_clear_scan_state(d_ws, scan_ws_bytes(plan.nseg) / 8, s) != hipSuccess)
+            return OKT_ERR_HIP;
+        timing_before(s);
+        constexpr bool zero = std::is_same<Source, DenseSource>::value;
+        auto* fill = stream_past_cache(n) ? slot_fill_kernel<true> : slot_fill_kernel<false>;
+        constexpr uint32_t per_wg = SLOT_FILL_BLOCK / WAVE;
+        hipLaunchKernelGGL(fill, dim3((plan.ntiles + per_wg - 1) / per_wg), dim3(SLOT_FILL_BLOCK), 0,
+                           s, d_acc, (uint32_t)n, d_threshold, (uint16_t*)(ws + plan.counts_at),
+                           (SlotEntry*)(ws + plan.slots_at), plan.ntiles);
+        timing_after(s);
+        return launch_slot_finish(d_acc, n, d_threshold, plan, ws, zero ? SLOT_ZERO : SLOT_KEEP,
+                                  zero, d_idx_out, d_val_out, capacity, d_nnz_out, s);
+    }
     ScanHeader* hdr = (ScanHeader*)d_ws;
     uint64_t* seg_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
     uint64_t* group_desc = seg_desc + shape.nseg;
@@ -78,6 +134,10 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
 }
 
 }  // namespace okt
+
+extern "C" void okt_debug_slot_min_n(uint64_t n) {
+    okt::g_slot_min_n.store(n, std::memory_order_relaxed);
+}
 
 extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshold,
                                     uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
@@ -165,6 +225,23 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
         return OKT_ERR_INVALID_ARG;
     const SelectShape shape = select_shape(n, device_cus());
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(n)) return OKT_ERR_WORKSPACE;
+    if (slots_apply(n, ws_bytes)) {
+        const SlotPlan plan = slot_plan(n, device_cus());
+        char* ws = (char*)d_ws;
+        if (launch_clear_scan_state(d_ws, scan_ws_bytes(plan.nseg) / 8, s) != hipSuccess)
+            return OKT_ERR_HIP;
+        timing_before(s);
+        auto* fill = stream_past_cache(n) ? slot_fill_accumulate_kernel<true, true>
+                                          : slot_fill_accumulate_kernel<true, false>;
+        constexpr uint32_t per_wg = SLOT_FILL_BLOCK / WAVE;
+        hipLaunchKernelGGL(fill, dim3((plan.ntiles + per_wg - 1) / per_wg), dim3(SLOT_FILL_BLOCK), 0,
+                           s, d_grad, d_residual_inout, lr, (uint32_t)n, d_threshold,
+                           (uint16_t*)(ws + plan.counts_at), (SlotEntry*)(ws + plan.slots_at),
+                           plan.ntiles);
+        timing_after(s);
+        return launch_slot_finish(d_residual_inout, n, d_threshold, plan, ws, SLOT_RESTORE, true,
+                                  d_idx_out, d_val_out, capacity, d_nnz_out, s);
+    }
     ScanHeader* hdr = (ScanHeader*)d_ws;
     uint64_t* seg_desc = (uint64_t*)((char*)d_ws + SCAN_HEADER_BYTES);
     uint64_t* group_desc = seg_desc + shape.nseg;

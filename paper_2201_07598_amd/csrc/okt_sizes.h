@@ -57,6 +57,53 @@ inline size_t select_ws_bytes(uint64_t n) {
 // what one iteration writes the next one still finds there.
 inline bool stream_past_cache(uint64_t n) { return n >= (96u << 20); }      // 384 MB of fp32 and up
 
+// ---- the same through per-tile slots ----
+// With a workspace that has room for them, the streaming pass of the selects
+// writes what a tile of SLOT_TILE elements (one wave) selects into the tile's own
+// slot of SLOT_C entries and counts it; a scan over the counts and a copy out of
+// the slots follow as a short second pass, and the tiles that selected more than
+// a slot holds (a local density above SLOT_C / SLOT_TILE = 3.1 %) are walked
+// again by a third.  Workspace: a scan state, then per tile a 2-byte count, a
+// 4-byte place, 4 bytes of the list of dense tiles and the slot, a good quarter of
+// the vector's bytes in all.
+constexpr uint32_t SLOT_TILE = 1024;
+constexpr uint32_t SLOT_C = 32;
+constexpr uint32_t SLOT_GROUP = 4;                   // tiles whose slots are interleaved
+constexpr uint32_t SLOT_SCAN_TILES = 1024;           // tiles per workgroup of the second pass and turn
+struct SlotPlan {
+    uint32_t ntiles;
+    uint32_t tpt;                // tiles per thread of the second pass
+    uint32_t nseg;               // workgroups of the second pass
+    size_t counts_at, place_at, dense_at, slots_at, bytes;   // offsets into the workspace; its size
+};
+inline size_t round_up_256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline SlotPlan slot_plan(uint64_t n, uint32_t cus) {
+    SlotPlan p;
+    p.ntiles = (uint32_t)((n + SLOT_TILE - 1) / SLOT_TILE);
+    // about half as many workgroups as compute units: the pass is short, and every
+    // workgroup takes a ticket from one counter
+    const uint64_t want = (uint64_t)SLOT_SCAN_TILES * (cus > 1 ? cus / 2 : 1);
+    p.tpt = (uint32_t)((p.ntiles + want - 1) / want);
+    if (p.tpt == 0) p.tpt = 1;
+    if (p.tpt > 63) p.tpt = 63;              // a workgroup's tiles are counted in 16 bits
+    const uint64_t per_seg = (uint64_t)SLOT_SCAN_TILES * p.tpt;
+    p.nseg = (uint32_t)((p.ntiles + per_seg - 1) / per_seg);
+    if (p.nseg == 0) p.nseg = 1;
+    // the scan state is sized for the most workgroups any device gives (tpt = 1)
+    const uint64_t segs_max = (uint64_t)p.ntiles / SLOT_SCAN_TILES + 1;
+    const size_t scan = 64 + 8 * (size_t)(segs_max + (segs_max + 63) / 64);
+    p.counts_at = round_up_256(scan);
+    p.place_at = p.counts_at + round_up_256(2 * (size_t)p.ntiles);
+    p.dense_at = p.place_at + round_up_256(4 * (size_t)p.ntiles);
+    p.slots_at = p.dense_at + round_up_256(4 * (size_t)p.ntiles);
+    p.bytes = p.slots_at + 8 * (size_t)SLOT_C * ((p.ntiles + SLOT_GROUP - 1) / SLOT_GROUP * SLOT_GROUP);
+    return p;
+}
+inline size_t slot_ws_bytes(uint64_t n) { return slot_plan(n, 256).bytes; }
+// Shorter vectors take the one-kernel select: three launches cost more than they
+// save there.
+constexpr uint64_t SLOT_MIN_N = 1u << 26;
+
 // ---- index intersection and residual restore ----
 constexpr int RST_BLOCK = 256;
 constexpr int RST_ROWS = 4;                              // entries per thread
@@ -83,12 +130,14 @@ inline size_t threshold_ws_bytes(uint64_t n) {
     return threshold_ws_min_bytes() + 4 * (size_t)(n / 8 + 1024);
 }
 // A refresh iteration in one pass: the threshold's state and histograms, two scan
-// states, and candidates with their indices (8 bytes each, a sixteenth of the
-// vector and some).  A shorter vector takes the three steps one after the other.
+// states, candidates with their indices (8 bytes each, a sixteenth of the vector
+// and some), and the slots through which a long vector's candidates are
+// collected.  A shorter vector takes the three steps one after the other.
 inline size_t refresh_scan_bytes(uint64_t n) { return (select_ws_bytes(n) + 255) & ~(size_t)255; }
 inline size_t refresh_ws_bytes(uint64_t n) {
     if (n < RS_SAMPLE_MIN_N) return 0;
-    return threshold_ws_min_bytes() + 2 * refresh_scan_bytes(n) + 8 * (size_t)(n / 8 + 1024);
+    return threshold_ws_min_bytes() + 2 * refresh_scan_bytes(n) + 8 * (size_t)(n / 8 + 1024) +
+           round_up_256(slot_ws_bytes(n));
 }
 
 // ---- sparse reduce ----

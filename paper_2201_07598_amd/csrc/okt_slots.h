@@ -1,0 +1,442 @@
+// Threshold select and compaction through per-tile slots: the streaming pass has
+// no scan in it (Sec. 3.1.3 threshold selection; Sec. 3.1.2 packaging;
+// Algorithm 2, line 6 residual update).
+//
+// The vector is cut into tiles of SLOT_TILE elements, one per wave.  The first
+// pass is a plain streaming kernel of many small workgroups, with no ticket, no
+// wait, no LDS: a wave loads its tile with four 16-byte loads per lane, ranks
+// the selected elements with ballots, and writes them into the tile's slot
+// (SLOT_C entries of workspace) and their number into counts[tile].  The second
+// pass reads the counts only: a chained scan over them gives every tile its
+// place in the output.  The third pass, again of many small workgroups, copies
+// the entries of the slots there in index order; a tile that selected more than
+// its slot holds ("dense") is walked once more, now that its place is known, and
+// written directly.  Only the dense tiles are read twice.
+#ifndef OKT_SLOTS_H
+#define OKT_SLOTS_H
+
+#include "okt_select_kernel.h"
+#include "okt_sizes.h"
+
+namespace okt {
+
+struct SlotEntry { uint32_t idx; float val; };
+static_assert(sizeof(SlotEntry) == 8, "an entry is one 8-byte store");
+
+constexpr uint32_t SLOT_FEW = 4;                          // entries a lane of the third pass copies by itself
+constexpr int SLOT_FILL_BLOCK = 256;                      // 4 waves = 4 tiles per workgroup
+static_assert(SLOT_FILL_BLOCK / WAVE == (int)SLOT_GROUP, "a workgroup of the first pass fills one group of slots");
+
+// Where entry j of a tile's slot lives.  The slots of the SLOT_GROUP tiles that one
+// workgroup of the first pass fills are interleaved entry by entry, so that the
+// first four entries of all of them - all there is, as a rule - share one
+// 128-byte line, which the workgroup always writes in full (with zeros where a
+// tile has fewer entries): the L2 hands a whole line to memory, where a part of a
+// line costs a read-modify-write, and a workgroup dirties one line, not four.
+__device__ __forceinline__ uint64_t slot_at(uint64_t tile, uint32_t j) {
+    return (tile / SLOT_GROUP) * (SLOT_GROUP * SLOT_C) + (uint64_t)j * SLOT_GROUP + tile % SLOT_GROUP;
+}
+// The first pass's stores for a tile that selected `count` entries, given the
+// sink's stores of the entries themselves: zeros up to SLOT_FEW entries.
+__device__ __forceinline__ void slot_pad(SlotEntry* __restrict__ slots, uint64_t tile, uint32_t count) {
+    const uint32_t j = count + (uint32_t)lane_id();
+    if (j < SLOT_FEW) slots[slot_at(tile, j)] = SlotEntry{0u, 0.0f};
+}
+constexpr int SLOT_SCAN_BLOCK = 1024;
+static_assert(SLOT_SCAN_BLOCK == (int)SLOT_SCAN_TILES, "one thread per tile and turn");
+constexpr int SLOT_EMIT_BLOCK = 256;
+constexpr int SLOT_EMIT_TILES = WAVE;                     // tiles per wave of the third pass: one per lane
+constexpr int SLOT_FULLER_WORD = 0, SLOT_DENSE_WORD = 1;  // words of the scan header's padding: tiles listed
+
+// The four rounds of a tile, lane l holding base + 256 u + 4 l .. + 3 of round u.
+// A tile that runs past the end of the vector is loaded element by element, with
+// zeros past the end.
+template <bool NT>
+__device__ __forceinline__ void tile_load(const float* __restrict__ src, uint64_t base, uint32_t n,
+                                          bool whole, float4 (&v)[4]) {
+    const int lane = lane_id();
+    if (whole) {
+        const float4* p = reinterpret_cast<const float4*>(src + base) + lane;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = load_quad<NT>(p + u * WAVE);
+    } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t i = base + 256u * u + 4u * (uint32_t)lane;
+            v[u].x = i < n ? src[i] : 0.0f;
+            v[u].y = i + 1 < n ? src[i + 1] : 0.0f;
+            v[u].z = i + 2 < n ? src[i + 2] : 0.0f;
+            v[u].w = i + 3 < n ? src[i + 3] : 0.0f;
+        }
+    }
+}
+
+// Which of the lane's sixteen elements are selected: bit 4u + c for component c
+// of round u.  Elements past the end of the vector never are.
+template <typename Test>
+__device__ __forceinline__ uint32_t tile_test(const float4 (&v)[4], uint64_t base, uint32_t n,
+                                              bool whole, Test test) {
+    const int lane = lane_id();
+    uint32_t bits = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const uint64_t i = base + 256u * u + 4u * (uint32_t)lane;
+        if (test(v[u].x) && (whole || i < n)) bits |= 1u << (4 * u);
+        if (test(v[u].y) && (whole || i + 1 < n)) bits |= 2u << (4 * u);
+        if (test(v[u].z) && (whole || i + 2 < n)) bits |= 4u << (4 * u);
+        if (test(v[u].w) && (whole || i + 3 < n)) bits |= 8u << (4 * u);
+    }
+    return bits;
+}
+
+// Feeds the selected elements of a tile to sink(rank, index, value) in index
+// order, rank counting from 0; returns their number (wave-uniform).
+template <typename Sink>
+__device__ __forceinline__ uint32_t tile_rank(const float4 (&v)[4], uint32_t bits, uint64_t base,
+                                              Sink&& sink) {
+    uint32_t count = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const uint32_t b = bits >> (4 * u);
+        count = select_round((uint32_t)base + 256u * u, v[u], (b & 1u) != 0, (b & 2u) != 0,
+                             (b & 4u) != 0, (b & 8u) != 0, count, sink);
+    }
+    return count;
+}
+
+// Number of selected elements of the wave's tile (wave-uniform).
+__device__ __forceinline__ uint32_t tile_count(uint32_t bits) {
+    uint32_t count = 0;
+#pragma unroll
+    for (int b = 0; b < 16; ++b) count += (uint32_t)__popcll(__ballot((bits >> b) & 1u));
+    return count;
+}
+
+// ---- first pass over a vector that is only read ----
+template <bool NT, typename Test>
+__device__ __forceinline__ void slot_fill_tile(const float* __restrict__ acc, uint32_t n, Test test,
+                                               uint16_t* __restrict__ counts,
+                                               SlotEntry* __restrict__ slots, uint32_t tile) {
+    const uint64_t base = (uint64_t)tile * SLOT_TILE;
+    const bool whole = base + SLOT_TILE <= n;
+    float4 v[4];
+    tile_load<NT>(acc, base, n, whole, v);
+    const uint32_t bits = tile_test(v, base, n, whole, test);
+    const uint32_t count = tile_count(bits);
+    if (lane_id() == 0) counts[tile] = (uint16_t)count;
+    if (count > SLOT_C) return;
+    if (count != 0)
+        tile_rank(v, bits, base, [&](uint32_t rank, uint32_t i, float x) {
+            slots[slot_at(tile, rank)] = SlotEntry{i, x};
+        });
+    slot_pad(slots, tile, count);
+}
+
+template <bool NT>
+__global__ __launch_bounds__(SLOT_FILL_BLOCK) void slot_fill_kernel(
+    const float* __restrict__ acc, uint32_t n, const float* __restrict__ d_threshold,
+    uint16_t* __restrict__ counts, SlotEntry* __restrict__ slots, uint32_t ntiles) {
+    const uint32_t tile = blockIdx.x * (SLOT_FILL_BLOCK / WAVE) + (threadIdx.x >> 6);
+    if (tile >= ntiles) return;
+    const float th = *d_threshold;
+    if (th == th) slot_fill_tile<NT>(acc, n, TestFloat{__builtin_fabsf(th)}, counts, slots, tile);
+    else slot_fill_tile<NT>(acc, n, TestKey{magnitude_key(th)}, counts, slots, tile);
+}
+
+// ---- first pass that forms the accumulator on the way ----
+// acc = eps + lr * G (product and sum rounded separately) is tested and written
+// back as the new residual.  With ZERO set the selected elements of a tile whose
+// slot holds them all are written as zeros, so that nothing has to come back to
+// them; a dense tile is written as it is and zeroed by the third pass.
+template <bool ZERO, bool NT, typename Test>
+__device__ __forceinline__ void slot_fill_accumulate_tile(
+    const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, Test test,
+    uint16_t* __restrict__ counts, SlotEntry* __restrict__ slots, uint32_t tile) {
+    const int lane = lane_id();
+    const uint64_t base = (uint64_t)tile * SLOT_TILE;
+    const bool whole = base + SLOT_TILE <= n;
+    float4 g[4], a[4];
+    tile_load<NT>(grad, base, n, whole, g);
+    tile_load<NT>(res, base, n, whole, a);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        a[u].x = __fadd_rn(a[u].x, __fmul_rn(lr, g[u].x));
+        a[u].y = __fadd_rn(a[u].y, __fmul_rn(lr, g[u].y));
+        a[u].z = __fadd_rn(a[u].z, __fmul_rn(lr, g[u].z));
+        a[u].w = __fadd_rn(a[u].w, __fmul_rn(lr, g[u].w));
+    }
+    const uint32_t bits = tile_test(a, base, n, whole, test);
+    const uint32_t count = tile_count(bits);
+    if (lane == 0) counts[tile] = (uint16_t)count;
+    if (count <= SLOT_C) {
+        if (count != 0)
+            tile_rank(a, bits, base, [&](uint32_t rank, uint32_t i, float x) {
+                slots[slot_at(tile, rank)] = SlotEntry{i, x};
+            });
+        slot_pad(slots, tile, count);
+    }
+    if (ZERO && count <= SLOT_C) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t b = bits >> (4 * u);
+            if (b & 1u) a[u].x = 0.0f;
+            if (b & 2u) a[u].y = 0.0f;
+            if (b & 4u) a[u].z = 0.0f;
+            if (b & 8u) a[u].w = 0.0f;
+        }
+    }
+    if (whole) {
+        float4* p = reinterpret_cast<float4*>(res + base) + lane;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) p[u * WAVE] = a[u];
+    } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t i = base + 256u * u + 4u * (uint32_t)lane;
+            if (i < n) res[i] = a[u].x;
+            if (i + 1 < n) res[i + 1] = a[u].y;
+            if (i + 2 < n) res[i + 2] = a[u].z;
+            if (i + 3 < n) res[i + 3] = a[u].w;
+        }
+    }
+}
+
+template <bool ZERO, bool NT>
+__global__ __launch_bounds__(SLOT_FILL_BLOCK) void slot_fill_accumulate_kernel(
+    const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n,
+    const float* __restrict__ d_threshold, uint16_t* __restrict__ counts,
+    SlotEntry* __restrict__ slots, uint32_t ntiles) {
+    const uint32_t tile = blockIdx.x * (SLOT_FILL_BLOCK / WAVE) + (threadIdx.x >> 6);
+    if (tile >= ntiles) return;
+    const float th = *d_threshold;
+    if (th == th)
+        slot_fill_accumulate_tile<ZERO, NT>(grad, res, lr, n, TestFloat{__builtin_fabsf(th)}, counts,
+                                            slots, tile);
+    else
+        slot_fill_accumulate_tile<ZERO, NT>(grad, res, lr, n, TestKey{magnitude_key(th)}, counts,
+                                            slots, tile);
+}
+
+// ---- second pass: the place of every tile ----
+// Workgroup `seg` (a ticket) owns 1024 x tpt consecutive tiles, tpt per thread; a
+// chained scan over the counts gives place[tile], the number of entries selected
+// before the tile.  The workgroup that holds the last tiles writes the totals.
+// The tiles that selected more than SLOT_FEW entries are listed on the way, in no
+// particular order, for the third pass to share them out evenly: those whose slot
+// holds them all from the front of `list`, the dense ones from its back (the list
+// has a word per tile, so the two never meet); one atomic per workgroup and kind.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void slot_scan_kernel(
+    const uint16_t* __restrict__ counts, uint32_t* __restrict__ place, uint32_t* __restrict__ list,
+    uint32_t ntiles, uint32_t tpt, uint64_t capacity, uint64_t* __restrict__ nnz_out,
+    ScanHeader* hdr, uint64_t* seg_desc, uint64_t* group_desc, uint32_t nseg) {
+    static_assert(BLOCK == SLOT_SCAN_BLOCK, "one thread per tile and turn");
+    constexpr int WAVES = BLOCK / WAVE;
+    __shared__ uint32_t s_count[WAVES];
+    __shared__ uint32_t s_listed[WAVES];       // fuller tiles in the low half, dense ones in the high half
+    __shared__ uint32_t s_seg;
+    __shared__ uint32_t s_list_base[2];
+    __shared__ uint32_t s_before[2];
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    if (tid == 0) s_seg = atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    const uint32_t seg = s_seg;
+    const uint64_t first_tile = ((uint64_t)seg * BLOCK + tid) * tpt;
+    uint32_t mine = 0, my_listed = 0;
+    for (uint32_t k = 0; k < tpt; ++k)
+        if (first_tile + k < ntiles) {
+            const uint32_t c = counts[first_tile + k];
+            mine += c;
+            my_listed += c > SLOT_C ? 0x10000u : c > SLOT_FEW ? 1u : 0u;
+        }
+    // a workgroup has at most 1024 x tpt tiles of either kind; the two sums share a
+    // word as long as that stays below 2^16
+    const uint32_t inclusive = wave_inclusive_scan(mine);
+    const uint32_t listed_inclusive = wave_inclusive_scan(my_listed);
+    if (lane == WAVE - 1) {
+        s_count[wave] = inclusive;
+        s_listed[wave] = listed_inclusive;
+    }
+    __syncthreads();
+    uint32_t aggregate = 0, wave_first = 0, listed_total = 0, listed_first = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+        if (w == wave) {
+            wave_first = aggregate;
+            listed_first = listed_total;
+        }
+        aggregate += s_count[w];
+        listed_total += s_listed[w];
+    }
+    const uint32_t group = seg / SCAN_GROUP;
+    if (tid == 2 * WAVE && (listed_total & 0xffffu) != 0)
+        s_list_base[0] = atomicAdd(&hdr->pad[SLOT_FULLER_WORD], listed_total & 0xffffu);
+    if (tid == 3 * WAVE && (listed_total >> 16) != 0)
+        s_list_base[1] = atomicAdd(&hdr->pad[SLOT_DENSE_WORD], listed_total >> 16);
+    if (wave == 0) {
+        const uint32_t before = scan_within_group(hdr, seg_desc, group_desc, seg, aggregate);
+        if (lane == 0) s_before[0] = before;
+    } else if (wave == 1) {
+        const uint32_t before = scan_across_groups(hdr, group_desc, group);
+        if (lane == 0) s_before[1] = before;
+    }
+    __syncthreads();
+    const uint32_t exclusive = s_before[0] + s_before[1];
+    if (tid == 0 && group != 0 && seg % SCAN_GROUP == SCAN_GROUP - 1)
+        scan_close_group(group_desc, group, exclusive + aggregate);
+
+    uint32_t pos = exclusive + wave_first + inclusive - mine;   // below 2^32: at most n entries in all
+    const uint32_t listed_before = listed_first + listed_inclusive - my_listed;
+    uint32_t fuller_at = (listed_total & 0xffffu) ? s_list_base[0] + (listed_before & 0xffffu) : 0u;
+    uint32_t dense_at = (listed_total >> 16) ? s_list_base[1] + (listed_before >> 16) : 0u;
+    for (uint32_t k = 0; k < tpt; ++k) {
+        const uint64_t t = first_tile + k;
+        if (t >= ntiles) break;
+        const uint32_t c = counts[t];
+        place[t] = pos;
+        if (c > SLOT_C) list[ntiles - 1 - dense_at++] = (uint32_t)t;
+        else if (c > SLOT_FEW) list[fuller_at++] = (uint32_t)t;
+        pos += c;
+    }
+    if (seg == nseg - 1 && tid == 0) {
+        const uint64_t total = (uint64_t)exclusive + aggregate;
+        const bool failed =
+            __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+        nnz_out[0] = failed ? ~0ull : (total < capacity ? total : capacity);
+        nnz_out[1] = failed ? ~0ull : total;
+    }
+}
+
+// ---- third pass: the entries go to their places ----
+// Three kinds of tile.  Few entries (at most SLOT_FEW, nearly every tile of a
+// sparsely selected vector): a wave owns 64 consecutive tiles, one per lane, and a
+// lane copies its tile's entries with two loads.  Fuller slots, and dense tiles
+// (count above SLOT_C, nothing in the slot): they come in runs, where a layer of
+// the model lies above the threshold, so they are taken from the lists of the
+// second pass and shared out evenly over all the waves of the launch, wherever
+// they lie.  A fuller slot is copied by half a wave, one lane per entry, four
+// slots in flight; a dense tile is walked again by a wave, which writes each
+// selected element at the tile's place plus its rank.
+//
+// What still has to happen to the vector where an entry came from: nothing (a
+// copy, or candidates), a zero where the entry is written out, or - for the slots
+// of a first pass that wrote the zeros itself - the value back where the output
+// is full.  Dense tiles were left as they were by every first pass, so
+// `DENSE_ZERO` alone says whether the walk zeroes what it writes out.  Entries
+// past the end of the output stay in the vector.
+enum SlotAfter { SLOT_KEEP = 0, SLOT_ZERO = 1, SLOT_RESTORE = 2 };
+
+template <int AFTER, bool DENSE_ZERO, typename Test>
+__device__ __forceinline__ void slot_emit_tiles(float* __restrict__ acc, uint32_t n, Test test,
+                                                const uint16_t* __restrict__ counts,
+                                                const uint32_t* __restrict__ place,
+                                                const SlotEntry* __restrict__ slots,
+                                                const uint32_t* __restrict__ list,
+                                                const ScanHeader* __restrict__ hdr,
+                                                uint32_t ntiles, uint32_t* __restrict__ idx_out,
+                                                float* __restrict__ val_out, uint64_t capacity) {
+    const int lane = lane_id();
+    const uint32_t wave_of_launch = blockIdx.x * (SLOT_EMIT_BLOCK / WAVE) + (threadIdx.x >> 6);
+    const uint32_t waves = gridDim.x * (SLOT_EMIT_BLOCK / WAVE);
+    auto put = [&](uint64_t pos, uint32_t i, uint32_t bits) {
+        if (pos < capacity) {
+            idx_out[pos] = i;
+            val_out[pos] = __uint_as_float(bits);
+            if (AFTER == SLOT_ZERO) acc[i] = 0.0f;
+        } else if (AFTER == SLOT_RESTORE) {
+            acc[i] = __uint_as_float(bits);
+        }
+    };
+    // ---- tiles with few entries: one lane per tile ----
+    const uint64_t t = (uint64_t)wave_of_launch * WAVE + lane;
+    if (t < ntiles) {                                   // nothing past the last tile
+        const uint32_t c = counts[t];
+        if (c != 0 && c <= SLOT_FEW) {
+            const uint64_t at = place[t];
+            const SlotEntry* from = slots + slot_at(t, 0);
+            SlotEntry e[SLOT_FEW];
+#pragma unroll
+            for (uint32_t j = 0; j < SLOT_FEW; ++j) e[j] = from[j * SLOT_GROUP];   // padded: all written
+#pragma unroll
+            for (uint32_t j = 0; j < SLOT_FEW; ++j)
+                if (j < c) put(at + j, e[j].idx, __float_as_uint(e[j].val));
+        }
+    }
+    // ---- fuller slots: half a wave per slot, one lane per entry, four in flight ----
+    const uint32_t nfuller = hdr->pad[SLOT_FULLER_WORD];
+    const uint32_t sub = (uint32_t)lane & 31u;
+    const uint32_t half_of_launch = 2u * wave_of_launch + ((uint32_t)lane >> 5);
+    for (uint64_t q0 = 4ull * half_of_launch; q0 < nfuller; q0 += 8ull * waves) {
+        uint32_t tile[4], c[4], at[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            tile[u] = q0 + u < nfuller ? list[q0 + u] : 0xffffffffu;
+            c[u] = 0;
+            at[u] = 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (tile[u] != 0xffffffffu) {
+                c[u] = counts[tile[u]];
+                at[u] = place[tile[u]];
+            }
+        SlotEntry e[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (sub < c[u]) e[u] = slots[slot_at(tile[u], sub)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (sub < c[u]) put((uint64_t)at[u] + sub, e[u].idx, __float_as_uint(e[u].val));
+    }
+    // ---- dense tiles: walked again, a wave each ----
+    const uint32_t ndense = hdr->pad[SLOT_DENSE_WORD];
+    for (uint32_t q = wave_of_launch; q < ndense; q += waves) {
+        const uint64_t tile = list[ntiles - 1 - q];
+        const uint64_t at = place[tile];
+        const uint64_t base = tile * SLOT_TILE;
+        const bool whole = base + SLOT_TILE <= n;
+        float4 v[4];
+        tile_load<false>(acc, base, n, whole, v);
+        const uint32_t bits = tile_test(v, base, n, whole, test);
+        tile_rank(v, bits, base, [&](uint32_t rank, uint32_t i, float x) {
+            const uint64_t pos = at + rank;
+            if (pos < capacity) {
+                idx_out[pos] = i;
+                val_out[pos] = x;
+                if (DENSE_ZERO) acc[i] = 0.0f;
+            }
+        });
+    }
+}
+
+template <int AFTER, bool DENSE_ZERO>
+__global__ __launch_bounds__(SLOT_EMIT_BLOCK) void slot_emit_kernel(
+    float* __restrict__ acc, uint32_t n, const float* __restrict__ d_threshold,
+    const uint16_t* __restrict__ counts, const uint32_t* __restrict__ place,
+    const SlotEntry* __restrict__ slots, const uint32_t* __restrict__ list,
+    const ScanHeader* __restrict__ hdr, uint32_t ntiles, uint32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, uint64_t capacity) {
+    const float th = *d_threshold;
+    if (th == th)
+        slot_emit_tiles<AFTER, DENSE_ZERO>(acc, n, TestFloat{__builtin_fabsf(th)}, counts, place,
+                                           slots, list, hdr, ntiles, idx_out, val_out, capacity);
+    else
+        slot_emit_tiles<AFTER, DENSE_ZERO>(acc, n, TestKey{magnitude_key(th)}, counts, place, slots,
+                                           list, hdr, ntiles, idx_out, val_out, capacity);
+}
+
+// ---- host side (okt_select.hip) ----
+// Shortest vector that takes the three-pass form (SLOT_MIN_N unless the test hook
+// has set another).
+uint64_t slot_min_n();
+// Second and third pass of a select through slots; the first pass has filled the
+// counts and the slots of the workspace `ws` (laid out by `plan`, scan state
+// cleared).  `d_threshold`: what the first pass tested against.  `after`: what the
+// entries of the slots still need done to the vector; `dense_zero`: the walk over
+// a dense tile zeroes what it writes out.
+int launch_slot_finish(float* d_acc, uint64_t n, const float* d_threshold, const SlotPlan& plan,
+                       char* ws, int after, bool dense_zero, uint32_t* d_idx_out, float* d_val_out,
+                       uint64_t capacity, uint64_t* d_nnz_out, hipStream_t s);
+
+}  // namespace okt
+#endif

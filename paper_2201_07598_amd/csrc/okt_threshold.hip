@@ -32,6 +32,7 @@
 #include "okt_device.h"
 #include "okt_select_kernel.h"
 #include "okt_sizes.h"
+#include "okt_slots.h"
 
 namespace okt {
 
@@ -383,15 +384,13 @@ __global__ void radix_init_kernel(RadixState* state, uint32_t* hist, uint32_t wo
 // Clears the radix state, the histograms and the two scan states (collection,
 // final select) of a refresh iteration.
 __global__ void refresh_init_kernel(RadixState* state, uint32_t* hist, uint32_t hist_words,
-                                    uint64_t* scan_a, uint64_t* scan_b, uint32_t scan_words,
-                                    uint32_t spin_limit) {
+                                    uint64_t* scan_a, uint32_t words_a, uint64_t* scan_b,
+                                    uint32_t words_b, uint32_t spin_limit) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < hist_words) hist[i] = 0;
-    if (i < scan_words) {
-        const uint64_t w = i == SCAN_SPIN_WORD ? (uint64_t)spin_limit : 0ull;
-        scan_a[i] = w;
-        scan_b[i] = w;
-    }
+    const uint64_t w = i == SCAN_SPIN_WORD ? (uint64_t)spin_limit : 0ull;
+    if (i < words_a) scan_a[i] = w;
+    if (i < words_b) scan_b[i] = w;
     if (i == 0) {
         RadixState z = {};
         *state = z;
@@ -574,8 +573,19 @@ extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual
 
     const SelectShape shape = select_shape(n, device_cus());
     const size_t scan_bytes = refresh_scan_bytes(n);
-    const size_t fixed = threshold_ws_min_bytes() + 2 * scan_bytes;
-    const uint64_t cand_cap = ws_bytes > fixed ? ((ws_bytes - fixed) / 8) & ~(uint64_t)63 : 0;
+    // The collection of the candidates goes through per-tile slots where the vector
+    // is long enough and the workspace has room for them next to the candidates;
+    // else through the chained scan of the one-kernel select.
+    const SlotPlan plan = slot_plan(n, device_cus());
+    const size_t slot_bytes = round_up_256(plan.bytes);
+    bool slots = n >= slot_min_n() && ws_bytes > threshold_ws_min_bytes() + scan_bytes + slot_bytes;
+    size_t fixed = threshold_ws_min_bytes() + scan_bytes + (slots ? slot_bytes : scan_bytes);
+    uint64_t cand_cap = ws_bytes > fixed ? ((ws_bytes - fixed) / 8) & ~(uint64_t)63 : 0;
+    if (slots && cand_cap < n / 16) {
+        slots = false;
+        fixed = threshold_ws_min_bytes() + 2 * scan_bytes;
+        cand_cap = ws_bytes > fixed ? ((ws_bytes - fixed) / 8) & ~(uint64_t)63 : 0;
+    }
     if (n < RS_SAMPLE_MIN_N || cand_cap < n / 16) {
         // short vector (or a workspace without room for candidates): the three steps
         // one after the other, each with the workspace to itself
@@ -593,18 +603,21 @@ extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual
     uint32_t* hist1 = hist_sample + RS_MAX_BINS;
     uint32_t* hist2 = hist1 + RS_MAX_BINS;
     uint32_t* hist3 = hist2 + RS_MAX_BINS;
-    char* scan_a = (char*)d_ws + threshold_ws_min_bytes();
-    char* scan_b = scan_a + scan_bytes;
-    float* cand_val = (float*)(scan_b + scan_bytes);
+    char* scan_b = (char*)d_ws + threshold_ws_min_bytes();          // the final select's
+    char* scan_a = scan_b + scan_bytes;                             // the collection's, or the slots
+    float* cand_val = (float*)(scan_a + (slots ? slot_bytes : scan_bytes));
     uint32_t* cand_idx = (uint32_t*)(cand_val + cand_cap);
     auto header = [](char* p) { return (ScanHeader*)p; };
     auto segs = [](char* p) { return (uint64_t*)(p + SCAN_HEADER_BYTES); };
 
-    const uint32_t scan_words = (uint32_t)(scan_ws_bytes(shape.nseg) / 8);
-    const uint32_t init_words = scan_words > 4u * RS_MAX_BINS ? scan_words : 4u * RS_MAX_BINS;
+    const uint32_t words_b = (uint32_t)(scan_ws_bytes(shape.nseg) / 8);
+    const uint32_t words_a = slots ? (uint32_t)(scan_ws_bytes(plan.nseg) / 8) : words_b;
+    uint32_t init_words = 4u * RS_MAX_BINS;
+    if (words_a > init_words) init_words = words_a;
+    if (words_b > init_words) init_words = words_b;
     hipLaunchKernelGGL(refresh_init_kernel, dim3((init_words + 255) / 256), dim3(256), 0, s, state,
-                       hist_sample, 4u * RS_MAX_BINS, (uint64_t*)scan_a, (uint64_t*)scan_b,
-                       scan_words, spin_limit_setting());
+                       hist_sample, 4u * RS_MAX_BINS, (uint64_t*)scan_a, words_a, (uint64_t*)scan_b,
+                       words_b, spin_limit_setting());
 
     const uint64_t blocks = n / 1024;
     uint64_t stride = blocks / RS_SAMPLE_BLOCKS;
@@ -614,14 +627,32 @@ extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual
                        dim3((unsigned)((nsamp + SAMPLE_PER_WG - 1) / SAMPLE_PER_WG)),
                        dim3(HIST_BLOCK), 0, s, d_residual_inout, d_grad, lr, (uint32_t)nsamp,
                        (uint32_t)stride, hist_sample, state, n, k);
-    timing_before(s);
-    auto* collect = stream_past_cache(n) ? accumulate_collect_kernel<SEL_BLOCK, SEL_U, SEL_STASH, true>
-                                         : accumulate_collect_kernel<SEL_BLOCK, SEL_U, SEL_STASH, false>;
-    hipLaunchKernelGGL(collect, dim3(shape.nseg),
-                       dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout, lr, (uint32_t)n, state,
-                       cand_idx, cand_val, cand_cap, header(scan_a), segs(scan_a),
-                       segs(scan_a) + shape.nseg, shape.nseg, shape.piece);
-    timing_after(s);
+    if (slots) {
+        // the sample's bound is a magnitude key, so its bits read as an fp32 are the
+        // bound itself: the slot kernels take it for their threshold
+        const float* bound = reinterpret_cast<const float*>(&state->cand_lo);
+        timing_before(s);
+        auto* fill = stream_past_cache(n) ? slot_fill_accumulate_kernel<false, true>
+                                          : slot_fill_accumulate_kernel<false, false>;
+        constexpr uint32_t per_wg = SLOT_FILL_BLOCK / WAVE;
+        hipLaunchKernelGGL(fill, dim3((plan.ntiles + per_wg - 1) / per_wg), dim3(SLOT_FILL_BLOCK), 0,
+                           s, d_grad, d_residual_inout, lr, (uint32_t)n, bound,
+                           (uint16_t*)(scan_a + plan.counts_at), (SlotEntry*)(scan_a + plan.slots_at),
+                           plan.ntiles);
+        timing_after(s);
+        const int rc = launch_slot_finish(d_residual_inout, n, bound, plan, scan_a, SLOT_KEEP, false,
+                                          cand_idx, cand_val, cand_cap, state->collected, s);
+        if (rc != OKT_OK) return rc;
+    } else {
+        timing_before(s);
+        auto* collect = stream_past_cache(n)
+                            ? accumulate_collect_kernel<SEL_BLOCK, SEL_U, SEL_STASH, true>
+                            : accumulate_collect_kernel<SEL_BLOCK, SEL_U, SEL_STASH, false>;
+        hipLaunchKernelGGL(collect, dim3(shape.nseg), dim3(SEL_BLOCK), 0, s, d_grad, d_residual_inout,
+                           lr, (uint32_t)n, state, cand_idx, cand_val, cand_cap, header(scan_a),
+                           segs(scan_a), segs(scan_a) + shape.nseg, shape.nseg, shape.piece);
+        timing_after(s);
+    }
 
     const uint64_t steps = (((n / 16) >> 2) + HIST_STEP4 - 1) / HIST_STEP4;
     const uint64_t one_per_cu = device_cus();
