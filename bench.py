@@ -395,17 +395,19 @@ def headline(args, torch, np, okt, wl, ev, cfg):
     for c, v in summarise(sep_main).items():
         table_main.setdefault(c, v)
     alg = algorithmic_bytes(n, nnz_now, E, U)
+    three_pass = n >= okt.okt_slot_min_n()
     kernels = {}
     for c, v in table.items():
         kernels[c] = {"calls_per_step": calls_per_step[c], "us_per_call": stats(np, v, alg.get(c))}
         if c in table_main:
-            kernels[c]["us_main_kernel"] = stats(np, table_main[c], main_kernel_bytes(c, alg, n))
+            kernels[c]["us_main_kernel"] = stats(np, table_main[c], main_kernel_bytes(c, alg, n, three_pass))
+            kernels[c]["kernel"] = main_kernel_name(c, three_pass)
 
     dom_us = float(np.mean(in_region[dominant])) if dominant in in_region else \
         float(np.median(table_main[dominant]))
-    dom_bytes = main_kernel_bytes(dominant, alg, n)
+    dom_bytes = main_kernel_bytes(dominant, alg, n, three_pass)
     achieved = dom_bytes / dom_us * 1e-3
-    roofline = {"bound": "hbm", "kernel": MAIN_KERNEL.get(dominant, dominant), "call": dominant,
+    roofline = {"bound": "hbm", "kernel": main_kernel_name(dominant, three_pass), "call": dominant,
                 "timed": "events recorded by the library right before and after the launch of the "
                          "call's main kernel, one launch per step inside the timed region",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -470,6 +472,11 @@ def headline(args, torch, np, okt, wl, ev, cfg):
     return out, host_contrib0, (lo, hi), iters
 
 
+# the first pass of the selects of a long vector (the library's three-pass form)
+THREE_PASS_KERNEL = {"select": "slot_fill_kernel", "select_copy": "slot_fill_kernel",
+                     "accumulate_select": "slot_fill_accumulate_kernel<zeroing>",
+                     "accumulate_topk_select": "slot_fill_accumulate_kernel<candidates>"}
+
 # the kernel that moves the data in each call
 MAIN_KERNEL = {"accumulate": "accumulate_kernel", "threshold": "collect_kernel",
                "threshold_full_vector": "radix_hist_kernel x 3 (no main kernel is bracketed)", "select": "select_kernel",
@@ -492,11 +499,24 @@ def algorithmic_bytes(n, nnz, E, U):
     }
 
 
-def main_kernel_bytes(call, alg, n):
+def main_kernel_bytes(call, alg, n, three_pass=False):
     """Bytes of the call's main kernel alone.  In the one-call refresh iteration that
     kernel forms the accumulator and sets the candidates aside (12 B per element);
-    the emitted entries and their zeros are written by the small kernels after it."""
-    return 12.0 * n if call == "accumulate_topk_select" else alg.get(call)
+    the emitted entries and their zeros are written by the small kernels after it.
+    The same holds for every select of a vector long enough for the three-pass
+    form: the first pass streams the vector (4 or 12 B per element), the entries
+    reach the output in the two short passes after it."""
+    if call == "accumulate_topk_select" or (three_pass and call == "accumulate_select"):
+        return 12.0 * n
+    if three_pass and call in ("select", "select_copy"):
+        return 4.0 * n
+    return alg.get(call)
+
+
+def main_kernel_name(call, three_pass=False):
+    if three_pass and call in THREE_PASS_KERNEL:
+        return THREE_PASS_KERNEL[call]
+    return MAIN_KERNEL.get(call, call)
 
 
 def read_traffic(workload, call):
@@ -587,16 +607,20 @@ def measure_calls(args, torch, np, okt, wl, ev, cfg):
            "state": "zero residual" if not cfg.burn_in else
            f"steady-state residual ({cfg.burn_in} untimed iterations of exact top-k on device noise)",
            "kernels": {}}
+    three_pass = n >= okt.okt_slot_min_n()
+    out["select_form"] = "three passes (per-tile slots)" if three_pass else "one kernel (chained scan)"
     for name, (call, restore, nbytes) in calls.items():
         whole, main = time_over_slots(torch, ev, call, nslots, restore, reps)
-        kbytes = main_kernel_bytes(name, {name: nbytes}, n)
+        kbytes = main_kernel_bytes(name, {name: nbytes}, n, three_pass)
         if name == "threshold_full_vector":
             main = []                      # three equal passes: the library brackets none of them
-        out["kernels"][name] = {"kernel": MAIN_KERNEL[name], "us_per_call": stats(np, whole, nbytes),
+        out["kernels"][name] = {"kernel": main_kernel_name(name, three_pass),
+                                "us_per_call": stats(np, whole, nbytes),
                                 "us_main_kernel": stats(np, main, kbytes)}
         kus = float(np.median(main)) if len(main) else float(np.median(whole))
-        log(f"[bench] {cfg.name} {name:24s} call {np.median(whole):9.1f} us  kernel {kus:9.1f} us "
-            f"= {kbytes / max(kus, 0.2) * 1e-3 / HBM_PEAK_GBS * 100:5.1f} % of peak")
+        log(f"[bench] {cfg.name} {name:24s} call {np.median(whole):9.1f} us = "
+            f"{nbytes / np.median(whole) * 1e-3 / HBM_PEAK_GBS * 100:5.1f} % of peak;  main kernel {kus:9.1f} us "
+            f"= {kbytes / max(kus, 0.2) * 1e-3 / HBM_PEAK_GBS * 100:5.1f} %")
     if drift and cfg.burn_in:
         out["reuse_selected_over_k"] = [round(v / k, 4) for v in drift]
         out["max_abs_drift"] = round(max(abs(v - k) / k for v in drift), 4)

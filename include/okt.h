@@ -83,6 +83,9 @@ void okt_debug_spin_limit(uint32_t polls);
  */
 void okt_debug_slot_min_n(uint64_t n);
 
+/* The length in force: vectors at least this long take the three-pass form. */
+uint64_t okt_slot_min_n(void);
+
 /*
  * Measurement hook.  The next call this thread makes records `start_event` right
  * before and `stop_event` right after the launch of its main kernel (hipEvent_t

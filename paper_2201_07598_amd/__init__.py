@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     okt_coo_threshold_select,
     okt_debug_slot_min_n,
     okt_debug_spin_limit,
+    okt_slot_min_n,
     okt_index_intersect_restore,
     okt_index_intersect_zero,
     okt_last_hip_error,

@@ -2,10 +2,12 @@
 //
 // HBM-bound streaming kernel: 8 B read + 4 B written per element.  Each thread
 // keeps ACC_ITERS 16-byte loads of both inputs in flight before the first use;
-// a wave reads 1 KiB contiguous per load instruction.  The product and the sum
+// a wave reads 1 KiB contiguous per load instruction; vectors far longer than the
+// last-level cache are read with the non-temporal hint.  The product and the sum
 // are rounded separately (no fused multiply-add), so the result is the same as
 // two fp32 tensor operations.
 #include "okt_device.h"
+#include "okt_sizes.h"
 
 namespace okt {
 
@@ -17,6 +19,7 @@ __device__ __forceinline__ float acc_one(float e, float g, float lr) {
     return __fadd_rn(e, __fmul_rn(lr, g));
 }
 
+template <bool NT>
 __global__ __launch_bounds__(ACC_BLOCK) void accumulate_kernel(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n) {
     const uint32_t n4 = n >> 2;
@@ -28,8 +31,8 @@ __global__ __launch_bounds__(ACC_BLOCK) void accumulate_kernel(
 #pragma unroll
         for (int it = 0; it < ACC_ITERS; ++it) {
             const uint32_t i = base4 + it * ACC_BLOCK + threadIdx.x;
-            g[it] = g4[i];
-            e[it] = e4[i];
+            g[it] = load_quad<NT>(g4 + i);
+            e[it] = load_quad<NT>(e4 + i);
         }
 #pragma unroll
         for (int it = 0; it < ACC_ITERS; ++it) {
@@ -72,8 +75,9 @@ extern "C" int okt_residual_accumulate(const float* d_grad, float* d_residual_in
     // the last workgroup also owns the n % 4 scalars, so there is always one
     const uint64_t blocks = n4 / ACC_TILE4 + 1;
     timing_before((hipStream_t)stream);
-    hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)blocks), dim3(ACC_BLOCK), 0,
-                       (hipStream_t)stream, d_grad, d_residual_inout, lr, (uint32_t)n);
+    auto* kernel = stream_past_cache(n) ? accumulate_kernel<true> : accumulate_kernel<false>;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(ACC_BLOCK), 0, (hipStream_t)stream,
+                       d_grad, d_residual_inout, lr, (uint32_t)n);
     timing_after((hipStream_t)stream);
     return launch_status();
 }

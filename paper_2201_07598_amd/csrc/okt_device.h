@@ -39,6 +39,38 @@ __device__ __forceinline__ T wave_inclusive_scan(T v) {
     return v;
 }
 
+// A 16-byte load, optionally with the non-temporal hint.  The hint pays on vectors
+// far larger than the last-level cache (nothing of them is found there again:
+// 4 to 7 % on the walks below) and costs as much on vectors that fit it, where
+// what one iteration writes the next one still finds cached; the host decides by
+// the vector's length.
+template <bool NT>
+__device__ __forceinline__ float4 load_quad(const float4* p) {
+    if (NT) {
+        typedef float v4f __attribute__((ext_vector_type(4)));
+        const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+        return make_float4(v.x, v.y, v.z, v.w);
+    }
+    return *p;
+}
+
+// One element of a long vector overwritten on its own, its line most likely not
+// in the cache.  The L2 takes a 4-byte store into a line it does not hold as a
+// partial line, and partial lines go out to memory as read-modify-writes, whose
+// cost lands on whatever streams next: some 330,000 such zeros slowed the 700 us
+// streaming kernel that followed by 60 us.  With the element loaded first the
+// line is there in full when the store arrives and leaves as an ordinary line
+// write, at half that cost.  (The value is not needed; the empty asm keeps the
+// load.  A non-temporal load does not help: it leaves no line behind.)  The load
+// is paid by the kernel that stores, the saving goes to the one after it: used
+// where the sum of the two was measured to gain (the zeros of a refresh
+// iteration's final select), not in the plain selects, where it came out even.
+__device__ __forceinline__ void scattered_store(float* p, float v) {
+    const float old = *p;
+    asm volatile("" ::"v"(old));
+    *p = v;
+}
+
 // ---------------------------------------------------------------------------
 // Chained scan across workgroups (decoupled look-back), two levels deep.
 //

@@ -105,15 +105,14 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
     if (slots_apply(n, ws_bytes)) {
         const SlotPlan plan = slot_plan(n, device_cus());
         char* ws = (char*)d_ws;
-        if (launch_clear_scan_state(d_ws, scan_ws_bytes(plan.nseg) / 8, s) != hipSuccess)
-            return OKT_ERR_HIP;
         timing_before(s);
         constexpr bool zero = std::is_same<Source, DenseSource>::value;
         auto* fill = stream_past_cache(n) ? slot_fill_kernel<true> : slot_fill_kernel<false>;
         constexpr uint32_t per_wg = SLOT_FILL_BLOCK / WAVE;
         hipLaunchKernelGGL(fill, dim3((plan.ntiles + per_wg - 1) / per_wg), dim3(SLOT_FILL_BLOCK), 0,
                            s, d_acc, (uint32_t)n, d_threshold, (uint16_t*)(ws + plan.counts_at),
-                           (SlotEntry*)(ws + plan.slots_at), plan.ntiles);
+                           (SlotEntry*)(ws + plan.slots_at), plan.ntiles, (uint64_t*)ws,
+                           (uint32_t)(scan_ws_bytes(plan.nseg) / 8), spin_limit_setting());
         timing_after(s);
         return launch_slot_finish(d_acc, n, d_threshold, plan, ws, zero ? SLOT_ZERO : SLOT_KEEP,
                                   zero, d_idx_out, d_val_out, capacity, d_nnz_out, s);
@@ -138,6 +137,8 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
 extern "C" void okt_debug_slot_min_n(uint64_t n) {
     okt::g_slot_min_n.store(n, std::memory_order_relaxed);
 }
+
+extern "C" uint64_t okt_slot_min_n(void) { return okt::slot_min_n(); }
 
 extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshold,
                                     uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
@@ -228,8 +229,6 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
     if (slots_apply(n, ws_bytes)) {
         const SlotPlan plan = slot_plan(n, device_cus());
         char* ws = (char*)d_ws;
-        if (launch_clear_scan_state(d_ws, scan_ws_bytes(plan.nseg) / 8, s) != hipSuccess)
-            return OKT_ERR_HIP;
         timing_before(s);
         auto* fill = stream_past_cache(n) ? slot_fill_accumulate_kernel<true, true>
                                           : slot_fill_accumulate_kernel<true, false>;
@@ -237,7 +236,8 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
         hipLaunchKernelGGL(fill, dim3((plan.ntiles + per_wg - 1) / per_wg), dim3(SLOT_FILL_BLOCK), 0,
                            s, d_grad, d_residual_inout, lr, (uint32_t)n, d_threshold,
                            (uint16_t*)(ws + plan.counts_at), (SlotEntry*)(ws + plan.slots_at),
-                           plan.ntiles);
+                           plan.ntiles, (uint64_t*)ws, (uint32_t)(scan_ws_bytes(plan.nseg) / 8),
+                           spin_limit_setting());
         timing_after(s);
         return launch_slot_finish(d_residual_inout, n, d_threshold, plan, ws, SLOT_RESTORE, true,
                                   d_idx_out, d_val_out, capacity, d_nnz_out, s);

@@ -54,21 +54,6 @@ struct StashMemory {                                 // the stashes of a workgro
     }
 };
 
-// A 16-byte load, optionally with the non-temporal hint.  The hint pays on vectors
-// far larger than the last-level cache (nothing of them is found there again:
-// 4 to 7 % on the walks below) and costs as much on vectors that fit it, where
-// what one iteration writes the next one still finds cached; the host decides by
-// the vector's length.
-template <bool NT>
-__device__ __forceinline__ float4 load_quad(const float4* p) {
-    if (NT) {
-        typedef float v4f __attribute__((ext_vector_type(4)));
-        const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
-        return make_float4(v.x, v.y, v.z, v.w);
-    }
-    return *p;
-}
-
 // One round of a wave: 64 lanes x float4 = 256 consecutive elements starting at
 // `first` (lane l holds first + 4l .. first + 4l + 3); sx..sw say which of the
 // lane's components are selected.  Calls sink(rank, index, value) for every
@@ -227,8 +212,8 @@ struct CandidateSource {
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return idx_in ? idx_in[i] : i; }
     // `walked` is the array the walk runs over, `i` the position in it, `o` the output index
     __device__ __forceinline__ void stash_emit(float* walked, uint32_t i, uint32_t o) const {
-        if (idx_in) res[o] = 0.0f;
-        else walked[i] = 0.0f;
+        if (idx_in) scattered_store(res + o, 0.0f);
+        else scattered_store(walked + i, 0.0f);
     }
     __device__ __forceinline__ void walk_emit(float* walked, uint32_t i, uint32_t o) const {
         stash_emit(walked, i, o);
@@ -289,7 +274,7 @@ __device__ __forceinline__ void select_finish(
             val_out[pos] = e.val;
             source.stash_emit(acc, e.idx, o);
         } else if (Source::restore) {
-            acc[e.idx] = e.val;             // output full: the entry stays in the residual
+            scattered_store(acc + e.idx, e.val);   // output full: the entry stays in the residual
         }
     }
     if (!all_stashed) {

@@ -62,12 +62,15 @@ inline bool stream_past_cache(uint64_t n) { return n >= (96u << 20); }      // 3
 // writes what a tile of SLOT_TILE elements (one wave) selects into the tile's own
 // slot of SLOT_C entries and counts it; a scan over the counts and a copy out of
 // the slots follow as a short second pass, and the tiles that selected more than
-// a slot holds (a local density above SLOT_C / SLOT_TILE = 3.1 %) are walked
-// again by a third.  Workspace: a scan state, then per tile a 2-byte count, a
-// 4-byte place, 4 bytes of the list of dense tiles and the slot, a good quarter of
-// the vector's bytes in all.
+// a slot holds (a local density above SLOT_C / SLOT_TILE = 12.5 %) are walked
+// again by a third.  Gradients select unevenly - in the layered workloads three
+// quarters of the selected entries sit in tiles that select 3 to 12 % - and a
+// slot costs address space, not traffic: only the entries written are ever
+// touched.  Workspace: a scan state, then per tile a 2-byte count, a 4-byte
+// place, 4 bytes of the list of fuller and dense tiles and the slot, as many bytes
+// as the vector has elements in all.
 constexpr uint32_t SLOT_TILE = 1024;
-constexpr uint32_t SLOT_C = 32;
+constexpr uint32_t SLOT_C = 128;
 constexpr uint32_t SLOT_GROUP = 4;                   // tiles whose slots are interleaved
 constexpr uint32_t SLOT_SCAN_TILES = 1024;           // tiles per workgroup of the second pass and turn
 struct SlotPlan {

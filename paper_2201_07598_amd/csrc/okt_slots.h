@@ -22,31 +22,33 @@ namespace okt {
 
 struct SlotEntry { uint32_t idx; float val; };
 static_assert(sizeof(SlotEntry) == 8, "an entry is one 8-byte store");
+static_assert(SLOT_C % 32 == 0 && SLOT_C <= SLOT_TILE, "half a wave copies a slot in whole turns");
 
 constexpr uint32_t SLOT_FEW = 4;                          // entries a lane of the third pass copies by itself
 constexpr int SLOT_FILL_BLOCK = 256;                      // 4 waves = 4 tiles per workgroup
 static_assert(SLOT_FILL_BLOCK / WAVE == (int)SLOT_GROUP, "a workgroup of the first pass fills one group of slots");
-
-// Where entry j of a tile's slot lives.  The slots of the SLOT_GROUP tiles that one
-// workgroup of the first pass fills are interleaved entry by entry, so that the
-// first four entries of all of them - all there is, as a rule - share one
-// 128-byte line, which the workgroup always writes in full (with zeros where a
-// tile has fewer entries): the L2 hands a whole line to memory, where a part of a
-// line costs a read-modify-write, and a workgroup dirties one line, not four.
-__device__ __forceinline__ uint64_t slot_at(uint64_t tile, uint32_t j) {
-    return (tile / SLOT_GROUP) * (SLOT_GROUP * SLOT_C) + (uint64_t)j * SLOT_GROUP + tile % SLOT_GROUP;
-}
-// The first pass's stores for a tile that selected `count` entries, given the
-// sink's stores of the entries themselves: zeros up to SLOT_FEW entries.
-__device__ __forceinline__ void slot_pad(SlotEntry* __restrict__ slots, uint64_t tile, uint32_t count) {
-    const uint32_t j = count + (uint32_t)lane_id();
-    if (j < SLOT_FEW) slots[slot_at(tile, j)] = SlotEntry{0u, 0.0f};
-}
 constexpr int SLOT_SCAN_BLOCK = 1024;
 static_assert(SLOT_SCAN_BLOCK == (int)SLOT_SCAN_TILES, "one thread per tile and turn");
 constexpr int SLOT_EMIT_BLOCK = 256;
 constexpr int SLOT_EMIT_TILES = WAVE;                     // tiles per wave of the third pass: one per lane
 constexpr int SLOT_FULLER_WORD = 0, SLOT_DENSE_WORD = 1;  // words of the scan header's padding: tiles listed
+
+// Where entry j of a tile's slot lives.  The first SLOT_FEW entries of every slot -
+// all there is, as a rule - lie together at the front of the slot area, those of
+// the SLOT_GROUP tiles that one workgroup of the first pass fills interleaved in
+// one 128-byte line, which the workgroup always writes in full (with zeros where a
+// tile has fewer entries).  So the usual stores of the first pass form one more
+// dense stream of whole lines, next to the vector's: the L2 hands a whole line to
+// memory where a part of a line costs a read-modify-write, a workgroup dirties one
+// line instead of four, and consecutive workgroups write consecutive lines.  The
+// later entries of the fuller slots follow behind, laid out the same way.
+__device__ __forceinline__ uint64_t slot_at(uint64_t tile, uint32_t j, uint32_t ntiles) {
+    const uint64_t group = tile / SLOT_GROUP, member = tile % SLOT_GROUP;
+    if (j < SLOT_FEW) return group * (SLOT_GROUP * SLOT_FEW) + (uint64_t)j * SLOT_GROUP + member;
+    const uint64_t groups = ((uint64_t)ntiles + SLOT_GROUP - 1) / SLOT_GROUP;
+    return groups * (SLOT_GROUP * SLOT_FEW) + group * (SLOT_GROUP * (SLOT_C - SLOT_FEW)) +
+           (uint64_t)(j - SLOT_FEW) * SLOT_GROUP + member;
+}
 
 // The four rounds of a tile, lane l holding base + 256 u + 4 l .. + 3 of round u.
 // A tile that runs past the end of the vector is loaded element by element, with
@@ -112,11 +114,39 @@ __device__ __forceinline__ uint32_t tile_count(uint32_t bits) {
     return count;
 }
 
+// The first pass's stores for a tile that selected `count` <= SLOT_C entries.  The
+// wave ranks its entries into `stage` (its own SLOT_C entries of LDS) and writes
+// them out with one store instruction per 64 entries, zeros up to SLOT_FEW: a
+// store per round that selected something would double the store instructions of
+// the pass, and those, not the bytes, are what it pays for.
+__device__ __forceinline__ void slot_store_tile(SlotEntry* __restrict__ slots, uint64_t tile,
+                                                uint32_t count, const float4 (&v)[4], uint32_t bits,
+                                                uint64_t base, SlotEntry* stage, uint32_t ntiles) {
+    if (count != 0)
+        tile_rank(v, bits, base,
+                  [&](uint32_t rank, uint32_t i, float x) { stage[rank] = SlotEntry{i, x}; });
+    __builtin_amdgcn_wave_barrier();             // the wave's own LDS writes come before its reads
+    const uint32_t upto = count > SLOT_FEW ? count : SLOT_FEW;
+    for (uint32_t j = (uint32_t)lane_id(); j < upto; j += WAVE)
+        slots[slot_at(tile, j, ntiles)] = j < count ? stage[j] : SlotEntry{0u, 0.0f};
+}
+
+// The first pass also clears the scan state of the second (header and descriptors,
+// `words` 64-bit words; nothing if `state` is null): one launch less, and the
+// second pass starts only when the first has ended.
+__device__ __forceinline__ void slot_clear_scan_state(uint64_t* __restrict__ state, uint32_t words,
+                                                      uint32_t spin_limit) {
+    if (blockIdx.x != 0 || state == nullptr) return;
+    for (uint32_t i = threadIdx.x; i < words; i += SLOT_FILL_BLOCK)
+        state[i] = i == SCAN_SPIN_WORD ? (uint64_t)spin_limit : 0ull;
+}
+
 // ---- first pass over a vector that is only read ----
 template <bool NT, typename Test>
 __device__ __forceinline__ void slot_fill_tile(const float* __restrict__ acc, uint32_t n, Test test,
                                                uint16_t* __restrict__ counts,
-                                               SlotEntry* __restrict__ slots, uint32_t tile) {
+                                               SlotEntry* __restrict__ slots, uint32_t tile,
+                                               SlotEntry* stage, uint32_t ntiles) {
     const uint64_t base = (uint64_t)tile * SLOT_TILE;
     const bool whole = base + SLOT_TILE <= n;
     float4 v[4];
@@ -125,22 +155,22 @@ __device__ __forceinline__ void slot_fill_tile(const float* __restrict__ acc, ui
     const uint32_t count = tile_count(bits);
     if (lane_id() == 0) counts[tile] = (uint16_t)count;
     if (count > SLOT_C) return;
-    if (count != 0)
-        tile_rank(v, bits, base, [&](uint32_t rank, uint32_t i, float x) {
-            slots[slot_at(tile, rank)] = SlotEntry{i, x};
-        });
-    slot_pad(slots, tile, count);
+    slot_store_tile(slots, tile, count, v, bits, base, stage, ntiles);
 }
 
 template <bool NT>
 __global__ __launch_bounds__(SLOT_FILL_BLOCK) void slot_fill_kernel(
     const float* __restrict__ acc, uint32_t n, const float* __restrict__ d_threshold,
-    uint16_t* __restrict__ counts, SlotEntry* __restrict__ slots, uint32_t ntiles) {
+    uint16_t* __restrict__ counts, SlotEntry* __restrict__ slots, uint32_t ntiles,
+    uint64_t* __restrict__ scan_state, uint32_t scan_words, uint32_t spin_limit) {
+    __shared__ SlotEntry s_stage[SLOT_FILL_BLOCK / WAVE][SLOT_C];
+    slot_clear_scan_state(scan_state, scan_words, spin_limit);
     const uint32_t tile = blockIdx.x * (SLOT_FILL_BLOCK / WAVE) + (threadIdx.x >> 6);
     if (tile >= ntiles) return;
     const float th = *d_threshold;
-    if (th == th) slot_fill_tile<NT>(acc, n, TestFloat{__builtin_fabsf(th)}, counts, slots, tile);
-    else slot_fill_tile<NT>(acc, n, TestKey{magnitude_key(th)}, counts, slots, tile);
+    SlotEntry* stage = s_stage[threadIdx.x >> 6];
+    if (th == th) slot_fill_tile<NT>(acc, n, TestFloat{__builtin_fabsf(th)}, counts, slots, tile, stage, ntiles);
+    else slot_fill_tile<NT>(acc, n, TestKey{magnitude_key(th)}, counts, slots, tile, stage, ntiles);
 }
 
 // ---- first pass that forms the accumulator on the way ----
@@ -151,7 +181,8 @@ __global__ __launch_bounds__(SLOT_FILL_BLOCK) void slot_fill_kernel(
 template <bool ZERO, bool NT, typename Test>
 __device__ __forceinline__ void slot_fill_accumulate_tile(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n, Test test,
-    uint16_t* __restrict__ counts, SlotEntry* __restrict__ slots, uint32_t tile) {
+    uint16_t* __restrict__ counts, SlotEntry* __restrict__ slots, uint32_t tile, SlotEntry* stage,
+    uint32_t ntiles) {
     const int lane = lane_id();
     const uint64_t base = (uint64_t)tile * SLOT_TILE;
     const bool whole = base + SLOT_TILE <= n;
@@ -168,13 +199,7 @@ __device__ __forceinline__ void slot_fill_accumulate_tile(
     const uint32_t bits = tile_test(a, base, n, whole, test);
     const uint32_t count = tile_count(bits);
     if (lane == 0) counts[tile] = (uint16_t)count;
-    if (count <= SLOT_C) {
-        if (count != 0)
-            tile_rank(a, bits, base, [&](uint32_t rank, uint32_t i, float x) {
-                slots[slot_at(tile, rank)] = SlotEntry{i, x};
-            });
-        slot_pad(slots, tile, count);
-    }
+    if (count <= SLOT_C) slot_store_tile(slots, tile, count, a, bits, base, stage, ntiles);
     if (ZERO && count <= SLOT_C) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -205,16 +230,19 @@ template <bool ZERO, bool NT>
 __global__ __launch_bounds__(SLOT_FILL_BLOCK) void slot_fill_accumulate_kernel(
     const float* __restrict__ grad, float* __restrict__ res, float lr, uint32_t n,
     const float* __restrict__ d_threshold, uint16_t* __restrict__ counts,
-    SlotEntry* __restrict__ slots, uint32_t ntiles) {
+    SlotEntry* __restrict__ slots, uint32_t ntiles, uint64_t* __restrict__ scan_state,
+    uint32_t scan_words, uint32_t spin_limit) {
+    __shared__ SlotEntry s_stage[SLOT_FILL_BLOCK / WAVE][SLOT_C];
+    slot_clear_scan_state(scan_state, scan_words, spin_limit);
     const uint32_t tile = blockIdx.x * (SLOT_FILL_BLOCK / WAVE) + (threadIdx.x >> 6);
     if (tile >= ntiles) return;
     const float th = *d_threshold;
     if (th == th)
         slot_fill_accumulate_tile<ZERO, NT>(grad, res, lr, n, TestFloat{__builtin_fabsf(th)}, counts,
-                                            slots, tile);
+                                            slots, tile, s_stage[threadIdx.x >> 6], ntiles);
     else
         slot_fill_accumulate_tile<ZERO, NT>(grad, res, lr, n, TestKey{magnitude_key(th)}, counts,
-                                            slots, tile);
+                                            slots, tile, s_stage[threadIdx.x >> 6], ntiles);
 }
 
 // ---- second pass: the place of every tile ----
@@ -344,60 +372,47 @@ __device__ __forceinline__ void slot_emit_tiles(float* __restrict__ acc, uint32_
             val_out[pos] = __uint_as_float(bits);
             if (AFTER == SLOT_ZERO) acc[i] = 0.0f;
         } else if (AFTER == SLOT_RESTORE) {
-            acc[i] = __uint_as_float(bits);
+            scattered_store(acc + i, __uint_as_float(bits));
         }
     };
-    // ---- tiles with few entries: one lane per tile ----
-    const uint64_t t = (uint64_t)wave_of_launch * WAVE + lane;
-    if (t < ntiles) {                                   // nothing past the last tile
-        const uint32_t c = counts[t];
-        if (c != 0 && c <= SLOT_FEW) {
-            const uint64_t at = place[t];
-            const SlotEntry* from = slots + slot_at(t, 0);
-            SlotEntry e[SLOT_FEW];
-#pragma unroll
-            for (uint32_t j = 0; j < SLOT_FEW; ++j) e[j] = from[j * SLOT_GROUP];   // padded: all written
-#pragma unroll
-            for (uint32_t j = 0; j < SLOT_FEW; ++j)
-                if (j < c) put(at + j, e[j].idx, __float_as_uint(e[j].val));
-        }
-    }
-    // ---- fuller slots: half a wave per slot, one lane per entry, four in flight ----
-    const uint32_t nfuller = hdr->pad[SLOT_FULLER_WORD];
+    // The three kinds are independent of one another, and each is a chain of two or
+    // three loads that wait for the one before (list -> count and place -> slot or
+    // tile).  A wave's first turn at each kind is therefore taken level by level,
+    // all kinds at once, so that the chains overlap; what is left after the first
+    // turn (long lists only) is taken one kind after the other.
+    constexpr uint32_t NONE = 0xffffffffu;
+    constexpr int TURNS = SLOT_C / 32;              // entries sub, sub + 32, ... of a fuller slot
     const uint32_t sub = (uint32_t)lane & 31u;
     const uint32_t half_of_launch = 2u * wave_of_launch + ((uint32_t)lane >> 5);
-    for (uint64_t q0 = 4ull * half_of_launch; q0 < nfuller; q0 += 8ull * waves) {
-        uint32_t tile[4], c[4], at[4];
+    auto fuller_meta = [&](const uint32_t (&tile)[4], uint32_t (&c)[4], uint32_t (&at)[4]) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            tile[u] = q0 + u < nfuller ? list[q0 + u] : 0xffffffffu;
             c[u] = 0;
             at[u] = 0;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (tile[u] != 0xffffffffu) {
+            if (tile[u] != NONE) {
                 c[u] = counts[tile[u]];
                 at[u] = place[tile[u]];
             }
-        SlotEntry e[4];
+        }
+    };
+    auto fuller_load = [&](const uint32_t (&tile)[4], const uint32_t (&c)[4], SlotEntry (&e)[4][TURNS]) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-            if (sub < c[u]) e[u] = slots[slot_at(tile[u], sub)];
+#pragma unroll
+            for (int v = 0; v < TURNS; ++v)
+                if (sub + 32u * v < c[u]) e[u][v] = slots[slot_at(tile[u], sub + 32u * v, ntiles)];
+    };
+    auto fuller_store = [&](const uint32_t (&c)[4], const uint32_t (&at)[4], const SlotEntry (&e)[4][TURNS]) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-            if (sub < c[u]) put((uint64_t)at[u] + sub, e[u].idx, __float_as_uint(e[u].val));
-    }
-    // ---- dense tiles: walked again, a wave each ----
-    const uint32_t ndense = hdr->pad[SLOT_DENSE_WORD];
-    for (uint32_t q = wave_of_launch; q < ndense; q += waves) {
-        const uint64_t tile = list[ntiles - 1 - q];
-        const uint64_t at = place[tile];
+#pragma unroll
+            for (int v = 0; v < TURNS; ++v)
+                if (sub + 32u * v < c[u])
+                    put((uint64_t)at[u] + sub + 32u * v, e[u][v].idx, __float_as_uint(e[u][v].val));
+    };
+    auto dense_finish = [&](uint64_t tile, uint64_t at, const float4 (&v)[4]) {
         const uint64_t base = tile * SLOT_TILE;
-        const bool whole = base + SLOT_TILE <= n;
-        float4 v[4];
-        tile_load<false>(acc, base, n, whole, v);
-        const uint32_t bits = tile_test(v, base, n, whole, test);
+        const uint32_t bits = tile_test(v, base, n, base + SLOT_TILE <= n, test);
         tile_rank(v, bits, base, [&](uint32_t rank, uint32_t i, float x) {
             const uint64_t pos = at + rank;
             if (pos < capacity) {
@@ -406,6 +421,69 @@ __device__ __forceinline__ void slot_emit_tiles(float* __restrict__ acc, uint32_
                 if (DENSE_ZERO) acc[i] = 0.0f;
             }
         });
+    };
+
+    // ---- level 1: counts, places and list items (the lists have a word per tile, so
+    // an item past a list's end is read, and then dropped, rather than waited for)
+    const uint64_t t = (uint64_t)wave_of_launch * WAVE + lane;       // few entries: one lane per tile
+    uint32_t few_c = 0;
+    uint64_t few_at = 0;
+    if (t < ntiles) {                                                // nothing past the last tile
+        few_c = counts[t];
+        few_at = place[t];
+    }
+    const uint64_t q0 = 4ull * half_of_launch;                       // fuller slots: half a wave per slot
+    uint32_t f_tile[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) f_tile[u] = q0 + u < ntiles ? list[q0 + u] : NONE;
+    uint32_t d_tile = wave_of_launch < ntiles ? list[ntiles - 1 - wave_of_launch] : NONE;   // dense: a wave per tile
+    const uint32_t nfuller = hdr->pad[SLOT_FULLER_WORD], ndense = hdr->pad[SLOT_DENSE_WORD];
+    if (few_c > SLOT_FEW) few_c = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (q0 + u >= nfuller) f_tile[u] = NONE;
+    if (wave_of_launch >= ndense) d_tile = NONE;                     // wave-uniform
+
+    // ---- level 2: the few entries, the fuller slots' counts and places, the dense tile
+    SlotEntry few_e[SLOT_FEW];
+    if (few_c != 0) {
+        const SlotEntry* from = slots + slot_at(t, 0, ntiles);
+#pragma unroll
+        for (uint32_t j = 0; j < SLOT_FEW; ++j) few_e[j] = from[j * SLOT_GROUP];   // padded: all written
+    }
+    uint32_t f_c[4], f_at[4];
+    fuller_meta(f_tile, f_c, f_at);
+    float4 d_v[4];
+    uint64_t d_at = 0;
+    if (d_tile != NONE) {
+        d_at = place[d_tile];
+        const uint64_t base = (uint64_t)d_tile * SLOT_TILE;
+        tile_load<false>(acc, base, n, base + SLOT_TILE <= n, d_v);
+    }
+
+    // ---- level 3: the fuller slots' entries; everything else goes out
+    SlotEntry f_e[4][TURNS];
+    fuller_load(f_tile, f_c, f_e);
+#pragma unroll
+    for (uint32_t j = 0; j < SLOT_FEW; ++j)
+        if (j < few_c) put(few_at + j, few_e[j].idx, __float_as_uint(few_e[j].val));
+    if (d_tile != NONE) dense_finish(d_tile, d_at, d_v);
+    fuller_store(f_c, f_at, f_e);
+
+    // ---- what long lists leave for further turns
+    for (uint64_t q = q0 + 8ull * waves; q < nfuller; q += 8ull * waves) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) f_tile[u] = q + u < nfuller ? list[q + u] : NONE;
+        fuller_meta(f_tile, f_c, f_at);
+        fuller_load(f_tile, f_c, f_e);
+        fuller_store(f_c, f_at, f_e);
+    }
+    for (uint64_t q = (uint64_t)wave_of_launch + waves; q < ndense; q += waves) {
+        const uint64_t tile = list[ntiles - 1 - q];
+        const uint64_t at = place[tile];
+        const uint64_t base = tile * SLOT_TILE;
+        tile_load<false>(acc, base, n, base + SLOT_TILE <= n, d_v);
+        dense_finish(tile, at, d_v);
     }
 }
 

@@ -638,7 +638,7 @@ extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual
         hipLaunchKernelGGL(fill, dim3((plan.ntiles + per_wg - 1) / per_wg), dim3(SLOT_FILL_BLOCK), 0,
                            s, d_grad, d_residual_inout, lr, (uint32_t)n, bound,
                            (uint16_t*)(scan_a + plan.counts_at), (SlotEntry*)(scan_a + plan.slots_at),
-                           plan.ntiles);
+                           plan.ntiles, (uint64_t*)nullptr, 0u, 0u);      // refresh_init_kernel cleared it
         timing_after(s);
         const int rc = launch_slot_finish(d_residual_inout, n, bound, plan, scan_a, SLOT_KEEP, false,
                                           cand_idx, cand_val, cand_cap, state->collected, s);

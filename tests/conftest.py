@@ -27,3 +27,14 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(params=["one_kernel", "three_pass"])
+def select_form(request):
+    """Runs a GPU test once with each form of the select calls: the one-kernel form
+    (chained scan inside the streaming kernel) and the three-pass form (per-tile
+    slots), which the library otherwise chooses by the vector's length."""
+    import paper_2201_07598_amd as okt
+    okt.okt_debug_slot_min_n(1 if request.param == "three_pass" else 1 << 40)
+    yield request.param
+    okt.okt_debug_slot_min_n(0)

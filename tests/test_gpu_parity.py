@@ -225,6 +225,7 @@ def check_select(acc, th, capacity):
     return total
 
 
+@pytest.mark.usefixtures("select_form")
 @pytest.mark.parametrize("n", [1, 2, 4095, 4096, 4097, 3 * 4096 + 5, 1_000_003, (1 << 22) + 1])
 def test_select_matches_oracle(n):
     acc = lap(n + 50, n)
@@ -233,6 +234,7 @@ def test_select_matches_oracle(n):
     assert check_select(acc, th, 4 * k) == cnt
 
 
+@pytest.mark.usefixtures("select_form")
 @pytest.mark.parametrize("n", [70_001, 5_000_003])
 def test_threshold_and_select_with_nan_and_inf_elements(n):
     """Not a case the method meets (gradients are finite), but the order of the
@@ -256,6 +258,7 @@ def test_threshold_and_select_with_nan_and_inf_elements(n):
         assert check_select(acc, rth, cnt + 3) == cnt
 
 
+@pytest.mark.usefixtures("select_form")
 def test_select_degenerate_thresholds():
     acc = lap(99, 50_001)
     assert check_select(acc, np.float32(np.inf), 16) == 0
@@ -265,6 +268,7 @@ def test_select_degenerate_thresholds():
     assert check_select(acc, np.float32(0.5), acc.size) == acc.size
 
 
+@pytest.mark.usefixtures("select_form")
 def test_select_truncates_in_index_order():
     acc = lap(98, 300_000)
     total = check_select(acc, np.float32(1e-3), 1000)
@@ -274,6 +278,7 @@ def test_select_truncates_in_index_order():
     check_select(acc, np.float32(1e-3), total - 1)
 
 
+@pytest.mark.usefixtures("select_form")
 def test_select_empty_vector():
     nnz = torch.full((2,), 5, dtype=torch.int64, device=DEV)
     acc = torch.zeros(1, dtype=torch.float32, device=DEV)
@@ -281,6 +286,7 @@ def test_select_empty_vector():
     assert list(u64(nnz)) == [0, 0]
 
 
+@pytest.mark.usefixtures("select_form")
 def test_select_is_deterministic():
     acc = lap(97, 2_000_000)
     a = gpu_select(acc, np.float32(2e-3), 100_000)
@@ -309,6 +315,7 @@ def check_fused(g, e, lr, th, capacity):
     return rtotal
 
 
+@pytest.mark.usefixtures("select_form")
 @pytest.mark.parametrize("n", [0, 1, 3, 1023, 4096, 4097, 70_001, 1_000_003, (1 << 22) + 5])
 def test_accumulate_select_matches_the_two_calls(n):
     g, e = lap(n + 3, n), lap(n + 4, n, 2e-3)
@@ -323,6 +330,7 @@ def test_accumulate_select_matches_the_two_calls(n):
     assert check_fused(g, e, lr, th, 4 * k) == cnt
 
 
+@pytest.mark.usefixtures("select_form")
 def test_accumulate_select_degenerate_and_truncated():
     n = 300_007
     g, e = lap(1, n), lap(2, n, 3e-3)
@@ -352,6 +360,7 @@ def layered(n, seed=5):
     return x
 
 
+@pytest.mark.usefixtures("select_form")
 @pytest.mark.timeout(300)
 def test_calls_captured_in_a_hip_graph_replay_like_eager():
     """The entry points enqueue kernels only (the scan state is cleared by a small
@@ -500,6 +509,7 @@ def test_a_wait_that_gives_up_is_reported():
     assert got["total"] == ref["idx"].size and np.array_equal(got["idx"], ref["idx"])
 
 
+@pytest.mark.usefixtures("select_form")
 def test_two_streams_each_with_its_own_workspace():
     """Calls enqueued on two streams, each with its own workspace and outputs, run
     side by side without a synchronisation between them: the library keeps no
@@ -542,6 +552,7 @@ def test_two_streams_each_with_its_own_workspace():
         assert bits_equal(L["res"].cpu().numpy(), res), j
 
 
+@pytest.mark.usefixtures("select_form")
 def test_select_where_pieces_overflow_their_stash():
     # long enough that a wave's piece (about n / 4096) holds more selected entries
     # than its stash where the selection is dense
@@ -572,6 +583,7 @@ def test_select_where_pieces_overflow_their_stash():
     assert np.array_equal(u32(idx), coo_idx[ridx]) and bits_equal(val.cpu().numpy(), rval)
 
 
+@pytest.mark.usefixtures("select_form")
 @pytest.mark.timeout(300)
 def test_accumulate_select_where_pieces_overflow_their_stash():
     n = 12_000_003
@@ -1069,6 +1081,7 @@ def run_loop(w, iterations, R, fused=False):
 @pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("name,n,iters", [("cfg1", 1_048_576, 1), ("cfg2", 2_000_003, 10),
                                           ("cfg3", 1_500_001, 34), ("cfg4", 4_000_007, 3)])
+@pytest.mark.usefixtures("select_form")
 def test_hot_path_loop_scaled(name, n, iters, fused):
     w = wl.WORKLOADS[name].scaled(n)
     counts, _ = run_loop(w, iters, w.P, fused=fused)

@@ -44,6 +44,7 @@ def selected_matches(idx, val, nnz, ridx, rval, total):
             and bits_equal(val[:ridx.size].cpu().numpy(), rval))
 
 
+@pytest.mark.usefixtures("select_form")
 @pytest.mark.parametrize("seed", range(6))
 def test_random_iterations_of_the_dense_path(seed):
     rng = np.random.default_rng(9000 + seed)
@@ -280,6 +281,7 @@ def test_random_vectors_through_the_sampled_threshold(seed):
             assert int(u64(cnt)[0]) == rcnt, where
 
 
+@pytest.mark.usefixtures("select_form")
 @pytest.mark.timeout(300)
 @pytest.mark.parametrize("seed", range(3))
 def test_random_refresh_iterations_in_one_call(seed):

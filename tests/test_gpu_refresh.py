@@ -12,7 +12,7 @@ import workloads as wl
 from oracle import okt_oracle as orc
 from tests.okt_harness import DEV, bits_equal, to_dev, u32, u64, workspace
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("select_form")]
 
 
 def lap(seed, n, scale=1e-3):
