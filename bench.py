@@ -395,16 +395,17 @@ def headline(args, torch, np, okt, wl, ev, cfg):
     for c, v in summarise(sep_main).items():
         table_main.setdefault(c, v)
     alg = algorithmic_bytes(n, nnz_now, E, U)
-    three_pass = n >= okt.okt_slot_min_n()
     kernels = {}
     for c, v in table.items():
         kernels[c] = {"calls_per_step": calls_per_step[c], "us_per_call": stats(np, v, alg.get(c))}
         if c in table_main:
+            three_pass = is_three_pass(okt, c, n)
             kernels[c]["us_main_kernel"] = stats(np, table_main[c], main_kernel_bytes(c, alg, n, three_pass))
             kernels[c]["kernel"] = main_kernel_name(c, three_pass)
 
     dom_us = float(np.mean(in_region[dominant])) if dominant in in_region else \
         float(np.median(table_main[dominant]))
+    three_pass = is_three_pass(okt, dominant, n)
     dom_bytes = main_kernel_bytes(dominant, alg, n, three_pass)
     achieved = dom_bytes / dom_us * 1e-3
     roofline = {"bound": "hbm", "kernel": main_kernel_name(dominant, three_pass), "call": dominant,
@@ -513,6 +514,13 @@ def main_kernel_bytes(call, alg, n, three_pass=False):
     return alg.get(call)
 
 
+def is_three_pass(okt, call, n):
+    """Whether the library gives this call, at this length, its three-pass form."""
+    if call in ("accumulate_select", "accumulate_topk_select"):
+        return n >= okt.okt_slot_min_n(True)
+    return call in ("select", "select_copy") and n >= okt.okt_slot_min_n(False)
+
+
 def main_kernel_name(call, three_pass=False):
     if three_pass and call in THREE_PASS_KERNEL:
         return THREE_PASS_KERNEL[call]
@@ -607,9 +615,11 @@ def measure_calls(args, torch, np, okt, wl, ev, cfg):
            "state": "zero residual" if not cfg.burn_in else
            f"steady-state residual ({cfg.burn_in} untimed iterations of exact top-k on device noise)",
            "kernels": {}}
-    three_pass = n >= okt.okt_slot_min_n()
-    out["select_form"] = "three passes (per-tile slots)" if three_pass else "one kernel (chained scan)"
+    forms = {True: "three passes (per-tile slots)", False: "one kernel (chained scan)"}
+    out["select_form"] = {"select": forms[is_three_pass(okt, "select", n)],
+                          "accumulating calls": forms[is_three_pass(okt, "accumulate_select", n)]}
     for name, (call, restore, nbytes) in calls.items():
+        three_pass = is_three_pass(okt, name, n)
         whole, main = time_over_slots(torch, ev, call, nslots, restore, reps)
         kbytes = main_kernel_bytes(name, {name: nbytes}, n, three_pass)
         if name == "threshold_full_vector":

@@ -77,14 +77,18 @@ void okt_debug_spin_limit(uint32_t polls);
 /*
  * Test hook: the shortest vector for which the select calls take their
  * three-pass form (per-tile slots in the workspace; see okt_threshold_select),
- * for every call made after this one, process-wide (0 = the built-in length,
- * 2^20 elements).  Both forms give the same output; with a length of 1 small
- * test vectors exercise the three-pass form.
+ * for every call made after this one, process-wide (0 = the built-in lengths).
+ * Both forms give the same output; with a length of 1 small test vectors
+ * exercise the three-pass form.
  */
 void okt_debug_slot_min_n(uint64_t n);
 
-/* The length in force: vectors at least this long take the three-pass form. */
-uint64_t okt_slot_min_n(void);
+/*
+ * The length in force: vectors at least this long take the three-pass form, in
+ * the plain selects (accumulating = 0) or in the calls that form the accumulator
+ * on the way (okt_accumulate_select, okt_accumulate_topk_select; nonzero).
+ */
+uint64_t okt_slot_min_n(int accumulating);
 
 /*
  * Measurement hook.  The next call this thread makes records `start_event` right
@@ -141,7 +145,9 @@ int okt_version(void);
 /*
  * Bytes of workspace that suffice for every call below on vectors of at most
  * n_max elements, reductions over regions at most n_max wide and at most P_max
- * contributions.  Pure host arithmetic.
+ * contributions: about 2 bytes per element of n_max (candidates of the exact
+ * threshold with their indices, and the per-tile slots of the three-pass
+ * selects), plus the reduce's slice table.  Pure host arithmetic.
  */
 size_t okt_workspace_bytes(uint64_t n_max, uint32_t P_max);
 
@@ -191,6 +197,15 @@ int okt_topk_threshold_exact(const float* d_acc, uint64_t n, uint64_t k,
  *                emitted and zeroed; the others stay in the residual.
  *   d_nnz_out    out  uint64[2]  {emitted = min(|S|, capacity), |S|}
  * A single pass over acc.  n = 0 gives {0, 0}.  n must be below 2^32.
+ * Workspace: okt_workspace_bytes(n, 0).  Two forms give the same output.  One
+ * kernel that places its entries through a scan across its workgroups needs
+ * only some KiB of it (a descriptor per workgroup) and is what a short vector,
+ * or a call with less than the full workspace, gets.  For a long vector (okt_slot_min_n and up) with the full workspace the
+ * call makes three passes: a streaming one with no scan in it, which sets what
+ * every 1024 elements select aside in the workspace, a scan over the counts, and
+ * a short one that moves the entries to their places; only the first touches
+ * the vector as a whole.  okt_threshold_select_copy, okt_accumulate_select and
+ * okt_accumulate_topk_select have the same two forms.
  */
 int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshold,
                          uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,

@@ -23,7 +23,7 @@ SIGNATURES = {
     "okt_time_next_kernel": (None, [c_vp, c_vp]),
     "okt_debug_spin_limit": (None, [c_u32]),
     "okt_debug_slot_min_n": (None, [c_u64]),
-    "okt_slot_min_n": (c_u64, []),
+    "okt_slot_min_n": (c_u64, [c_int]),
     "okt_version": (c_int, []),
     "okt_stream_copy": (c_int, [c_vp, c_vp, c_u64, c_vp]),
     "okt_stream_sum": (c_int, [c_vp, c_u64, c_vp, c_vp]),
@@ -116,9 +116,10 @@ def okt_debug_slot_min_n(n: int) -> None:
     load_library().okt_debug_slot_min_n(int(n))
 
 
-def okt_slot_min_n() -> int:
-    """Vectors at least this long take the three-pass select."""
-    return load_library().okt_slot_min_n()
+def okt_slot_min_n(accumulating: bool = False) -> int:
+    """Vectors at least this long take the three-pass form (plain selects, or the
+    calls that form the accumulator on the way)."""
+    return load_library().okt_slot_min_n(1 if accumulating else 0)
 
 
 def okt_version() -> int:

@@ -49,14 +49,14 @@ static int dense_select_args(const float* d_acc, uint64_t n, const float* d_thre
     return OKT_OK;
 }
 
-// Shortest vector that takes the slot path (okt_debug_slot_min_n; 0 = SLOT_MIN_N).
+// Shortest vector that takes the slot path (okt_debug_slot_min_n; 0 = built in).
 static std::atomic<uint64_t> g_slot_min_n{0};
-uint64_t slot_min_n() {
+uint64_t slot_min_n(bool accumulating) {
     const uint64_t set = g_slot_min_n.load(std::memory_order_relaxed);
-    return set ? set : SLOT_MIN_N;
+    return set ? set : accumulating ? SLOT_MIN_N_ACCUMULATE : SLOT_MIN_N_SELECT;
 }
-static bool slots_apply(uint64_t n, size_t ws_bytes) {
-    return n >= slot_min_n() && ws_bytes >= slot_ws_bytes(n);
+static bool slots_apply(uint64_t n, size_t ws_bytes, bool accumulating) {
+    return n >= slot_min_n(accumulating) && ws_bytes >= slot_ws_bytes(n);
 }
 
 int launch_slot_finish(float* d_acc, uint64_t n, const float* d_threshold, const SlotPlan& plan,
@@ -102,7 +102,7 @@ static int launch_dense_select(float* d_acc, uint64_t n, const float* d_threshol
     }
     const SelectShape shape = select_shape(n, device_cus());
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(n)) return OKT_ERR_WORKSPACE;
-    if (slots_apply(n, ws_bytes)) {
+    if (slots_apply(n, ws_bytes, false)) {
         const SlotPlan plan = slot_plan(n, device_cus());
         char* ws = (char*)d_ws;
         timing_before(s);
@@ -138,7 +138,7 @@ extern "C" void okt_debug_slot_min_n(uint64_t n) {
     okt::g_slot_min_n.store(n, std::memory_order_relaxed);
 }
 
-extern "C" uint64_t okt_slot_min_n(void) { return okt::slot_min_n(); }
+extern "C" uint64_t okt_slot_min_n(int accumulating) { return okt::slot_min_n(accumulating != 0); }
 
 extern "C" int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshold,
                                     uint32_t* d_idx_out, float* d_val_out, uint64_t capacity,
@@ -226,7 +226,7 @@ extern "C" int okt_accumulate_select(const float* d_grad, float* d_residual_inou
         return OKT_ERR_INVALID_ARG;
     const SelectShape shape = select_shape(n, device_cus());
     if (!d_ws || !aligned(d_ws, 256) || ws_bytes < select_ws_bytes(n)) return OKT_ERR_WORKSPACE;
-    if (slots_apply(n, ws_bytes)) {
+    if (slots_apply(n, ws_bytes, true)) {
         const SlotPlan plan = slot_plan(n, device_cus());
         char* ws = (char*)d_ws;
         timing_before(s);

@@ -103,9 +103,14 @@ inline SlotPlan slot_plan(uint64_t n, uint32_t cus) {
     return p;
 }
 inline size_t slot_ws_bytes(uint64_t n) { return slot_plan(n, 256).bytes; }
-// Shorter vectors take the one-kernel select: three launches cost more than they
-// save there.
-constexpr uint64_t SLOT_MIN_N = 1u << 26;
+// Shorter vectors take the one-kernel form: the two extra launches and the scan's
+// fixed few microseconds cost more than the leaner streaming pass saves there.
+// Measured crossover: the calls that form the accumulator on the way (12 bytes an
+// element: the saving is three times the select's) gain from about 40 M elements
+// on, the plain selects from about 100 M, where the vector no longer fits the
+// last-level cache.
+constexpr uint64_t SLOT_MIN_N_SELECT = 96u << 20;
+constexpr uint64_t SLOT_MIN_N_ACCUMULATE = 1u << 25;
 
 // ---- index intersection and residual restore ----
 constexpr int RST_BLOCK = 256;

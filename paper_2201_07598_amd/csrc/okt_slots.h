@@ -504,9 +504,10 @@ __global__ __launch_bounds__(SLOT_EMIT_BLOCK) void slot_emit_kernel(
 }
 
 // ---- host side (okt_select.hip) ----
-// Shortest vector that takes the three-pass form (SLOT_MIN_N unless the test hook
-// has set another).
-uint64_t slot_min_n();
+// Shortest vector that takes the three-pass form, for the plain selects or for the
+// calls that form the accumulator on the way (the built-in lengths unless the test
+// hook has set another).
+uint64_t slot_min_n(bool accumulating);
 // Second and third pass of a select through slots; the first pass has filled the
 // counts and the slots of the workspace `ws` (laid out by `plan`, scan state
 // cleared).  `d_threshold`: what the first pass tested against.  `after`: what the

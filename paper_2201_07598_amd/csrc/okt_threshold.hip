@@ -578,7 +578,7 @@ extern "C" int okt_accumulate_topk_select(const float* d_grad, float* d_residual
     // else through the chained scan of the one-kernel select.
     const SlotPlan plan = slot_plan(n, device_cus());
     const size_t slot_bytes = round_up_256(plan.bytes);
-    bool slots = n >= slot_min_n() && ws_bytes > threshold_ws_min_bytes() + scan_bytes + slot_bytes;
+    bool slots = n >= slot_min_n(true) && ws_bytes > threshold_ws_min_bytes() + scan_bytes + slot_bytes;
     size_t fixed = threshold_ws_min_bytes() + scan_bytes + (slots ? slot_bytes : scan_bytes);
     uint64_t cand_cap = ws_bytes > fixed ? ((ws_bytes - fixed) / 8) & ~(uint64_t)63 : 0;
     if (slots && cand_cap < n / 16) {
