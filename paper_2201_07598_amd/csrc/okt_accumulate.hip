@@ -3,7 +3,7 @@
 // HBM-bound streaming kernel: 8 B read + 4 B written per element.  Each thread
 // keeps ACC_ITERS 16-byte loads of both inputs in flight before the first use;
 // a wave reads 1 KiB contiguous per load instruction; vectors far longer than the
-// last-level cache are read with the non-temporal hint.  The product and the sum
+// last-level cache are read and written with the non-temporal hint.  The product and the sum
 // are rounded separately (no fused multiply-add), so the result is the same as
 // two fp32 tensor operations.
 #include "okt_device.h"
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(ACC_BLOCK) void accumulate_kernel(
             r.y = acc_one(e[it].y, g[it].y, lr);
             r.z = acc_one(e[it].z, g[it].z, lr);
             r.w = acc_one(e[it].w, g[it].w, lr);
-            e4[i] = r;
+            store_quad<NT>(e4 + i, r);
         }
         return;
     }

@@ -4,6 +4,7 @@
 // step that reads and writes (accumulate, 8 B in + 4 B out per element), the sum
 // for a step that only reads (select at low density, the threshold passes).
 #include "okt_device.h"
+#include "okt_sizes.h"
 
 namespace okt {
 
@@ -12,6 +13,9 @@ constexpr int CEIL_ITERS = 4;
 constexpr int CEIL_TILE4 = CEIL_BLOCK * CEIL_ITERS;       // float4 per workgroup and trip
 constexpr uint32_t CEIL_SUM_GROUPS = OKT_STREAM_SUM_PARTIALS;
 
+// Like the hot path's kernels, the copy reads and writes a vector far larger than
+// the last-level cache with the non-temporal hint (NT, set by the host).
+template <bool NT>
 __global__ __launch_bounds__(CEIL_BLOCK) void stream_copy_kernel(
     const float* __restrict__ src, float* __restrict__ dst, uint32_t n) {
     const uint32_t n4 = n >> 2;
@@ -21,9 +25,11 @@ __global__ __launch_bounds__(CEIL_BLOCK) void stream_copy_kernel(
     if (base4 + CEIL_TILE4 <= n4) {
         float4 v[CEIL_ITERS];
 #pragma unroll
-        for (int it = 0; it < CEIL_ITERS; ++it) v[it] = s4[base4 + it * CEIL_BLOCK + threadIdx.x];
+        for (int it = 0; it < CEIL_ITERS; ++it)
+            v[it] = load_quad<NT>(s4 + base4 + it * CEIL_BLOCK + threadIdx.x);
 #pragma unroll
-        for (int it = 0; it < CEIL_ITERS; ++it) d4[base4 + it * CEIL_BLOCK + threadIdx.x] = v[it];
+        for (int it = 0; it < CEIL_ITERS; ++it)
+            store_quad<NT>(d4 + base4 + it * CEIL_BLOCK + threadIdx.x, v[it]);
         return;
     }
     for (int it = 0; it < CEIL_ITERS; ++it) {
@@ -34,17 +40,9 @@ __global__ __launch_bounds__(CEIL_BLOCK) void stream_copy_kernel(
     if (threadIdx.x < 4 && tail < n) dst[tail] = src[tail];
 }
 
-// A 16-byte load with the non-temporal hint: 5 % faster for this kernel on data
-// that is in no cache.  The hot path does not use it: on the loads of the fused
-// accumulate+select and of the select walks it gains 4-5 % on cold data and loses
-// as much in a training step, where the residual an iteration writes is still in
-// the last-level cache when the next one reads it; on dense stores it always
-// loses (a copy 10 % slower).
-typedef float v4f __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 load_once(const float4* p) {
-    const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
-    return make_float4(v.x, v.y, v.z, v.w);
-}
+// The read-only kernel always loads with the non-temporal hint (5 % faster on
+// data that is in no cache, which is how it is timed).
+__device__ __forceinline__ float4 load_once(const float4* p) { return load_quad<true>(p); }
 
 // Every workgroup strides over the vector, CEIL_ITERS 16-byte loads in flight per
 // thread, and leaves one partial sum; nothing else is written.
@@ -170,8 +168,9 @@ extern "C" int okt_stream_copy(const float* d_src, float* d_dst, uint64_t n, voi
     if (!aligned(d_src, 16) || !aligned(d_dst, 16)) return OKT_ERR_INVALID_ARG;
     const uint64_t blocks = (n >> 2) / CEIL_TILE4 + 1;     // the last one owns the ragged end
     timing_before((hipStream_t)stream);
-    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(CEIL_BLOCK), 0,
-                       (hipStream_t)stream, d_src, d_dst, (uint32_t)n);
+    auto* kernel = stream_past_cache(n) ? stream_copy_kernel<true> : stream_copy_kernel<false>;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(CEIL_BLOCK), 0, (hipStream_t)stream,
+                       d_src, d_dst, (uint32_t)n);
     timing_after((hipStream_t)stream);
     return launch_status();
 }

@@ -429,8 +429,8 @@ __device__ __forceinline__ void accumulate_select_body(
         float4* edst = reinterpret_cast<float4*>(res + r) + lane;
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            edst[u * WAVE] = round((uint32_t)r + 256u * u, a[u], test(a[u].x), test(a[u].y),
-                                   test(a[u].z), test(a[u].w));
+            store_quad<NT>(edst + u * WAVE, round((uint32_t)r + 256u * u, a[u], test(a[u].x),
+                                                  test(a[u].y), test(a[u].z), test(a[u].w)));
     }
     for (; r + 256 <= end; r += 256) {               // whole rounds short of a batch
         const float4 gq = load_quad<NT>(reinterpret_cast<const float4*>(grad + r) + lane);

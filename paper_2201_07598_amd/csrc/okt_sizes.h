@@ -52,10 +52,12 @@ inline size_t select_ws_bytes(uint64_t n) {
     return 64 + 8 * (size_t)(t + (t + 63) / 64);
 }
 
-// Vectors far longer than the 256 MB last-level cache are read with the
-// non-temporal hint (nothing of them is found cached again); shorter ones are not:
-// what one iteration writes the next one still finds there.
-inline bool stream_past_cache(uint64_t n) { return n >= (96u << 20); }      // 384 MB of fp32 and up
+// Vectors longer than the 256 MB last-level cache are read, and where a kernel
+// rewrites them densely written, with the non-temporal hint: nothing of them is
+// found cached again, and what goes around the cache pushes nothing out.  Shorter
+// ones are not: what one kernel writes the next still finds there (the select
+// that follows an accumulate, the zeros that follow a refresh iteration's pass).
+inline bool stream_past_cache(uint64_t n) { return n >= (64u << 20); }      // 256 MiB of fp32 and up
 
 // ---- the same through per-tile slots ----
 // With a workspace that has room for them, the streaming pass of the selects

@@ -213,7 +213,7 @@ __device__ __forceinline__ void slot_fill_accumulate_tile(
     if (whole) {
         float4* p = reinterpret_cast<float4*>(res + base) + lane;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) p[u * WAVE] = a[u];
+        for (int u = 0; u < 4; ++u) store_quad<NT>(p + u * WAVE, a[u]);
     } else {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
