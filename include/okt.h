@@ -214,8 +214,10 @@ int okt_threshold_select(float* d_acc_inout, uint64_t n, const float* d_threshol
 /*
  * okt_threshold_select for callers that cannot allocate or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid
- * hipMalloc.  Same arguments without d_ws / ws_bytes, same results bit for bit,
- * same launches.  The scan state lives in an array of
+ * hipMalloc.  Same arguments without d_ws / ws_bytes, same results bit for bit;
+ * always the one-kernel form of okt_threshold_select (a fill kernel that clears
+ * the scan state, then the select kernel), whatever the length.  The scan state
+ * lives in an array of
  * OKT_SELECT_NOALLOC_SCRATCH_BYTES of device memory that is part of the library
  * (every GPU the library runs on holds its own copy until the process ends);
  * the call allocates and frees nothing.

@@ -189,8 +189,9 @@ extern "C" int okt_threshold_select_noalloc(float* d_acc_inout, uint64_t n,
         const int rc = okt::static_scratch(&ws);
         if (rc != OKT_OK) return rc;
     }
-    // the same launches as okt_threshold_select: a fill kernel that clears the scan
-    // state (the array keeps what the last call left), then the select kernel
+    // the launches of okt_threshold_select's one-kernel form (the array is too small
+    // for slots at any length that would take the other): a fill kernel that clears
+    // the scan state (the array keeps what the last call left), then the select kernel
     return okt::launch_dense_select<okt::DenseSource>(d_acc_inout, n, d_threshold, d_idx_out,
                                                       d_val_out, capacity, d_nnz_out, ws,
                                                       sizeof(scratch), (hipStream_t)stream);
