@@ -71,23 +71,6 @@ __device__ __forceinline__ void store_quad(float4* p, const float4& v) {
     }
 }
 
-// One element of a long vector overwritten on its own, its line most likely not
-// in the cache.  The L2 takes a 4-byte store into a line it does not hold as a
-// partial line, and partial lines go out to memory as read-modify-writes, whose
-// cost lands on whatever streams next: some 330,000 such zeros slowed the 700 us
-// streaming kernel that followed by 60 us.  With the element loaded first the
-// line is there in full when the store arrives and leaves as an ordinary line
-// write, at half that cost.  (The value is not needed; the empty asm keeps the
-// load.  A non-temporal load does not help: it leaves no line behind.)  The load
-// is paid by the kernel that stores, the saving goes to the one after it: used
-// where the sum of the two was measured to gain (the zeros of a refresh
-// iteration's final select), not in the plain selects, where it came out even.
-__device__ __forceinline__ void scattered_store(float* p, float v) {
-    const float old = *p;
-    asm volatile("" ::"v"(old));
-    *p = v;
-}
-
 // ---------------------------------------------------------------------------
 // Chained scan across workgroups (decoupled look-back), two levels deep.
 //

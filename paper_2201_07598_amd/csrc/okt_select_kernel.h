@@ -212,8 +212,8 @@ struct CandidateSource {
     __device__ __forceinline__ uint32_t out_index(uint32_t i) const { return idx_in ? idx_in[i] : i; }
     // `walked` is the array the walk runs over, `i` the position in it, `o` the output index
     __device__ __forceinline__ void stash_emit(float* walked, uint32_t i, uint32_t o) const {
-        if (idx_in) scattered_store(res + o, 0.0f);
-        else scattered_store(walked + i, 0.0f);
+        if (idx_in) res[o] = 0.0f;
+        else walked[i] = 0.0f;
     }
     __device__ __forceinline__ void walk_emit(float* walked, uint32_t i, uint32_t o) const {
         stash_emit(walked, i, o);
@@ -274,7 +274,7 @@ __device__ __forceinline__ void select_finish(
             val_out[pos] = e.val;
             source.stash_emit(acc, e.idx, o);
         } else if (Source::restore) {
-            scattered_store(acc + e.idx, e.val);   // output full: the entry stays in the residual
+            acc[e.idx] = e.val;             // output full: the entry stays in the residual
         }
     }
     if (!all_stashed) {

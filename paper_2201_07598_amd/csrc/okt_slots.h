@@ -372,7 +372,7 @@ __device__ __forceinline__ void slot_emit_tiles(float* __restrict__ acc, uint32_
             val_out[pos] = __uint_as_float(bits);
             if (AFTER == SLOT_ZERO) acc[i] = 0.0f;
         } else if (AFTER == SLOT_RESTORE) {
-            scattered_store(acc + i, __uint_as_float(bits));
+            acc[i] = __uint_as_float(bits);
         }
     };
     // The three kinds are independent of one another, and each is a chain of two or
