@@ -4,9 +4,9 @@
 //
 // The vector is cut into tiles of SLOT_TILE elements, one per wave.  The first
 // pass is a plain streaming kernel of many small workgroups, with no ticket, no
-// wait, no LDS: a wave loads its tile with four 16-byte loads per lane, ranks
-// the selected elements with ballots, and writes them into the tile's slot
-// (SLOT_C entries of workspace) and their number into counts[tile].  The second
+// wait, no barrier, no loop: a wave loads its tile with four 16-byte loads per
+// lane, ranks the selected elements with ballots, and writes them into the tile's
+// slot (SLOT_C entries of workspace) and their number into counts[tile].  The second
 // pass reads the counts only: a chained scan over them gives every tile its
 // place in the output.  The third pass, again of many small workgroups, copies
 // the entries of the slots there in index order; a tile that selected more than
@@ -116,9 +116,10 @@ __device__ __forceinline__ uint32_t tile_count(uint32_t bits) {
 
 // The first pass's stores for a tile that selected `count` <= SLOT_C entries.  The
 // wave ranks its entries into `stage` (its own SLOT_C entries of LDS) and writes
-// them out with one store instruction per 64 entries, zeros up to SLOT_FEW: a
-// store per round that selected something would double the store instructions of
-// the pass, and those, not the bytes, are what it pays for.
+// them out, zeros up to SLOT_FEW included, with one store instruction per 64
+// entries, so that its share of the group's first line goes out at once.  (A
+// store per round that selected something, and one more for the zeros, measured
+// the same: the pass pays for the lines it dirties, not for store instructions.)
 __device__ __forceinline__ void slot_store_tile(SlotEntry* __restrict__ slots, uint64_t tile,
                                                 uint32_t count, const float4 (&v)[4], uint32_t bits,
                                                 uint64_t base, SlotEntry* stage, uint32_t ntiles) {
