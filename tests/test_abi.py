@@ -177,3 +177,20 @@ def test_index_searches_match_std_lower_bound(tmp_path):
     out = subprocess.run([str(exe)], capture_output=True, text=True)
     assert out.returncode == 0, out.stdout
     assert "0 disagreements" in out.stdout
+
+
+def test_workspace_plans_hold_on_any_device(tmp_path):
+    """The workspace layouts are host arithmetic (okt_sizes.h): for lengths up to
+    2^32 - 1 and devices of 1 to 1024 compute units the parts of the three-pass
+    select's workspace lie in order without overlap, cover every tile, and fit the
+    size a caller is told; both select forms' launches cover the vector."""
+    gxx = shutil.which("g++")
+    if gxx is None:
+        pytest.skip("no g++")
+    exe = tmp_path / "sizes_check"
+    subprocess.run([gxx, "-O2", "-std=c++17", "-Wall", "-Werror", "-I",
+                    os.path.join(ROOT, "paper_2201_07598_amd", "csrc"),
+                    os.path.join(ROOT, "tests", "cabi", "sizes_check.cpp"), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout
+    assert "0 violations" in out.stdout
