@@ -401,14 +401,14 @@ def headline(args, torch, np, okt, wl, ev, cfg):
         if c in table_main:
             three_pass = is_three_pass(okt, c, n)
             kernels[c]["us_main_kernel"] = stats(np, table_main[c], main_kernel_bytes(c, alg, n, three_pass))
-            kernels[c]["kernel"] = main_kernel_name(c, three_pass)
+            kernels[c]["kernel"] = main_kernel_name(c, three_pass, n)
 
     dom_us = float(np.mean(in_region[dominant])) if dominant in in_region else \
         float(np.median(table_main[dominant]))
     three_pass = is_three_pass(okt, dominant, n)
     dom_bytes = main_kernel_bytes(dominant, alg, n, three_pass)
     achieved = dom_bytes / dom_us * 1e-3
-    roofline = {"bound": "hbm", "kernel": main_kernel_name(dominant, three_pass), "call": dominant,
+    roofline = {"bound": "hbm", "kernel": main_kernel_name(dominant, three_pass, n), "call": dominant,
                 "timed": "events recorded by the library right before and after the launch of the "
                          "call's main kernel, one launch per step inside the timed region",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -473,10 +473,13 @@ def headline(args, torch, np, okt, wl, ev, cfg):
     return out, host_contrib0, (lo, hi), iters
 
 
-# the first pass of the selects of a long vector (the library's three-pass form)
-THREE_PASS_KERNEL = {"select": "slot_fill_kernel", "select_copy": "slot_fill_kernel",
-                     "accumulate_select": "slot_fill_accumulate_kernel<zeroing>",
-                     "accumulate_topk_select": "slot_fill_accumulate_kernel<candidates>"}
+# the first pass of the selects of a long vector (the library's three-pass form), by
+# the names a kernel trace shows: the last template argument says whether the
+# vector is read and written with the non-temporal hint (64 Mi elements and up)
+THREE_PASS_KERNEL = {"select": "slot_fill_kernel<{nt}>", "select_copy": "slot_fill_kernel<{nt}>",
+                     "accumulate_select": "slot_fill_accumulate_kernel<true, {nt}>",
+                     "accumulate_topk_select": "slot_fill_accumulate_kernel<false, {nt}>"}
+NON_TEMPORAL_FROM = 64 << 20
 
 # the kernel that moves the data in each call
 MAIN_KERNEL = {"accumulate": "accumulate_kernel", "threshold": "collect_kernel",
@@ -521,9 +524,9 @@ def is_three_pass(okt, call, n):
     return call in ("select", "select_copy") and n >= okt.okt_slot_min_n(False)
 
 
-def main_kernel_name(call, three_pass=False):
+def main_kernel_name(call, three_pass=False, n=0):
     if three_pass and call in THREE_PASS_KERNEL:
-        return THREE_PASS_KERNEL[call]
+        return THREE_PASS_KERNEL[call].format(nt="true" if n >= NON_TEMPORAL_FROM else "false")
     return MAIN_KERNEL.get(call, call)
 
 
@@ -624,7 +627,7 @@ def measure_calls(args, torch, np, okt, wl, ev, cfg):
         kbytes = main_kernel_bytes(name, {name: nbytes}, n, three_pass)
         if name == "threshold_full_vector":
             main = []                      # three equal passes: the library brackets none of them
-        out["kernels"][name] = {"kernel": main_kernel_name(name, three_pass),
+        out["kernels"][name] = {"kernel": main_kernel_name(name, three_pass, n),
                                 "us_per_call": stats(np, whole, nbytes),
                                 "us_main_kernel": stats(np, main, kbytes)}
         kus = float(np.median(main)) if len(main) else float(np.median(whole))
