@@ -57,7 +57,8 @@ inline size_t select_ws_bytes(uint64_t n) {
 // found cached again, and what goes around the cache pushes nothing out.  Shorter
 // ones are not: what one kernel writes the next still finds there (the select
 // that follows an accumulate, the zeros that follow a refresh iteration's pass).
-inline bool stream_past_cache(uint64_t n) { return n >= (64u << 20); }      // 256 MiB of fp32 and up
+constexpr uint64_t STREAM_PAST_CACHE_N = 64u << 20;                          // 256 MiB of fp32 and up
+inline bool stream_past_cache(uint64_t n) { return n >= STREAM_PAST_CACHE_N; }
 
 // ---- the same through per-tile slots ----
 // With a workspace that has room for them, the streaming pass of the selects

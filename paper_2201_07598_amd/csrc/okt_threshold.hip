@@ -164,10 +164,22 @@ __global__ __launch_bounds__(HIST_BLOCK) void radix_hist_kernel(
     const uint4* src4 = reinterpret_cast<const uint4*>(src);
     const uint32_t stride = gridDim.x * (uint32_t)HIST_STEP4;
     // m4 < 2^30 and stride <= 2^21, so base4 never wraps
+    // a pass over the whole of a vector longer than the last-level cache finds nothing
+    // of it there (wave-uniform choice)
+    const bool around_cache = !use_cand && m64 >= STREAM_PAST_CACHE_N;
     for (; base4 + HIST_STEP4 <= m4; base4 += stride) {
         uint4 v[HIST_ITERS];
 #pragma unroll
-        for (int it = 0; it < HIST_ITERS; ++it) v[it] = src4[base4 + it * HIST_BLOCK + threadIdx.x];
+        for (int it = 0; it < HIST_ITERS; ++it) {
+            const uint4* at = src4 + base4 + it * HIST_BLOCK + threadIdx.x;
+            if (around_cache) {
+                typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+                const v4u q = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(at));
+                v[it] = make_uint4(q.x, q.y, q.z, q.w);
+            } else {
+                v[it] = *at;
+            }
+        }
 #pragma unroll
         for (int it = 0; it < HIST_ITERS; ++it) {
             take(v[it].x); take(v[it].y); take(v[it].z); take(v[it].w);
